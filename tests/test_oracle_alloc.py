@@ -1,0 +1,122 @@
+"""Pins for the allocation oracle (exhaustive search over the paper's Sec. III-B model)."""
+import os
+
+import pytest
+
+import workloads as wl
+from oracle import alloc as oa
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+CFG = [15, 30, 45, 60]
+
+
+def worked_problem(mode):
+    a = wl.Worker([1, 1], [[100, 60, 50, 45], [80, 70, 65, 64]])
+    b = wl.Worker([1], [[200, 110, 80, 60]])
+    return wl.AllocProblem(60, CFG, [a, b], 1, mode)
+
+
+def read_gold():
+    ev, best = [], []
+    for line in open(os.path.join(GOLD, "alloc_worked_example.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        mode = {"EXCESS": oa.OVERLAP_EXCESS, "LITERAL": oa.OVERLAP_LITERAL}[t[1]]
+        (ev if t[0] == "eval" else best).append((mode, [int(v) for v in t[2:]]))
+    return ev, best
+
+
+def test_hand_worked_example_evaluations():
+    ev, _ = read_gold()
+    assert len(ev) >= 10
+    for mode, (ca0, ca1, cb, _sumb, s_d, num) in ev:
+        p = worked_problem(mode)
+        r = oa.evaluate(p, [[CFG.index(ca0), CFG.index(ca1)], [CFG.index(cb)]])
+        assert r is not None and r[0] == num and r[1] == s_d
+
+
+def test_hand_worked_example_optimum_and_tie_break():
+    _, best = read_gold()
+    for mode, (i0, i1, i2, num, s0, s1) in best:
+        assign, obj, sw = oa.solve_exhaustive(worked_problem(mode))
+        assert assign == [[i0, i1], [i2]] and obj == num and sw == [s0, s1]
+
+
+def test_calibration_two_identical_kernels_take_twice_as_long():
+    # Sec. III-B: two identical kernels sharing the same CUs both took twice as long -> alpha = 1.
+    beta = 1000
+    p = wl.AllocProblem(60, [60], [wl.Worker([1], [[beta]]), wl.Worker([1], [[beta]])], 0, oa.OVERLAP_EXCESS)
+    _, num, _ = oa.solve_exhaustive(p)
+    assert num == (2 * beta * 2) * 60          # J = 2*beta*(1+1), scaled by T*D = 60
+    # a lone worker on the whole GPU is not slowed down under EXCESS ...
+    solo = wl.AllocProblem(60, [60], [wl.Worker([1], [[beta]])], 0, oa.OVERLAP_EXCESS)
+    assert oa.solve_exhaustive(solo)[1] == beta * 60
+    # ... but is (alpha = 1) under the formula as printed, which is why EXCESS is the default reading
+    solo.overlap_mode = oa.OVERLAP_LITERAL
+    assert oa.solve_exhaustive(solo)[1] == 2 * beta * 60
+
+
+def test_switch_count_identity_onehot_form():
+    import random
+    r = random.Random(5)
+    for _ in range(200):
+        n, k = r.randint(1, 12), r.randint(1, 5)
+        v = [r.randrange(k) for _ in range(n)]
+        assert oa.switch_total(v) == oa.switch_total_onehot(v, k)
+    assert oa.switch_total([0, 0, 1, 1, 0]) == 2 and oa.switch_total([3]) == 0
+
+
+def test_single_worker_takes_per_unit_argmin_when_budget_allows():
+    for seed in range(20):
+        p = wl.random_problem(seed, 1, [4], [32, 64, 128, 192, 256], 256, switch_max=3, shape="random")
+        assign, num, sw = oa.solve_exhaustive(p)
+        w = p.workers[0]
+        for g, c in enumerate(assign[0]):
+            assert w.beta[g][c] == min(w.beta[g])
+        n = sum(w.n_kernels)
+        assert num == sum(min(r) for r in w.beta) * 256 * n      # alpha = 0, scaled by T*D
+
+
+def test_flat_tables_choose_fewest_cus():
+    p = wl.random_problem(3, 2, [3, 2], [32, 64, 128], 128, switch_max=2, shape="flat")
+    assign, _, sw = oa.solve_exhaustive(p)
+    assert assign == [[0, 0, 0], [0, 0]] and sw == [0, 0]
+
+
+def test_zero_budget_means_one_config_per_worker():
+    for seed in range(10):
+        p = wl.random_problem(100 + seed, 2, [3, 3], [15, 30, 45, 60], 60, switch_max=0)
+        assign, num, sw = oa.solve_exhaustive(p)
+        assert sw == [0, 0] and all(len(set(a)) == 1 for a in assign)
+        # |C|^W candidates evaluated directly
+        cands = [oa.evaluate(p, [[a] * 3, [b] * 3])[0] for a in range(4) for b in range(4)]
+        assert num == min(cands)
+
+
+def test_objective_monotone_in_switch_budget_and_table_i_bound():
+    for seed in range(10):
+        prev = None
+        for sm in range(0, 4):
+            p = wl.random_problem(200 + seed, 2, [4, 2], [15, 30, 45, 60], 60, switch_max=sm)
+            assign, num, sw = oa.solve_exhaustive(p)
+            assert all(s <= sm for s in sw)
+            assert all(0 <= c < 4 for a in assign for c in a)           # one valid config per unit
+            if prev is not None:
+                assert num <= prev
+            prev = num
+
+
+def test_infeasible_assignment_is_rejected():
+    p = worked_problem(oa.OVERLAP_EXCESS)
+    p.switch_max = 0
+    assert oa.evaluate(p, [[0, 1], [0]]) is None
+
+
+def test_table_mode_uses_excess_granules():
+    a = wl.Worker([1], [[100, 50]])
+    b = wl.Worker([1], [[100, 50]])
+    p = wl.AllocProblem(64, [32, 64], [a, b], 0, oa.OVERLAP_TABLE, alpha_ppm=[0, 300000, 900000], granule=32)
+    # (64,64): excess 64 -> granule 2 -> 100*(1.9) = 190 ; (32,64): excess 32 -> 150*1.3 = 195 ; (32,32): 200
+    assign, num, _ = oa.solve_exhaustive(p)
+    assert assign == [[1], [1]] and num == 100 * 1_900_000
