@@ -1,0 +1,114 @@
+// Device-side helpers shared by the kernels of libeclip (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eclip {
+
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
+
+// 16-bit storage types are carried as raw bit patterns; the tag types select the conversions.
+struct bf16_t { uint16_t bits; };
+struct f16_t { uint16_t bits; };
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;          // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;               // round to nearest even
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b)
+{
+    return (float)__builtin_bit_cast(_Float16, (uint16_t)b);
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
+{
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+template <typename T> struct Cvt;
+template <> struct Cvt<float> {
+    static constexpr int VEC = 4;                                 // elements per 16-byte access
+    __device__ static __forceinline__ float load(const float *p) { return *p; }
+    __device__ static __forceinline__ void store(float *p, float v) { *p = v; }
+};
+template <> struct Cvt<bf16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ float load(const bf16_t *p) { return bf16_bits_to_f32(p->bits); }
+    __device__ static __forceinline__ void store(bf16_t *p, float v) { p->bits = (uint16_t)f32_to_bf16_bits(v); }
+    __device__ static __forceinline__ float from_bits(uint32_t b) { return bf16_bits_to_f32(b); }
+    __device__ static __forceinline__ uint32_t to_bits(float v) { return f32_to_bf16_bits(v); }
+};
+template <> struct Cvt<f16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ float load(const f16_t *p) { return f16_bits_to_f32(p->bits); }
+    __device__ static __forceinline__ void store(f16_t *p, float v) { p->bits = (uint16_t)f32_to_f16_bits(v); }
+    __device__ static __forceinline__ float from_bits(uint32_t b) { return f16_bits_to_f32(b); }
+    __device__ static __forceinline__ uint32_t to_bits(float v) { return f32_to_f16_bits(v); }
+};
+
+// V consecutive elements <-> V floats.  V == Cvt<T>::VEC uses one 16-byte access, V == 1 a scalar one.
+template <typename T, int V> struct Pack {
+    __device__ static __forceinline__ void load(const T *p, float (&v)[V])
+    {
+        if constexpr (V == 1) {
+            v[0] = Cvt<T>::load(p);
+        } else if constexpr (sizeof(T) == 4) {
+            const float4 q = *reinterpret_cast<const float4 *>(p);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+            const uint4 q = *reinterpret_cast<const uint4 *>(p);
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[2 * i] = Cvt<T>::from_bits(w[i] & 0xffffu);
+                v[2 * i + 1] = Cvt<T>::from_bits(w[i] >> 16);
+            }
+        }
+    }
+    __device__ static __forceinline__ void store(T *p, const float (&v)[V])
+    {
+        if constexpr (V == 1) {
+            Cvt<T>::store(p, v[0]);
+        } else if constexpr (sizeof(T) == 4) {
+            *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        } else {
+            uint32_t w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i] = Cvt<T>::to_bits(v[2 * i]) | (Cvt<T>::to_bits(v[2 * i + 1]) << 16);
+            *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+};
+
+__device__ __forceinline__ float apply_act(int act, float v)
+{
+    switch (act) {
+    case ACT_RELU:  return fmaxf(v, 0.0f);
+    case ACT_RELU6: return fminf(fmaxf(v, 0.0f), 6.0f);
+    case ACT_GELU:  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    default:        return v;
+    }
+}
+
+// Sum / max over the 64 lanes of a wavefront; every lane receives the result.
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+}  // namespace eclip

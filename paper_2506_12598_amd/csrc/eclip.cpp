@@ -1,0 +1,1022 @@
+// libeclip host side: stream pool, model loader, executor, profiler, C ABI.
+#include "eclip.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "kernels.h"
+
+namespace eclip {
+std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u128 *obj_out, uint32_t *sw_out, bool *limit);
+}
+using namespace eclip;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+// ------------------------------------------------------------------------------------------------
+static thread_local std::string g_err;
+
+static eclip_status fail(eclip_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return st;
+}
+#define HIP_TRY(call)                                                                                         \
+    do {                                                                                                      \
+        hipError_t e_ = (call);                                                                               \
+        if (e_ != hipSuccess) return fail(ECLIP_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+extern "C" const char *eclip_last_error(void) { return g_err.c_str(); }
+
+// ECLIP_TRACE=1 in the environment prints the library's set-up steps to stderr.
+static bool trace_on()
+{
+    static const bool on = getenv("ECLIP_TRACE") != nullptr;
+    return on;
+}
+#define TRACE(...)                                                        \
+    do {                                                                  \
+        if (trace_on()) { fprintf(stderr, "[eclip] " __VA_ARGS__); fputc('\n', stderr); fflush(stderr); } \
+    } while (0)
+
+// ------------------------------------------------------------------------------------------------
+// pool
+// ------------------------------------------------------------------------------------------------
+struct PoolStream {
+    hipStream_t stream = nullptr;
+    uint32_t n_cu = 0;
+    std::vector<uint32_t> words;
+    int32_t owner = -1;
+};
+struct eclip_pool {
+    int device = 0;
+    uint32_t device_cus = 0;
+    std::vector<PoolStream> streams;
+    int n_models = 0;
+    std::mutex mu;
+};
+
+static uint32_t popcount_words(const uint32_t *w, uint32_t n)
+{
+    uint32_t c = 0;
+    for (uint32_t i = 0; i < n; ++i) c += (uint32_t)__builtin_popcount(w[i]);
+    return c;
+}
+
+extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, uint32_t n_masks, eclip_pool **out)
+{
+    if (!out) return fail(ECLIP_EINVAL, "out is null");
+    *out = nullptr;
+    if (!masks || n_masks == 0) return fail(ECLIP_EINVAL, "no masks given");
+    if (n_masks > ECLIP_MAX_POOL_STREAMS) return fail(ECLIP_ELIMIT, "%u masks exceed the pool limit of %u streams", n_masks, ECLIP_MAX_POOL_STREAMS);
+    for (uint32_t i = 0; i < n_masks; ++i) {
+        if (masks[i].n_words && !masks[i].words) return fail(ECLIP_EINVAL, "mask %u: words is null", i);
+        if (masks[i].n_words && popcount_words(masks[i].words, masks[i].n_words) == 0)
+            return fail(ECLIP_EINVAL, "mask %u enables no CU", i);
+    }
+    int n_dev = 0;
+    TRACE("pool_create: %u masks", n_masks);
+    HIP_TRY(hipGetDeviceCount(&n_dev));
+    TRACE("devices: %d", n_dev);
+    if (device < 0 || device >= n_dev) return fail(ECLIP_EINVAL, "device %d out of range (%d devices)", device, n_dev);
+    HIP_TRY(hipSetDevice(device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, device));
+    const uint32_t cus = (uint32_t)prop.multiProcessorCount;
+    TRACE("device %d: %s, %u CUs", device, prop.name, cus);
+    for (uint32_t i = 0; i < n_masks; ++i)
+        for (uint32_t wd = 0; wd < masks[i].n_words; ++wd)
+            for (uint32_t b = 0; b < 32; ++b)
+                if ((masks[i].words[wd] >> b & 1u) && wd * 32 + b >= cus)
+                    return fail(ECLIP_EINVAL, "mask %u enables CU %u but the device has %u", i, wd * 32 + b, cus);
+    // Consecutive mask bits rotate over the device's XCDs (bit i belongs to XCD i % n_xcc); the runtime does
+    // not survive a queue mask that leaves an XCD without any CU, so such masks are refused here.
+    uint32_t n_xcc = (cus == 256) ? 8u : 1u;
+    if (const char *ev = getenv("ECLIP_NUM_XCC")) n_xcc = (uint32_t)std::max(1, atoi(ev));
+    for (uint32_t i = 0; i < n_masks; ++i) {
+        if (masks[i].n_words == 0) continue;
+        std::vector<uint32_t> per(n_xcc, 0u);
+        for (uint32_t b = 0; b < masks[i].n_words * 32; ++b)
+            if (masks[i].words[b / 32] >> (b % 32) & 1u) per[b % n_xcc]++;
+        for (uint32_t x = 0; x < n_xcc; ++x)
+            if (per[x] == 0) return fail(ECLIP_EINVAL, "mask %u leaves XCD %u (mask bits congruent to %u modulo %u) without a CU", i, x, x, n_xcc);
+    }
+    HIP_TRY(attention_init());
+    TRACE("kernel attributes set");
+    eclip_pool *p = new (std::nothrow) eclip_pool;
+    if (!p) return fail(ECLIP_ENOMEM, "out of host memory");
+    p->device = device;
+    p->device_cus = cus;
+    p->streams.resize(n_masks);
+    for (uint32_t i = 0; i < n_masks; ++i) {
+        PoolStream &s = p->streams[i];
+        s.owner = masks[i].owner;
+        hipError_t e;
+        if (masks[i].n_words == 0) {
+            s.n_cu = cus;
+            e = hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking);
+        } else {
+            s.words.assign(masks[i].words, masks[i].words + masks[i].n_words);
+            s.n_cu = popcount_words(s.words.data(), masks[i].n_words);
+            e = hipExtStreamCreateWithCUMask(&s.stream, masks[i].n_words, s.words.data());
+        }
+        TRACE("stream %u: %u CUs, %s", i, s.n_cu, hipGetErrorString(e));
+        if (e != hipSuccess) {
+            for (uint32_t j = 0; j < i; ++j) (void)hipStreamDestroy(p->streams[j].stream);
+            delete p;
+            return fail(ECLIP_EHIP, "creating pool stream %u failed: %s", i, hipGetErrorString(e));
+        }
+    }
+    *out = p;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_pool_stream(const eclip_pool *pool, uint32_t mask_id, void **hip_stream, uint32_t *n_cu)
+{
+    if (!pool) return fail(ECLIP_EINVAL, "pool is null");
+    if (mask_id >= pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    if (hip_stream) *hip_stream = (void *)pool->streams[mask_id].stream;
+    if (n_cu) *n_cu = pool->streams[mask_id].n_cu;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_pool_device_cus(const eclip_pool *pool, uint32_t *n_cu)
+{
+    if (!pool || !n_cu) return fail(ECLIP_EINVAL, "null argument");
+    *n_cu = pool->device_cus;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_pool_destroy(eclip_pool *pool)
+{
+    if (!pool) return fail(ECLIP_EINVAL, "pool is null");
+    if (pool->n_models > 0) return fail(ECLIP_ESTATE, "%d models are still loaded on this pool", pool->n_models);
+    HIP_TRY(hipSetDevice(pool->device));
+    for (PoolStream &s : pool->streams) {
+        (void)hipStreamSynchronize(s.stream);
+        (void)hipStreamDestroy(s.stream);
+    }
+    delete pool;
+    return ECLIP_OK;
+}
+
+// The granule order of worker 0: odd granules (1-based) ascending, then even ones; worker 1 walks it
+// backwards, so that the two start at opposite ends (Sec. III-A: SE 1,3,2 against SE 4,2,3).  Further
+// pairs of workers use the same two walks rotated.
+extern "C" eclip_status eclip_mask_layout(uint32_t total_cus, uint32_t granule, uint32_t n_workers, uint32_t worker,
+                                          uint32_t take, uint32_t stripe, uint32_t *words_out, uint32_t n_words)
+{
+    if (!words_out) return fail(ECLIP_EINVAL, "words_out is null");
+    if (granule == 0 || total_cus == 0 || total_cus % granule) return fail(ECLIP_EINVAL, "granule %u does not divide %u CUs", granule, total_cus);
+    const uint32_t ng = total_cus / granule;
+    if (n_workers == 0 || worker >= n_workers) return fail(ECLIP_EINVAL, "worker %u of %u", worker, n_workers);
+    if (take == 0 || take > ng) return fail(ECLIP_EINVAL, "take %u of %u granules", take, ng);
+    if ((uint64_t)n_words * 32 < total_cus) return fail(ECLIP_EINVAL, "n_words too small for %u CUs", total_cus);
+    if (stripe && granule % stripe) return fail(ECLIP_EINVAL, "stripe %u does not divide the granule of %u CUs", stripe, granule);
+    std::vector<uint32_t> order;
+    for (uint32_t g = 0; g < ng; g += 2) order.push_back(g);
+    for (uint32_t g = 1; g < ng; g += 2) order.push_back(g);
+    if (worker & 1u) std::reverse(order.begin(), order.end());
+    const uint32_t pairs = (n_workers + 1) / 2;
+    const uint32_t rot = (worker / 2) * (ng / pairs) % ng;
+    std::rotate(order.begin(), order.begin() + rot, order.end());
+    std::fill(words_out, words_out + n_words, 0u);
+    for (uint32_t i = 0; i < take; ++i) {
+        const uint32_t g = order[i];
+        for (uint32_t j = 0; j < granule; ++j) {
+            const uint32_t bit = stripe ? stripe * (g + ng * (j / stripe)) + j % stripe : g * granule + j;
+            words_out[bit / 32] |= 1u << (bit % 32);
+        }
+    }
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_pool_probe(eclip_pool *pool, uint32_t mask_id, uint32_t n_blocks, uint32_t *out)
+{
+    if (!pool || !out) return fail(ECLIP_EINVAL, "null argument");
+    if (mask_id >= pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    if (n_blocks == 0 || n_blocks > 65536) return fail(ECLIP_EINVAL, "n_blocks must be 1..65536");
+    HIP_TRY(hipSetDevice(pool->device));
+    uint32_t *d = nullptr;
+    HIP_TRY(hipMalloc(&d, (size_t)n_blocks * 4));
+    hipStream_t s = pool->streams[mask_id].stream;
+    hipError_t e = launch_probe(d, (int)n_blocks, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(out, d, (size_t)n_blocks * 4, hipMemcpyDeviceToHost);
+    (void)hipFree(d);
+    if (e != hipSuccess) return fail(ECLIP_EHIP, "probe failed: %s", hipGetErrorString(e));
+    return ECLIP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// model
+// ------------------------------------------------------------------------------------------------
+static const size_t NONE = (size_t)-1;
+
+struct Dims { int kind, c, h, w; };   // c as stored (the network input's channels may be padded)
+
+struct LayerPlan {
+    eclip_layer L;
+    Dims in, out;
+    int in_c_logical = 0;      // channels of the input before padding
+    size_t out_off = 0;        // byte offset of this layer's output in the activation arena
+    size_t w_dev = NONE, b_dev = NONE, g_dev = NONE, be_dev = NONE;   // byte offsets in the device weight arena
+    bool gemm = false;         // runs on the matrix-core GEMM kernel
+};
+
+struct eclip_req {
+    eclip_model *model = nullptr;
+    hipEvent_t start = nullptr, done = nullptr;
+    bool pending = false;
+    uint32_t n_kernels = 0, n_switches = 0;
+};
+
+struct eclip_model {
+    eclip_pool *pool = nullptr;
+    int dtype = 0, esize = 2;
+    int in_kind = 0, in_c = 0, in_h = 0, in_w = 0, in_cp = 0;
+    uint32_t max_batch = 1;
+    std::vector<LayerPlan> layers;
+    std::vector<uint32_t> group_of_layer;
+    uint32_t n_groups = 0;
+    std::vector<uint32_t> mask_of_group;
+    bool has_alloc = false;
+
+    char *d_weights = nullptr;
+    char *d_act = nullptr;
+    char *d_in_stage = nullptr;    // channels-last copy of an IMAGE input
+    float *d_ws = nullptr;
+    size_t ws_floats = 0;
+    unsigned *d_counters = nullptr;
+    size_t n_counters = 0;
+    void *d_self_in = nullptr;     // zero input / scratch output for profiling
+    float *d_self_out = nullptr;
+
+    std::vector<eclip_req> reqs;
+    std::vector<hipEvent_t> switch_events;
+    hipEvent_t last_done = nullptr;     // done event of the most recent request (owned by its req)
+    hipStream_t last_stream = nullptr;
+    uint32_t inflight = 0;
+    std::mutex mu;
+};
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static int elem_size(int dtype) { return dtype == ECLIP_F32 ? 4 : 2; }
+
+static size_t out_elems(const eclip_model *m) {
+    const Dims &d = m->layers.back().out;
+    return (size_t)d.c * d.h * d.w;
+}
+static size_t in_elems(const eclip_model *m) {
+    if (m->in_kind == ECLIP_IN_TOKENS) return (size_t)m->in_w;
+    return (size_t)m->in_c * m->in_h * m->in_w;
+}
+
+static void free_model(eclip_model *m)
+{
+    if (!m) return;
+    (void)hipFree(m->d_weights);
+    (void)hipFree(m->d_act);
+    (void)hipFree(m->d_in_stage);
+    (void)hipFree(m->d_ws);
+    (void)hipFree(m->d_counters);
+    (void)hipFree(m->d_self_in);
+    (void)hipFree(m->d_self_out);
+    for (eclip_req &r : m->reqs) {
+        if (r.start) (void)hipEventDestroy(r.start);
+        if (r.done) (void)hipEventDestroy(r.done);
+    }
+    for (hipEvent_t e : m->switch_events)
+        if (e) (void)hipEventDestroy(e);
+    delete m;
+}
+
+// Validates the descriptor and fills the per-layer plans (shapes only).  No HIP call.
+static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, eclip_model *m)
+{
+    if (d->dtype < ECLIP_F32 || d->dtype > ECLIP_F16) return fail(ECLIP_EINVAL, "unknown dtype %d", d->dtype);
+    if (d->in_kind < ECLIP_IN_IMAGE || d->in_kind > ECLIP_IN_VEC) return fail(ECLIP_EINVAL, "unknown input kind %d", d->in_kind);
+    if (!d->layers || d->n_layers == 0) return fail(ECLIP_EINVAL, "model has no layers");
+    if (d->n_layers > 4096) return fail(ECLIP_ELIMIT, "more than 4096 layers");
+    if (!d->group_of_layer || d->n_groups == 0) return fail(ECLIP_EINVAL, "no kernel-group partition");
+    if (d->max_batch == 0 || d->max_inflight == 0) return fail(ECLIP_EINVAL, "max_batch and max_inflight must be >= 1");
+    if (d->max_inflight > 1024) return fail(ECLIP_ELIMIT, "max_inflight above 1024");
+    if (d->in_c <= 0 || d->in_h <= 0 || d->in_w <= 0) return fail(ECLIP_EINVAL, "non-positive input dims");
+    if (d->group_of_layer[0] != 0) return fail(ECLIP_EINVAL, "group_of_layer must start at 0");
+    for (uint32_t i = 1; i < d->n_layers; ++i) {
+        const uint32_t a = d->group_of_layer[i - 1], b = d->group_of_layer[i];
+        if (b != a && b != a + 1) return fail(ECLIP_EINVAL, "group_of_layer not non-decreasing in steps of one at layer %u", i);
+    }
+    if (d->group_of_layer[d->n_layers - 1] != d->n_groups - 1) return fail(ECLIP_EINVAL, "group_of_layer does not end at n_groups-1");
+
+    const bool f32 = d->dtype == ECLIP_F32;
+    m->dtype = d->dtype;
+    m->esize = elem_size(d->dtype);
+    m->in_kind = d->in_kind; m->in_c = d->in_c; m->in_h = d->in_h; m->in_w = d->in_w;
+    // a 16-bit image input is staged with its channel count rounded up to 8 when a matrix-core layer reads it
+    bool gemm_reads_input = false;
+    for (uint32_t i = 0; i < d->n_layers; ++i) {
+        const eclip_layer &L = d->layers[i];
+        if (L.in0 == -1 && ((L.op == ECLIP_OP_CONV && L.groups == 1) || L.op == ECLIP_OP_LINEAR)) gemm_reads_input = true;
+    }
+    m->in_cp = (d->in_kind == ECLIP_IN_IMAGE && !f32 && gemm_reads_input) ? (int)align_up((size_t)d->in_c, 8) : d->in_c;
+    m->max_batch = d->max_batch;
+    m->n_groups = d->n_groups;
+    m->group_of_layer.assign(d->group_of_layer, d->group_of_layer + d->n_layers);
+    m->layers.resize(d->n_layers);
+
+    Dims in_dims;
+    if (d->in_kind == ECLIP_IN_IMAGE) in_dims = Dims{ECLIP_KIND_IMAGE, m->in_cp, d->in_h, d->in_w};
+    else if (d->in_kind == ECLIP_IN_VEC) {
+        if (d->in_h != 1 || d->in_w != 1) return fail(ECLIP_EINVAL, "VEC input needs h = w = 1");
+        in_dims = Dims{ECLIP_KIND_VEC, d->in_c, 1, 1};
+    } else {
+        if (d->in_h != 1) return fail(ECLIP_EINVAL, "SEQ/TOKENS input needs h = 1");
+        in_dims = Dims{ECLIP_KIND_SEQ, d->in_c, 1, d->in_w};
+    }
+    auto check_off = [&](int64_t off, size_t n, const char *what, uint32_t i) -> eclip_status {
+        if (off < 0 || (size_t)off + n > weight_elems)
+            return fail(ECLIP_EINVAL, "layer %u: %s offset %lld (+%zu) outside the weight blob of %zu elements", i, what, (long long)off, n, weight_elems);
+        return ECLIP_OK;
+    };
+    for (uint32_t i = 0; i < d->n_layers; ++i) {
+        const eclip_layer &L = d->layers[i];
+        LayerPlan &P = m->layers[i];
+        P.L = L;
+        if (L.in0 < -1 || L.in0 >= (int)i) return fail(ECLIP_EINVAL, "layer %u: in0 = %d is not an earlier layer", i, L.in0);
+        if (L.in1 != -2 && (L.in1 < -1 || L.in1 >= (int)i)) return fail(ECLIP_EINVAL, "layer %u: in1 = %d is not an earlier layer", i, L.in1);
+        if (L.in0 == -1 && d->in_kind == ECLIP_IN_TOKENS && L.op != ECLIP_OP_EMBED)
+            return fail(ECLIP_EINVAL, "layer %u: only EMBED may read token ids", i);
+        const Dims in = L.in0 == -1 ? in_dims : m->layers[L.in0].out;
+        P.in = in;
+        P.in_c_logical = (L.in0 == -1 && d->in_kind == ECLIP_IN_IMAGE) ? d->in_c : in.c;
+        Dims out{L.kind, L.c, L.h, L.w};
+        if (L.c <= 0 || L.h <= 0 || L.w <= 0) return fail(ECLIP_EINVAL, "layer %u: non-positive output dims", i);
+        if (L.act < ECLIP_ACT_NONE || L.act > ECLIP_ACT_GELU) return fail(ECLIP_EINVAL, "layer %u: unknown activation %d", i, L.act);
+        eclip_status st;
+        switch (L.op) {
+        case ECLIP_OP_CONV: {
+            if (in.kind != ECLIP_KIND_IMAGE || L.kind != ECLIP_KIND_IMAGE) return fail(ECLIP_EINVAL, "layer %u: CONV needs IMAGE input and output", i);
+            if (L.kh <= 0 || L.kw <= 0 || L.stride <= 0 || L.pad < 0) return fail(ECLIP_EINVAL, "layer %u: bad conv geometry", i);
+            if (in.h + 2 * L.pad < L.kh || in.w + 2 * L.pad < L.kw) return fail(ECLIP_EINVAL, "layer %u: kernel larger than padded input", i);
+            const int ho = (in.h + 2 * L.pad - L.kh) / L.stride + 1, wo = (in.w + 2 * L.pad - L.kw) / L.stride + 1;
+            if (L.h != ho || L.w != wo) return fail(ECLIP_EINVAL, "layer %u: CONV output %dx%d declared, %dx%d expected", i, L.h, L.w, ho, wo);
+            const bool dw = L.groups > 1;
+            if (dw && in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: depthwise CONV directly on a channel-padded network input is not supported", i);
+            if (L.groups != 1 && !(L.groups == P.in_c_logical && L.c == L.groups))
+                return fail(ECLIP_EINVAL, "layer %u: groups must be 1 or equal to both channel counts (depthwise)", i);
+            if ((st = check_off(L.w_off, (size_t)L.c * (P.in_c_logical / L.groups) * L.kh * L.kw, "weight", i))) return st;
+            if (L.b_off >= 0 && (st = check_off(L.b_off, L.c, "bias", i))) return st;
+            if (!f32 && !dw && in.c % 8) return fail(ECLIP_EINVAL, "layer %u: 16-bit CONV needs an input channel count that is a multiple of 8 (got %d)", i, in.c);
+            P.gemm = !f32 && !dw;
+            break;
+        }
+        case ECLIP_OP_LINEAR: {
+            const bool seq = in.kind == ECLIP_KIND_SEQ;
+            if (seq) { if (L.kind != ECLIP_KIND_SEQ || L.h != 1 || L.w != in.w) return fail(ECLIP_EINVAL, "layer %u: LINEAR on a sequence keeps [S] (w)", i); }
+            else if (L.kind != ECLIP_KIND_VEC || L.h != 1 || L.w != 1) return fail(ECLIP_EINVAL, "layer %u: LINEAR on an image/vector yields a VEC", i);
+            const size_t k_logical = seq ? (size_t)in.c : (size_t)P.in_c_logical * in.h * in.w;
+            if ((st = check_off(L.w_off, (size_t)L.c * k_logical, "weight", i))) return st;
+            if (L.b_off >= 0 && (st = check_off(L.b_off, L.c, "bias", i))) return st;
+            if (!f32 && in.c % 8) return fail(ECLIP_EINVAL, "layer %u: 16-bit LINEAR needs an input channel count that is a multiple of 8 (got %d)", i, in.c);
+            P.gemm = !f32;
+            break;
+        }
+        case ECLIP_OP_MAXPOOL: {
+            if (in.kind != ECLIP_KIND_IMAGE || L.kind != ECLIP_KIND_IMAGE) return fail(ECLIP_EINVAL, "layer %u: MAXPOOL needs IMAGE tensors", i);
+            if (L.kh <= 0 || L.kw <= 0 || L.stride <= 0 || L.pad < 0 || 2 * L.pad > std::min(L.kh, L.kw))
+                return fail(ECLIP_EINVAL, "layer %u: bad pooling geometry", i);
+            if (in.h + 2 * L.pad < L.kh || in.w + 2 * L.pad < L.kw) return fail(ECLIP_EINVAL, "layer %u: window larger than padded input", i);
+            const int ho = (in.h + 2 * L.pad - L.kh) / L.stride + 1, wo = (in.w + 2 * L.pad - L.kw) / L.stride + 1;
+            if (L.h != ho || L.w != wo || L.c != in.c) return fail(ECLIP_EINVAL, "layer %u: MAXPOOL output dims mismatch", i);
+            if (in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: MAXPOOL directly on a channel-padded network input is not supported", i);
+            break;
+        }
+        case ECLIP_OP_GAP:
+            if (in.kind != ECLIP_KIND_IMAGE || L.kind != ECLIP_KIND_VEC || L.c != in.c || L.h != 1 || L.w != 1)
+                return fail(ECLIP_EINVAL, "layer %u: GAP maps IMAGE [C,H,W] to VEC [C]", i);
+            if (in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: GAP directly on a channel-padded network input is not supported", i);
+            break;
+        case ECLIP_OP_LAYERNORM:
+        case ECLIP_OP_SOFTMAX: {
+            if (in.kind == ECLIP_KIND_IMAGE) return fail(ECLIP_EINVAL, "layer %u: row operators need SEQ or VEC tensors", i);
+            if (L.kind != in.kind || L.c != in.c || L.h != in.h || L.w != in.w) return fail(ECLIP_EINVAL, "layer %u: row operator changes shape", i);
+            const int v = f32 ? (in.c % 4 ? 1 : 4) : (in.c % 8 ? 1 : 8);
+            if ((in.c / v + 63) / 64 > 16) return fail(ECLIP_EINVAL, "layer %u: row of %d elements exceeds the kernel's register budget", i, in.c);
+            if (L.op == ECLIP_OP_LAYERNORM) {
+                if (L.g_off >= 0 && (st = check_off(L.g_off, L.c, "gamma", i))) return st;
+                if (L.be_off >= 0 && (st = check_off(L.be_off, L.c, "beta", i))) return st;
+                if (!(L.eps >= 0.0f)) return fail(ECLIP_EINVAL, "layer %u: negative eps", i);
+            }
+            break;
+        }
+        case ECLIP_OP_ATTENTION: {
+            if (f32) return fail(ECLIP_EINVAL, "layer %u: ATTENTION needs a 16-bit model", i);
+            if (in.kind != ECLIP_KIND_SEQ || L.kind != ECLIP_KIND_SEQ || in.c % 3 || L.c != in.c / 3 || L.w != in.w || L.h != 1)
+                return fail(ECLIP_EINVAL, "layer %u: ATTENTION maps SEQ [S,3*Hd] to SEQ [S,Hd]", i);
+            if (L.heads <= 0 || L.c % L.heads) return fail(ECLIP_EINVAL, "layer %u: heads must divide the hidden size", i);
+            const int dh = L.c / L.heads;
+            if (dh != 32 && dh != 64) return fail(ECLIP_EINVAL, "layer %u: head size %d not supported (32 or 64)", i, dh);
+            if (in.w > 512) return fail(ECLIP_EINVAL, "layer %u: sequence length %d above 512", i, in.w);
+            break;
+        }
+        case ECLIP_OP_EMBED: {
+            if (L.in0 != -1 || d->in_kind != ECLIP_IN_TOKENS) return fail(ECLIP_EINVAL, "layer %u: EMBED reads the token-id input", i);
+            if (L.kind != ECLIP_KIND_SEQ || L.h != 1 || L.w != d->in_w || L.c != d->in_c) return fail(ECLIP_EINVAL, "layer %u: EMBED output must be SEQ [S,Hd]", i);
+            if (L.aux0 <= 0 || L.aux1 < d->in_w) return fail(ECLIP_EINVAL, "layer %u: EMBED needs vocab > 0 and at least S positions", i);
+            if ((st = check_off(L.w_off, (size_t)L.aux0 * L.c, "token table", i))) return st;
+            if ((st = check_off(L.g_off, (size_t)L.aux1 * L.c, "position table", i))) return st;
+            if ((st = check_off(L.be_off, (size_t)2 * L.c, "type table", i))) return st;
+            break;
+        }
+        case ECLIP_OP_ELTWISE:
+            if (L.kind != in.kind || L.c != in.c || L.h != in.h || L.w != in.w) return fail(ECLIP_EINVAL, "layer %u: ELTWISE changes shape", i);
+            if (in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: ELTWISE directly on a channel-padded network input is not supported", i);
+            if (L.b_off >= 0 && (st = check_off(L.b_off, L.c, "bias", i))) return st;
+            break;
+        default:
+            return fail(ECLIP_EINVAL, "layer %u: unknown op %d", i, L.op);
+        }
+        if (L.in1 != -2) {
+            if (L.op == ECLIP_OP_MAXPOOL || L.op == ECLIP_OP_GAP || L.op == ECLIP_OP_SOFTMAX || L.op == ECLIP_OP_ATTENTION || L.op == ECLIP_OP_EMBED)
+                return fail(ECLIP_EINVAL, "layer %u: this op takes no second input", i);
+            if (L.in1 == -1 && d->in_kind == ECLIP_IN_TOKENS) return fail(ECLIP_EINVAL, "layer %u: token ids cannot be a residual", i);
+            const Dims r = L.in1 == -1 ? in_dims : m->layers[L.in1].out;
+            if (r.kind != out.kind || r.c != out.c || r.h != out.h || r.w != out.w)
+                return fail(ECLIP_EINVAL, "layer %u: residual input shape differs from the output shape", i);
+        }
+        if ((size_t)out.c * out.h * out.w * d->max_batch > ((size_t)1 << 31)) return fail(ECLIP_ELIMIT, "layer %u: tensor above 2^31 elements", i);
+        P.out = out;
+    }
+    return ECLIP_OK;
+}
+
+// Converts one 16-bit or 32-bit element array; helpers for the weight re-layout (host side).
+static void put(std::vector<char> &arena, size_t &cursor, const void *src, size_t bytes, size_t *off_out)
+{
+    cursor = align_up(cursor, 256);
+    if (arena.size() < cursor + bytes) arena.resize(cursor + bytes);
+    if (src) memcpy(arena.data() + cursor, src, bytes);
+    *off_out = cursor;
+    cursor += bytes;
+}
+
+template <typename E>
+static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &arena, size_t &cursor)
+{
+    const bool f32 = m->dtype == ECLIP_F32;
+    for (LayerPlan &P : m->layers) {
+        const eclip_layer &L = P.L;
+        const size_t es = sizeof(E);
+        if (L.op == ECLIP_OP_CONV || L.op == ECLIP_OP_LINEAR) {
+            // logical [cout][cin_g][kh][kw]; a LINEAR on an image is a convolution whose window is the image
+            int kh = L.kh, kw = L.kw;
+            const int cin_l = P.in_c_logical, cin_s = P.in.c;
+            if (L.op == ECLIP_OP_LINEAR) { kh = (P.in.kind == ECLIP_KIND_IMAGE) ? P.in.h : 1; kw = (P.in.kind == ECLIP_KIND_IMAGE) ? P.in.w : 1; }
+            const bool dw = L.op == ECLIP_OP_CONV && L.groups > 1;
+            const E *src = w + L.w_off;
+            if (dw) {                                   // -> [kh][kw][c]
+                std::vector<E> t((size_t)kh * kw * L.c);
+                for (int c = 0; c < L.c; ++c)
+                    for (int i = 0; i < kh * kw; ++i) t[(size_t)i * L.c + c] = src[(size_t)c * kh * kw + i];
+                put(arena, cursor, t.data(), t.size() * es, &P.w_dev);
+            } else if (f32) {                           // -> [kh][kw][cin][cout]
+                std::vector<E> t((size_t)kh * kw * cin_s * L.c);
+                for (int co = 0; co < L.c; ++co)
+                    for (int ci = 0; ci < cin_l; ++ci)
+                        for (int i = 0; i < kh * kw; ++i)
+                            t[((size_t)i * cin_s + ci) * L.c + co] = src[((size_t)co * cin_l + ci) * kh * kw + i];
+                put(arena, cursor, t.data(), t.size() * es, &P.w_dev);
+            } else {                                    // -> [cout][kh][kw][cin_stored], padded channels zero
+                const size_t K = (size_t)kh * kw * cin_s;
+                size_t off;
+                put(arena, cursor, nullptr, (size_t)L.c * K * es, &off);
+                E *dst = reinterpret_cast<E *>(arena.data() + off);
+                if (kh * kw == 1 && cin_l == cin_s) {
+                    memcpy(dst, src, (size_t)L.c * K * es);
+                } else {
+                    memset(dst, 0, (size_t)L.c * K * es);
+                    for (int co = 0; co < L.c; ++co)
+                        for (int ci = 0; ci < cin_l; ++ci)
+                            for (int i = 0; i < kh * kw; ++i)
+                                dst[(size_t)co * K + (size_t)i * cin_s + ci] = src[((size_t)co * cin_l + ci) * kh * kw + i];
+                }
+                P.w_dev = off;
+            }
+            if (L.b_off >= 0) put(arena, cursor, w + L.b_off, (size_t)L.c * es, &P.b_dev);
+        } else if (L.op == ECLIP_OP_LAYERNORM) {
+            if (L.g_off >= 0) put(arena, cursor, w + L.g_off, (size_t)L.c * es, &P.g_dev);
+            if (L.be_off >= 0) put(arena, cursor, w + L.be_off, (size_t)L.c * es, &P.be_dev);
+        } else if (L.op == ECLIP_OP_EMBED) {
+            put(arena, cursor, w + L.w_off, (size_t)L.aux0 * L.c * es, &P.w_dev);
+            put(arena, cursor, w + L.g_off, (size_t)L.aux1 * L.c * es, &P.g_dev);
+            put(arena, cursor, w + L.be_off, (size_t)2 * L.c * es, &P.be_dev);
+        } else if (L.op == ECLIP_OP_ELTWISE) {
+            if (L.b_off >= 0) put(arena, cursor, w + L.b_off, (size_t)L.c * es, &P.b_dev);
+        }
+    }
+}
+
+// GEMM view of a CONV / LINEAR layer
+struct GemmShape { int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad; };
+static GemmShape gemm_shape(const LayerPlan &P, int batch)
+{
+    const eclip_layer &L = P.L;
+    GemmShape g;
+    g.B = batch; g.Cin = P.in.c; g.Cout = L.c;
+    if (L.op == ECLIP_OP_CONV) {
+        g.H = P.in.h; g.W = P.in.w; g.Ho = L.h; g.Wo = L.w; g.KH = L.kh; g.KW = L.kw; g.stride = L.stride; g.pad = L.pad;
+    } else if (P.in.kind == ECLIP_KIND_IMAGE) {
+        g.H = P.in.h; g.W = P.in.w; g.Ho = 1; g.Wo = 1; g.KH = P.in.h; g.KW = P.in.w; g.stride = 1; g.pad = 0;
+    } else {
+        g.H = 1; g.W = P.in.w; g.Ho = 1; g.Wo = P.in.w; g.KH = 1; g.KW = 1; g.stride = 1; g.pad = 0;
+    }
+    return g;
+}
+
+extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_desc *desc, const void *weights,
+                                         size_t weight_bytes, int weights_on_device, eclip_model **out)
+{
+    if (!out) return fail(ECLIP_EINVAL, "out is null");
+    *out = nullptr;
+    if (!desc) return fail(ECLIP_EINVAL, "descriptor is null");
+    if (!weights && weight_bytes) return fail(ECLIP_EINVAL, "weights is null");
+    eclip_model *m = new (std::nothrow) eclip_model;
+    if (!m) return fail(ECLIP_ENOMEM, "out of host memory");
+    const int es = (desc->dtype == ECLIP_F32) ? 4 : 2;
+    eclip_status st = plan_model(desc, weight_bytes / (size_t)es, m);
+    if (st != ECLIP_OK) { delete m; return st; }
+    if (!pool) { delete m; return fail(ECLIP_EINVAL, "pool is null"); }
+    m->pool = pool;
+
+#define LOAD_TRY(call)                                                                                   \
+    do {                                                                                                 \
+        hipError_t e_ = (call);                                                                          \
+        if (e_ != hipSuccess) {                                                                          \
+            free_model(m);                                                                               \
+            return fail(e_ == hipErrorOutOfMemory ? ECLIP_ENOMEM : ECLIP_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+        }                                                                                                \
+    } while (0)
+
+    LOAD_TRY(hipSetDevice(pool->device));
+    // ---- weights: host copy -> re-layout -> device arena
+    std::vector<char> host_copy;
+    const void *w_host = weights;
+    if (weights_on_device) {
+        host_copy.resize(weight_bytes);
+        LOAD_TRY(hipMemcpy(host_copy.data(), weights, weight_bytes, hipMemcpyDeviceToHost));
+        w_host = host_copy.data();
+    }
+    std::vector<char> arena;
+    size_t cursor = 0;
+    if (es == 4) relayout_weights<uint32_t>(m, (const uint32_t *)w_host, arena, cursor);
+    else relayout_weights<uint16_t>(m, (const uint16_t *)w_host, arena, cursor);
+    LOAD_TRY(hipMalloc((void **)&m->d_weights, std::max<size_t>(cursor, 256)));
+    if (cursor) LOAD_TRY(hipMemcpy(m->d_weights, arena.data(), cursor, hipMemcpyHostToDevice));
+    std::vector<char>().swap(arena);
+
+    // ---- activation arena: one buffer per layer, sized for max_batch
+    size_t act = 0;
+    for (LayerPlan &P : m->layers) {
+        P.out_off = act;
+        act += align_up((size_t)P.out.c * P.out.h * P.out.w * m->max_batch * (size_t)es, 256);
+    }
+    LOAD_TRY(hipMalloc((void **)&m->d_act, std::max<size_t>(act, 256)));
+    if (m->in_kind == ECLIP_IN_IMAGE)
+        LOAD_TRY(hipMalloc((void **)&m->d_in_stage, (size_t)m->in_cp * m->in_h * m->in_w * m->max_batch * (size_t)es));
+
+    // ---- split-K workspace: enough for the most demanding GEMM layer at any CU count, capped
+    size_t ws = 0;
+    for (const LayerPlan &P : m->layers) {
+        if (!P.gemm) continue;
+        const GemmShape g = gemm_shape(P, (int)m->max_batch);
+        const size_t MN = (size_t)g.B * g.Ho * g.Wo * g.Cout;
+        const size_t KT = ((size_t)g.KH * g.KW * g.Cin + 31) / 32;
+        if (MN <= (size_t)512 * 64 * 64) ws = std::max(ws, MN * std::min<size_t>(32, std::max<size_t>(1, KT / 4)));
+    }
+    m->ws_floats = std::min<size_t>(ws, (size_t)16 << 20);
+    m->n_counters = 4096;
+    LOAD_TRY(hipMalloc((void **)&m->d_ws, std::max<size_t>(m->ws_floats * 4, 256)));
+    LOAD_TRY(hipMalloc((void **)&m->d_counters, m->n_counters * 4));
+    LOAD_TRY(hipMemset(m->d_counters, 0, m->n_counters * 4));
+
+    // ---- profiling buffers, requests, events
+    const size_t in_bytes = in_elems(m) * m->max_batch * (size_t)(m->in_kind == ECLIP_IN_TOKENS ? 4 : es);
+    LOAD_TRY(hipMalloc(&m->d_self_in, std::max<size_t>(in_bytes, 256)));
+    LOAD_TRY(hipMemset(m->d_self_in, 0, std::max<size_t>(in_bytes, 256)));
+    LOAD_TRY(hipMalloc((void **)&m->d_self_out, std::max<size_t>(out_elems(m) * m->max_batch * 4, 256)));
+    m->reqs.resize(desc->max_inflight);
+    for (eclip_req &r : m->reqs) {
+        r.model = m;
+        LOAD_TRY(hipEventCreate(&r.start));
+        LOAD_TRY(hipEventCreate(&r.done));
+    }
+    m->switch_events.assign(m->n_groups, nullptr);
+    for (hipEvent_t &e : m->switch_events) LOAD_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    LOAD_TRY(hipDeviceSynchronize());
+#undef LOAD_TRY
+    {
+        std::lock_guard<std::mutex> lk(pool->mu);
+        pool->n_models++;
+    }
+    *out = m;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_model_free(eclip_model *model)
+{
+    if (!model) return fail(ECLIP_EINVAL, "model is null");
+    {
+        std::lock_guard<std::mutex> lk(model->mu);
+        if (model->inflight) return fail(ECLIP_ESTATE, "%u requests still in flight", model->inflight);
+    }
+    eclip_pool *pool = model->pool;
+    HIP_TRY(hipSetDevice(pool->device));
+    HIP_TRY(hipDeviceSynchronize());
+    free_model(model);
+    std::lock_guard<std::mutex> lk(pool->mu);
+    pool->n_models--;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_alloc_set(eclip_model *model, const uint32_t *mask_id_of_group, uint32_t n_groups)
+{
+    if (!model || !mask_id_of_group) return fail(ECLIP_EINVAL, "null argument");
+    if (n_groups != model->n_groups) return fail(ECLIP_EINVAL, "table has %u groups, the model %u", n_groups, model->n_groups);
+    for (uint32_t g = 0; g < n_groups; ++g)
+        if (mask_id_of_group[g] >= model->pool->streams.size())
+            return fail(ECLIP_EINVAL, "group %u: unknown mask id %u", g, mask_id_of_group[g]);
+    std::lock_guard<std::mutex> lk(model->mu);
+    model->mask_of_group.assign(mask_id_of_group, mask_id_of_group + n_groups);
+    model->has_alloc = true;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_model_switches(const eclip_model *model, uint32_t *n_switches)
+{
+    if (!model || !n_switches) return fail(ECLIP_EINVAL, "null argument");
+    if (!model->has_alloc) return fail(ECLIP_ESTATE, "no allocation table installed");
+    uint32_t n = 0;
+    for (uint32_t g = 1; g < model->n_groups; ++g) n += model->mask_of_group[g] != model->mask_of_group[g - 1];
+    *n_switches = n;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_model_group_size(const eclip_model *model, uint32_t group, uint32_t *n_kernels)
+{
+    if (!model || !n_kernels) return fail(ECLIP_EINVAL, "null argument");
+    if (group >= model->n_groups) return fail(ECLIP_EINVAL, "unknown group %u", group);
+    *n_kernels = (uint32_t)std::count(model->group_of_layer.begin(), model->group_of_layer.end(), group);
+    return ECLIP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// executor
+// ------------------------------------------------------------------------------------------------
+static const void *wptr(const eclip_model *m, size_t off) { return off == NONE ? nullptr : (const void *)(m->d_weights + off); }
+
+// Launches layer i on `s`.  `d_out32` non-null: this is the last layer and its result goes to the caller.
+static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_t s, int n_cu, const void *d_in, float *d_out32,
+                               uint32_t *n_launched)
+{
+    LayerPlan &P = m->layers[i];
+    const eclip_layer &L = P.L;
+    const int dt = m->dtype;
+    auto src = [&](int idx) -> const void * {
+        if (idx == -2) return nullptr;
+        if (idx == -1) return m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in;
+        return (const void *)(m->d_act + m->layers[idx].out_off);
+    };
+    void *y = m->d_act + P.out_off;
+    // the last layer writes float32 straight into the caller's buffer when its internal layout is the
+    // logical one (SEQ / VEC) and its kernel has a float output path
+    const bool chan_last_out = P.out.kind != ECLIP_KIND_IMAGE || (P.out.h == 1 && P.out.w == 1);
+    float *y32 = nullptr;
+    hipError_t e = hipSuccess;
+    const long rows = (long)batch * P.out.h * P.out.w;
+    *n_launched += 1;
+    switch (L.op) {
+    case ECLIP_OP_CONV:
+    case ECLIP_OP_LINEAR: {
+        const GemmShape g = gemm_shape(P, batch);
+        if (P.gemm) {
+            if (d_out32 && chan_last_out) y32 = d_out32;
+            ConvGemmArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y32 ? nullptr : y, y32, m->d_ws, m->d_counters,
+                           g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, dt};
+            const GemmPlan pl = conv_gemm_plan((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats, m->n_counters);
+            e = launch_conv_gemm(a, pl, s);
+        } else if (L.op == ECLIP_OP_CONV && L.groups > 1) {
+            DwConvArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y, g.B, g.H, g.W, L.c, g.Ho, g.Wo, g.KH, g.KW, g.stride, g.pad, L.act, dt};
+            e = launch_dwconv(a, n_cu, s);
+        } else {
+            float *yf = (float *)y;
+            if (d_out32 && chan_last_out) { yf = d_out32; y32 = d_out32; }
+            ConvF32Args a{(const float *)src(L.in0), (const float *)wptr(m, P.w_dev), (const float *)wptr(m, P.b_dev), (const float *)src(L.in1), yf,
+                          g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act};
+            e = launch_conv_f32(a, s);
+        }
+        break;
+    }
+    case ECLIP_OP_MAXPOOL: {
+        PoolArgs a{src(L.in0), y, batch, P.in.h, P.in.w, L.c, L.h, L.w, L.kh, L.kw, L.stride, L.pad, dt};
+        e = launch_maxpool(a, n_cu, s);
+        break;
+    }
+    case ECLIP_OP_GAP:
+        if (d_out32) y32 = d_out32;
+        e = launch_gap(src(L.in0), y, y32, batch, P.in.h * P.in.w, L.c, dt, n_cu, s);
+        break;
+    case ECLIP_OP_LAYERNORM:
+    case ECLIP_OP_SOFTMAX: {
+        if (d_out32) y32 = d_out32;
+        RowArgs a{src(L.in0), src(L.in1), wptr(m, P.g_dev), wptr(m, P.be_dev), y, y32, rows, L.c, L.eps, dt};
+        e = L.op == ECLIP_OP_LAYERNORM ? launch_layernorm(a, n_cu, s) : launch_softmax(a, n_cu, s);
+        break;
+    }
+    case ECLIP_OP_ATTENTION: {
+        if (d_out32) y32 = d_out32;
+        AttnArgs a{src(L.in0), y, y32, batch, P.in.w, L.c, L.heads, dt};
+        e = launch_attention(a, n_cu, s);
+        break;
+    }
+    case ECLIP_OP_EMBED: {
+        EmbedArgs a{(const int32_t *)d_in, wptr(m, P.w_dev), wptr(m, P.g_dev), wptr(m, P.be_dev), y, batch, P.out.w, L.c, L.aux0, dt};
+        e = launch_embed(a, n_cu, s);
+        break;
+    }
+    case ECLIP_OP_ELTWISE: {
+        if (d_out32 && chan_last_out) y32 = d_out32;
+        EltArgs a{src(L.in0), wptr(m, P.b_dev), src(L.in1), y, y32, rows, L.c, L.act, dt};
+        e = launch_eltwise(a, n_cu, s);
+        break;
+    }
+    default:
+        e = hipErrorInvalidValue;
+    }
+    if (e != hipSuccess || !d_out32 || y32) return e;
+    // the layer could not write the caller's buffer itself: convert its internal output
+    *n_launched += 1;
+    if (P.out.kind == ECLIP_KIND_IMAGE && !chan_last_out) return launch_nhwc_to_nchw_f32(y, d_out32, batch, P.out.c, P.out.h, P.out.w, dt, s);
+    return launch_to_f32(y, d_out32, rows * P.out.c, dt, s);
+}
+
+static hipError_t launch_input_stage(eclip_model *m, int batch, const void *d_in, hipStream_t s, uint32_t *n_launched)
+{
+    if (m->in_kind != ECLIP_IN_IMAGE) return hipSuccess;
+    *n_launched += 1;
+    return launch_nchw_to_nhwc(d_in, m->d_in_stage, batch, m->in_c, m->in_h, m->in_w, m->in_cp, m->dtype, s);
+}
+
+extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out)
+{
+    if (!model || !out) return fail(ECLIP_EINVAL, "null argument");
+    *out = nullptr;
+    if (!d_in || !d_out) return fail(ECLIP_EINVAL, "null device buffer");
+    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
+    std::lock_guard<std::mutex> lk(model->mu);
+    if (!model->has_alloc) return fail(ECLIP_ESTATE, "eclip_alloc_set has not been called");
+    eclip_req *r = nullptr;
+    for (eclip_req &q : model->reqs)
+        if (!q.pending) { r = &q; break; }
+    if (!r) return fail(ECLIP_ELIMIT, "more than %zu requests in flight", model->reqs.size());
+    eclip_pool *pool = model->pool;
+    HIP_TRY(hipSetDevice(pool->device));
+
+    const uint32_t n_layers = (uint32_t)model->layers.size();
+    hipStream_t cur = pool->streams[model->mask_of_group[0]].stream;
+    // requests of one model run in order: the first kernel waits for the previous request when that
+    // one ended on another stream (on the same stream, queue order already serialises them)
+    if (model->last_done && model->last_stream != cur) HIP_TRY(hipStreamWaitEvent(cur, model->last_done, 0));
+    HIP_TRY(hipEventRecord(r->start, cur));
+    r->n_kernels = 0;
+    r->n_switches = 0;
+    HIP_TRY(launch_input_stage(model, (int)batch, d_in, cur, &r->n_kernels));
+    uint32_t prev_group = 0;
+    for (uint32_t i = 0; i < n_layers; ++i) {
+        const uint32_t g = model->group_of_layer[i];
+        const PoolStream &ps = pool->streams[model->mask_of_group[g]];
+        if (g != prev_group && ps.stream != cur) {
+            // group boundary that changes stream: the next group waits for everything queued so far
+            HIP_TRY(hipEventRecord(model->switch_events[g], cur));
+            HIP_TRY(hipStreamWaitEvent(ps.stream, model->switch_events[g], 0));
+            cur = ps.stream;
+            r->n_switches++;
+        }
+        prev_group = g;
+        HIP_TRY(launch_layer(model, i, (int)batch, cur, (int)ps.n_cu, d_in, i + 1 == n_layers ? (float *)d_out : nullptr, &r->n_kernels));
+    }
+    HIP_TRY(hipEventRecord(r->done, cur));
+    r->pending = true;
+    model->inflight++;
+    model->last_done = r->done;
+    model->last_stream = cur;
+    *out = r;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_wait(eclip_req *req, uint64_t timeout_ns, eclip_timing *opt_out)
+{
+    if (!req || !req->model) return fail(ECLIP_EINVAL, "request is null");
+    eclip_model *m = req->model;
+    if (!req->pending) return fail(ECLIP_ESTATE, "request is not pending");
+    if (timeout_ns == UINT64_MAX) {
+        HIP_TRY(hipEventSynchronize(req->done));
+    } else {
+        const auto deadline = std::chrono::steady_clock::now() + std::chrono::nanoseconds(timeout_ns);
+        for (;;) {
+            const hipError_t e = hipEventQuery(req->done);
+            if (e == hipSuccess) break;
+            if (e != hipErrorNotReady) return fail(ECLIP_EHIP, "hipEventQuery failed: %s", hipGetErrorString(e));
+            if (std::chrono::steady_clock::now() >= deadline) return fail(ECLIP_ETIMEOUT, "request still running after %llu ns", (unsigned long long)timeout_ns);
+            std::this_thread::yield();
+        }
+    }
+    if (opt_out) {
+        float ms = 0.0f;
+        HIP_TRY(hipEventElapsedTime(&ms, req->start, req->done));
+        opt_out->gpu_ns = (uint64_t)((double)ms * 1e6);
+        opt_out->n_kernels = req->n_kernels;
+        opt_out->n_switches = req->n_switches;
+    }
+    std::lock_guard<std::mutex> lk(m->mu);
+    req->pending = false;
+    m->inflight--;
+    if (m->last_done == req->done && m->inflight == 0) { /* keep last_done: the event stays valid and signalled */ }
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_profile_group(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
+                                            uint32_t iters, uint64_t *ns_per_kernel_out)
+{
+    if (!model || !ns_per_kernel_out) return fail(ECLIP_EINVAL, "null argument");
+    if (group >= model->n_groups) return fail(ECLIP_EINVAL, "unknown group %u", group);
+    if (mask_id >= model->pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
+    if (iters == 0 || iters > 10000) return fail(ECLIP_EINVAL, "iters must be 1..10000");
+    std::lock_guard<std::mutex> lk(model->mu);
+    if (model->inflight) return fail(ECLIP_ESTATE, "requests in flight");
+    eclip_pool *pool = model->pool;
+    HIP_TRY(hipSetDevice(pool->device));
+    const PoolStream &ps = pool->streams[mask_id];
+    const uint32_t n_layers = (uint32_t)model->layers.size();
+    uint32_t dummy = 0;
+    // untimed full pass so that every activation buffer holds finite data
+    HIP_TRY(launch_input_stage(model, (int)batch, model->d_self_in, ps.stream, &dummy));
+    for (uint32_t i = 0; i < n_layers; ++i)
+        HIP_TRY(launch_layer(model, i, (int)batch, ps.stream, (int)ps.n_cu, model->d_self_in, i + 1 == n_layers ? model->d_self_out : nullptr, &dummy));
+    HIP_TRY(hipStreamSynchronize(ps.stream));
+    std::vector<uint32_t> idx;
+    for (uint32_t i = 0; i < n_layers; ++i)
+        if (model->group_of_layer[i] == group) idx.push_back(i);
+    const size_t nk = idx.size();
+    std::vector<hipEvent_t> ev(nk + 1, nullptr);
+    eclip_status st = ECLIP_OK;
+    for (hipEvent_t &e : ev)
+        if (hipEventCreate(&e) != hipSuccess) st = fail(ECLIP_EHIP, "hipEventCreate failed");
+    std::vector<std::vector<float>> samples(nk);
+    for (uint32_t it = 0; it < iters + 2 && st == ECLIP_OK; ++it) {       // two warm-up rounds
+        hipError_t e = hipEventRecord(ev[0], ps.stream);
+        for (size_t k = 0; k < nk && e == hipSuccess; ++k) {
+            const uint32_t i = idx[k];
+            e = launch_layer(model, i, (int)batch, ps.stream, (int)ps.n_cu, model->d_self_in, i + 1 == n_layers ? model->d_self_out : nullptr, &dummy);
+            if (e == hipSuccess) e = hipEventRecord(ev[k + 1], ps.stream);
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(ps.stream);
+        if (e != hipSuccess) { st = fail(ECLIP_EHIP, "profiling launch failed: %s", hipGetErrorString(e)); break; }
+        if (it < 2) continue;
+        for (size_t k = 0; k < nk; ++k) {
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, ev[k], ev[k + 1]) != hipSuccess) { st = fail(ECLIP_EHIP, "hipEventElapsedTime failed"); break; }
+            samples[k].push_back(ms);
+        }
+    }
+    for (hipEvent_t e : ev)
+        if (e) (void)hipEventDestroy(e);
+    if (st != ECLIP_OK) return st;
+    for (size_t k = 0; k < nk; ++k) {
+        std::sort(samples[k].begin(), samples[k].end());
+        ns_per_kernel_out[k] = (uint64_t)std::llround((double)samples[k][samples[k].size() / 2] * 1e6);
+    }
+    return ECLIP_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// allocator entry point
+// ------------------------------------------------------------------------------------------------
+extern "C" eclip_status eclip_alloc_solve(const eclip_alloc_problem *problem, uint32_t *cfg_idx_out,
+                                          eclip_u128 *objective_out, uint32_t *switches_out)
+{
+    bool limit = false;
+    std::string err;
+    try {
+        err = solve_alloc(problem, cfg_idx_out, objective_out, switches_out, &limit);
+    } catch (const std::bad_alloc &) {
+        return fail(ECLIP_ENOMEM, "allocation solver ran out of memory");
+    }
+    if (err.empty()) return ECLIP_OK;
+    return fail(limit ? ECLIP_ELIMIT : ECLIP_EINVAL, "%s", err.c_str());
+}
+
+// ------------------------------------------------------------------------------------------------
+// repartitioning overhead
+// ------------------------------------------------------------------------------------------------
+extern "C" eclip_status eclip_bench_switch(eclip_pool *pool, uint32_t mask_a, uint32_t mask_b, uint32_t iters,
+                                           double *same_stream_ns, double *pooled_ns, double *create_ns)
+{
+    if (!pool) return fail(ECLIP_EINVAL, "pool is null");
+    if (mask_a >= pool->streams.size() || mask_b >= pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id");
+    if (iters == 0 || iters > 100000) return fail(ECLIP_EINVAL, "iters must be 1..100000");
+    HIP_TRY(hipSetDevice(pool->device));
+    const PoolStream &A = pool->streams[mask_a], &B = pool->streams[mask_b];
+    uint32_t *d = nullptr;
+    HIP_TRY(hipMalloc(&d, 256));
+    HIP_TRY(hipMemset(d, 0, 256));
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    eclip_status st = ECLIP_OK;
+    auto now = [] { return std::chrono::steady_clock::now(); };
+    auto ns = [](std::chrono::steady_clock::time_point a, std::chrono::steady_clock::time_point b) {
+        return (double)std::chrono::duration_cast<std::chrono::nanoseconds>(b - a).count();
+    };
+#define B_TRY(call)                                                                                       \
+    do {                                                                                                  \
+        hipError_t e_ = (call);                                                                           \
+        if (e_ != hipSuccess) { st = fail(ECLIP_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); goto done; } \
+    } while (0)
+    B_TRY(hipEventCreateWithFlags(&ev[0], hipEventDisableTiming));
+    B_TRY(hipEventCreateWithFlags(&ev[1], hipEventDisableTiming));
+    {
+        // warm-up
+        for (int i = 0; i < 16; ++i) { B_TRY(launch_tick(d, A.stream)); }
+        B_TRY(hipStreamSynchronize(A.stream));
+        // (1) no repartitioning
+        auto t0 = now();
+        for (uint32_t i = 0; i < iters; ++i) B_TRY(launch_tick(d, A.stream));
+        B_TRY(hipStreamSynchronize(A.stream));
+        auto t1 = now();
+        if (same_stream_ns) *same_stream_ns = ns(t0, t1) / iters;
+        // (2) alternate between two pooled streams; each kernel waits for the previous one
+        t0 = now();
+        for (uint32_t i = 0; i < iters; ++i) {
+            const hipStream_t cur = (i & 1) ? B.stream : A.stream, prev = (i & 1) ? A.stream : B.stream;
+            if (i) {
+                B_TRY(hipEventRecord(ev[i & 1], prev));
+                B_TRY(hipStreamWaitEvent(cur, ev[i & 1], 0));
+            }
+            B_TRY(launch_tick(d, cur));
+        }
+        B_TRY(hipStreamSynchronize(A.stream));
+        B_TRY(hipStreamSynchronize(B.stream));
+        t1 = now();
+        if (pooled_ns) *pooled_ns = ns(t0, t1) / iters;
+        // (3) apply the mask at run time: a fresh masked stream per kernel
+        if (create_ns) {
+            const uint32_t n = std::min<uint32_t>(iters, 2000);
+            std::vector<uint32_t> all_words((pool->device_cus + 31) / 32, 0u);
+            const std::vector<uint32_t> *words = &B.words;
+            if (B.words.empty()) {
+                for (uint32_t c = 0; c < pool->device_cus; ++c) all_words[c / 32] |= 1u << (c % 32);
+                words = &all_words;
+            }
+            hipStream_t prev = nullptr;
+            t0 = now();
+            for (uint32_t i = 0; i < n; ++i) {
+                hipStream_t sN = nullptr;
+                B_TRY(hipExtStreamCreateWithCUMask(&sN, (uint32_t)words->size(), words->data()));
+                if (prev) {
+                    B_TRY(hipEventRecord(ev[0], prev));
+                    B_TRY(hipStreamWaitEvent(sN, ev[0], 0));
+                }
+                B_TRY(launch_tick(d, sN));
+                if (prev) { B_TRY(hipStreamSynchronize(prev)); B_TRY(hipStreamDestroy(prev)); }
+                prev = sN;
+            }
+            if (prev) { B_TRY(hipStreamSynchronize(prev)); B_TRY(hipStreamDestroy(prev)); }
+            t1 = now();
+            *create_ns = ns(t0, t1) / n;
+        }
+    }
+done:
+#undef B_TRY
+    if (ev[0]) (void)hipEventDestroy(ev[0]);
+    if (ev[1]) (void)hipEventDestroy(ev[1]);
+    (void)hipDeviceSynchronize();
+    (void)hipFree(d);
+    return st;
+}

@@ -1,0 +1,237 @@
+// Fused multi-head attention for short sequences (S <= 512, head size 32 or 64):
+//   out[b, s, h*d + j] = sum_t softmax_t(q_s . k_t / sqrt(d)) v_t[j]
+// with q, k, v read from one [B][S][3*Hd] tensor ([q | k | v], head-major).
+//
+// One workgroup of NW wavefronts handles NW*16 query rows of one (batch, head).  Per wavefront:
+//   1. scores: for every block of 16 keys, D[key][query] = K_blk (16 x d) . Q^T (d x 16) with
+//      v_mfma_f32_16x16x32 (d/32 instructions); a lane then holds, for its query (lane & 15), the 4
+//      keys 4*(lane>>4)..+3 of every key block -- the whole score row stays in registers;
+//   2. softmax over keys: in-lane over blocks and the 4 values, then across the 4 lane groups that
+//      share a query (xor-shuffles by 16 and 32); fp32 throughout;
+//   3. out^T = V^T . P^T: the contraction index of one MFMA covers two key blocks; the lane's own 8
+//      probabilities (4 per block) are already the column operand it must supply, and V^T is read from
+//      an LDS copy transposed on load so that the matching 4 keys are 8 contiguous bytes.
+// Probabilities are rounded to the 16-bit type for the second product, scores are never stored.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace eclip {
+
+namespace {
+
+template <typename T> struct MmaA;
+template <> struct MmaA<bf16_t> {
+    __device__ static __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct MmaA<f16_t> {
+    __device__ static __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
+
+struct AttnDev {
+    const uint16_t *qkv;
+    uint16_t *y;
+    float *y32;
+    int B, S, Hd, heads, Sp, ldv;   // Sp = S rounded up to 32; ldv = LDS pitch of V^T in elements
+    float scale;
+};
+
+// KB = number of 16-key blocks held in registers (Sp / 16 <= KB)
+template <typename T, int D, int KB, int NW>
+__global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t vt[];    // [D][ldv]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qblocks = (p.S + NW * 16 - 1) / (NW * 16);
+    const int qb = blockIdx.x % qblocks;
+    const int bh = blockIdx.x / qblocks;
+    const int h = bh % p.heads, b = bh / p.heads;
+    const long row0 = (long)b * p.S;
+    const int ld = 3 * p.Hd;
+    const uint16_t *qp = p.qkv + h * D;
+    const uint16_t *kp = p.qkv + p.Hd + h * D;
+    const uint16_t *vp = p.qkv + 2 * p.Hd + h * D;
+
+    // ---- V^T into LDS: thread loads 8 consecutive head dims of one key, scatters them to 8 rows
+    for (int c = tid; c < p.Sp * (D / 8); c += NW * 64) {
+        const int key = c / (D / 8), j0 = (c % (D / 8)) * 8;
+        uint4 q = make_uint4(0, 0, 0, 0);
+        if (key < p.S) q = *reinterpret_cast<const uint4 *>(vp + (row0 + key) * ld + j0);
+        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            vt[(j0 + 2 * i) * p.ldv + key] = (uint16_t)(w[i] & 0xffffu);
+            vt[(j0 + 2 * i + 1) * p.ldv + key] = (uint16_t)(w[i] >> 16);
+        }
+    }
+    __syncthreads();
+
+    const int q_row = qb * NW * 16 + wave * 16 + (lane & 15);      // this lane's query
+    const int g = lane >> 4;                                        // lane group: contraction chunk / key quad
+    const bool q_ok = q_row < p.S;
+
+    // ---- Q fragments (column operand): 8 consecutive head dims per lane and 32-wide K step
+    uint4 qf[D / 32];
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) {
+        qf[ks] = make_uint4(0, 0, 0, 0);
+        if (q_ok) qf[ks] = *reinterpret_cast<const uint4 *>(qp + (row0 + q_row) * ld + ks * 32 + g * 8);
+    }
+
+    // ---- scores
+    f32x4 sc[KB];
+    const int nkb = p.Sp / 16;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        sc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (kb < nkb) {
+            const int key = kb * 16 + (lane & 15);
+#pragma unroll
+            for (int ks = 0; ks < D / 32; ++ks) {
+                uint4 kf = make_uint4(0, 0, 0, 0);
+                if (key < p.S) kf = *reinterpret_cast<const uint4 *>(kp + (row0 + key) * ld + ks * 32 + g * 8);
+                sc[kb] = MmaA<T>::run(kf, qf[ks], sc[kb]);
+            }
+        }
+    }
+
+    // ---- softmax over keys (lane holds keys kb*16 + 4*g + r)
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+        if (kb < nkb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int key = kb * 16 + 4 * g + r;
+                const float v = key < p.S ? sc[kb][r] * p.scale : -INFINITY;
+                sc[kb][r] = v;
+                mx = fmaxf(mx, v);
+            }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float sum = 0.0f;
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+        if (kb < nkb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float e = __expf(sc[kb][r] - mx);      // exp(-inf) = 0 for padded keys
+                sc[kb][r] = e;
+                sum += e;
+            }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.0f / sum;
+
+    // ---- out^T[j][query] = sum_key V^T[j][key] * P[query][key]
+    f32x4 o[D / 16];
+#pragma unroll
+    for (int jb = 0; jb < D / 16; ++jb) o[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kp2 = 0; kp2 < KB / 2; ++kp2) {
+        if (2 * kp2 < nkb) {
+            // contraction slot e of lane group g  <->  key (2*kp2 + e/4)*16 + 4*g + e%4
+            uint4 pf;
+            pf.x = Cvt<T>::to_bits(sc[2 * kp2][0] * inv) | (Cvt<T>::to_bits(sc[2 * kp2][1] * inv) << 16);
+            pf.y = Cvt<T>::to_bits(sc[2 * kp2][2] * inv) | (Cvt<T>::to_bits(sc[2 * kp2][3] * inv) << 16);
+            pf.z = Cvt<T>::to_bits(sc[2 * kp2 + 1][0] * inv) | (Cvt<T>::to_bits(sc[2 * kp2 + 1][1] * inv) << 16);
+            pf.w = Cvt<T>::to_bits(sc[2 * kp2 + 1][2] * inv) | (Cvt<T>::to_bits(sc[2 * kp2 + 1][3] * inv) << 16);
+#pragma unroll
+            for (int jb = 0; jb < D / 16; ++jb) {
+                const uint16_t *vr = vt + (jb * 16 + (lane & 15)) * p.ldv + 4 * g;
+                const uint2 lo = *reinterpret_cast<const uint2 *>(vr + (2 * kp2) * 16);
+                const uint2 hi = *reinterpret_cast<const uint2 *>(vr + (2 * kp2 + 1) * 16);
+                o[jb] = MmaA<T>::run(make_uint4(lo.x, lo.y, hi.x, hi.y), pf, o[jb]);
+            }
+        }
+    }
+
+    // lane holds head dims jb*16 + 4*g .. +3 of its query
+    if (q_ok) {
+        const long off = (row0 + q_row) * p.Hd + h * D + 4 * g;
+#pragma unroll
+        for (int jb = 0; jb < D / 16; ++jb) {
+            if (p.y32) {
+                *reinterpret_cast<float4 *>(p.y32 + off + jb * 16) = make_float4(o[jb][0], o[jb][1], o[jb][2], o[jb][3]);
+            } else {
+                uint2 q;
+                q.x = Cvt<T>::to_bits(o[jb][0]) | (Cvt<T>::to_bits(o[jb][1]) << 16);
+                q.y = Cvt<T>::to_bits(o[jb][2]) | (Cvt<T>::to_bits(o[jb][3]) << 16);
+                *reinterpret_cast<uint2 *>(p.y + off + jb * 16) = q;
+            }
+        }
+    }
+}
+
+inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
+inline int ldv_of(int Sp) { return Sp + 8; }
+
+template <typename T, int D, int NW>
+hipError_t launch_d(const AttnDev &d, size_t lds, hipStream_t s)
+{
+    const int qblocks = (d.S + NW * 16 - 1) / (NW * 16);
+    const dim3 grid((unsigned)(d.B * d.heads * qblocks)), block(NW * 64);
+    const int nkb = d.Sp / 16;
+    if (nkb <= 8) hipLaunchKernelGGL((attention_kernel<T, D, 8, NW>), grid, block, lds, s, d);
+    else if (nkb <= 16) hipLaunchKernelGGL((attention_kernel<T, D, 16, NW>), grid, block, lds, s, d);
+    else if (nkb <= 32) hipLaunchKernelGGL((attention_kernel<T, D, 32, NW>), grid, block, lds, s, d);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+template <typename T, int D, int NW>
+hipError_t set_attr()
+{
+    hipError_t e;
+    const int lim = 96 * 1024;
+    if ((e = hipFuncSetAttribute((const void *)attention_kernel<T, D, 8, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)attention_kernel<T, D, 16, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)attention_kernel<T, D, 32, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+}
+
+}  // namespace
+
+size_t attention_lds_bytes(int S, int d) { return (size_t)d * ldv_of(round_up(S, 32)) * sizeof(uint16_t); }
+
+hipError_t attention_init()
+{
+    hipError_t e;
+#define SET(T)                                                         \
+    if ((e = set_attr<T, 32, 1>()) != hipSuccess) return e;            \
+    if ((e = set_attr<T, 32, 4>()) != hipSuccess) return e;            \
+    if ((e = set_attr<T, 64, 1>()) != hipSuccess) return e;            \
+    if ((e = set_attr<T, 64, 4>()) != hipSuccess) return e;
+    SET(bf16_t)
+    SET(f16_t)
+#undef SET
+    return hipSuccess;
+}
+
+hipError_t launch_attention(const AttnArgs &a, int n_cu, hipStream_t s)
+{
+    AttnDev d;
+    d.qkv = (const uint16_t *)a.qkv; d.y = (uint16_t *)a.y; d.y32 = a.y32;
+    d.B = a.B; d.S = a.S; d.Hd = a.Hd; d.heads = a.heads;
+    d.Sp = round_up(a.S, 32);
+    d.ldv = ldv_of(d.Sp);
+    const int D = a.Hd / a.heads;
+    d.scale = 1.0f / sqrtf((float)D);
+    const size_t lds = attention_lds_bytes(a.S, D);
+    // few (batch, head) pairs: one wavefront per workgroup spreads the query blocks over more CUs
+    const long wg4 = (long)a.B * a.heads * ((a.S + 63) / 64);
+    const bool small = wg4 < n_cu;
+#define GO(T)                                                                                  \
+    if (D == 32) return small ? launch_d<T, 32, 1>(d, lds, s) : launch_d<T, 32, 4>(d, lds, s); \
+    if (D == 64) return small ? launch_d<T, 64, 1>(d, lds, s) : launch_d<T, 64, 4>(d, lds, s);
+    if (a.dtype == DT_BF16) { GO(bf16_t) }
+    else { GO(f16_t) }
+#undef GO
+    return hipErrorInvalidValue;
+}
+
+}  // namespace eclip

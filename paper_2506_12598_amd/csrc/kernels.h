@@ -1,0 +1,104 @@
+// Host-callable launchers of the gfx950 kernels.  Every launcher validates nothing: the caller
+// (the model loader) has already checked shapes, alignment and capacity.  Internal layout of all
+// activations is channels-last: [B][H][W][C] for images, [B][S][Hd] for sequences, [B][n] for vectors.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace eclip {
+
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+
+// ---- implicit-GEMM convolution / linear on the matrix cores (16-bit types) -------------------
+// y[m][n] = act(sum_k A[m][k] * w[n][k] + bias[n] + res[m][n]),  m = (b,oh,ow), k = (kh,kw,ci).
+struct ConvGemmArgs {
+    const void *x;       // [B][H][W][Cin]           Cin % 8 == 0
+    const void *w;       // [Cout][KH][KW][Cin]
+    const void *bias;    // [Cout] or null
+    const void *res;     // [M][Cout] or null
+    void *y;             // [M][Cout] in the model dtype, or null when y32 is used
+    float *y32;          // [M][Cout] float output, or null
+    float *ws;           // split-K partial sums, >= splits*M*Cout floats when splits > 1
+    unsigned *counters;  // one zero-initialised counter per output tile when splits > 1
+    int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, act, dtype;
+};
+struct GemmPlan {
+    int variant;   // tile shape, see conv_gemm_tile()
+    int splits;    // K is cut into this many slices, reduced by the last-arriving workgroup
+    int tiles;     // output tiles = workgroups per slice
+};
+void conv_gemm_tile(int variant, int *bm, int *bn);
+// Chooses tile shape and K split for a stream restricted to n_cu compute units.
+GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats, size_t n_counters);
+hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &p, hipStream_t s);
+
+// ---- float32 direct convolution / linear (plain FMA) -------------------------------------------
+struct ConvF32Args {
+    const float *x;      // [B][H][W][Cin]
+    const float *w;      // [KH][KW][Cin][Cout]
+    const float *bias, *res;
+    float *y;            // [M][Cout]
+    int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, act;
+};
+hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t s);
+
+// ---- memory-bound kernels ---------------------------------------------------------------------
+struct DwConvArgs {
+    const void *x, *w, *bias, *res;   // x [B][H][W][C]; w [KH][KW][C]
+    void *y;
+    int B, H, W, C, Ho, Wo, KH, KW, stride, pad, act, dtype;
+};
+hipError_t launch_dwconv(const DwConvArgs &a, int n_cu, hipStream_t s);
+
+struct PoolArgs {
+    const void *x; void *y;
+    int B, H, W, C, Ho, Wo, KH, KW, stride, pad, dtype;
+};
+hipError_t launch_maxpool(const PoolArgs &a, int n_cu, hipStream_t s);
+// mean over HW: x [B][HW][C] -> y [B][C] (model dtype) or y32 (float)
+hipError_t launch_gap(const void *x, void *y, float *y32, int B, int HW, int C, int dtype, int n_cu, hipStream_t s);
+
+struct RowArgs {
+    const void *x, *res, *gamma, *beta;
+    void *y; float *y32;
+    long rows; int width; float eps; int dtype;
+};
+hipError_t launch_layernorm(const RowArgs &a, int n_cu, hipStream_t s);
+hipError_t launch_softmax(const RowArgs &a, int n_cu, hipStream_t s);
+
+struct EltArgs {
+    const void *x, *bias, *res; void *y; float *y32;
+    long rows; int width; int act; int dtype;
+};
+hipError_t launch_eltwise(const EltArgs &a, int n_cu, hipStream_t s);
+
+struct EmbedArgs {
+    const int32_t *ids; const void *tok, *pos, *typ; void *y;
+    int B, S, Hd, vocab, dtype;
+};
+hipError_t launch_embed(const EmbedArgs &a, int n_cu, hipStream_t s);
+
+// ---- fused attention ---------------------------------------------------------------------------
+struct AttnArgs {
+    const void *qkv;     // [B][S][3*Hd]
+    void *y; float *y32; // [B][S][Hd]
+    int B, S, Hd, heads, dtype;
+};
+size_t attention_lds_bytes(int S, int d);
+hipError_t launch_attention(const AttnArgs &a, int n_cu, hipStream_t s);
+hipError_t attention_init();   // raises the dynamic LDS limit once per process
+
+// ---- layout conversion at the model boundary ------------------------------------------------------
+// [B][C][H][W] (model dtype) -> [B][H][W][Cp], channels C..Cp-1 zero
+hipError_t launch_nchw_to_nhwc(const void *x, void *y, int B, int C, int H, int W, int Cp, int dtype, hipStream_t s);
+// internal [B][H][W][C] -> float32 [B][C][H][W]
+hipError_t launch_nhwc_to_nchw_f32(const void *x, float *y, int B, int C, int H, int W, int dtype, hipStream_t s);
+// n elements of the model dtype -> float32
+hipError_t launch_to_f32(const void *x, float *y, long n, int dtype, hipStream_t s);
+
+// ---- diagnostics -------------------------------------------------------------------------------
+hipError_t launch_probe(uint32_t *out, int n_blocks, hipStream_t s);
+hipError_t launch_tick(uint32_t *p, hipStream_t s);
+hipError_t launch_fill_u32(uint32_t *p, uint32_t v, long n, hipStream_t s);
+
+}  // namespace eclip

@@ -1,0 +1,207 @@
+"""GPU parity: every kernel and every model, through the C ABI, element by element against the CPU oracle.
+
+Tolerances (stated by the build target): float32 configuration max-abs error <= 1e-4; bf16 / fp16
+configurations max-abs error <= 2e-2 x (max - min of the oracle output).  Single kernels whose only
+rounding is float32 accumulation are held to a much tighter bound so that a dropped K-slice, a wrong tap
+or a transposed operand cannot hide inside the model-level tolerance.
+"""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import forward as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from gpu_util import GpuModel, run_gpu, rel_to_range, shared_pool  # noqa: E402
+
+TOL_16 = 2e-2
+TOL_F32 = 1e-4
+DTS = [wl.DT_BF16, wl.DT_F16]
+
+
+def check(model, batch=1, tol=None, dist="normal", seed=None):
+    x = wl.make_input(model, batch, seed=seed, dist=dist)
+    exp = orc.run_model(model, x)
+    got = run_gpu(model, x)
+    assert got.shape == exp.shape
+    assert np.isfinite(got).all()
+    if model.dtype == wl.DT_F32:
+        err = float(np.abs(got - exp).max())
+        assert err <= (tol or TOL_F32), f"max abs err {err}"
+    else:
+        err = rel_to_range(got, exp)
+        assert err <= (tol or TOL_16), f"err/range {err}"
+    return err
+
+
+# ---------------- configuration 1: tiny CNN, float32 ------------------------------------------------------
+def test_tiny_cnn_f32_config():
+    check(wl.tiny_cnn(seed=0), batch=1, dist="uniform")
+
+
+def test_tiny_cnn_f32_batch4():
+    check(wl.tiny_cnn(seed=0), batch=4, dist="uniform")
+
+
+# ---------------- implicit-GEMM convolution ----------------------------------------------------------------
+CONV_CASES = [
+    # cin cout  h   w  k  s  p  res  act           what it exercises
+    (16, 32, 20, 20, 3, 1, 1, False, wl.ACT_RELU),    # several 64x64 tiles, ragged M (400)
+    (3, 64, 40, 40, 7, 2, 3, False, wl.ACT_RELU),     # stem: 3 input channels padded to 8, K tail (392)
+    (64, 128, 14, 14, 1, 2, 0, False, wl.ACT_NONE),   # 1x1 stride-2 projection
+    (64, 64, 12, 12, 3, 1, 1, True, wl.ACT_RELU),     # residual + ReLU epilogue
+    (256, 512, 7, 7, 3, 2, 1, False, wl.ACT_RELU),    # tiny M (16), deep K (2304): split-K path
+    (512, 512, 7, 7, 3, 1, 1, True, wl.ACT_RELU),     # M = 49, K = 4608: split-K with residual
+    (32, 40, 9, 11, 3, 1, 1, False, wl.ACT_RELU6),    # ragged N (40) and M (99)
+    (8, 8, 5, 5, 5, 1, 2, False, wl.ACT_NONE),        # window as large as the image
+    (128, 256, 56, 56, 1, 1, 0, False, wl.ACT_RELU),  # many tiles: 128x128 variant
+]
+
+
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("cin,cout,h,w,k,s,p,res,act", CONV_CASES)
+def test_conv_gemm(cin, cout, h, w, k, s, p, res, act, dt):
+    m = wl.single_layer("conv", dt, seed=cin + cout + k, cin=cin, cout=cout, h=h, w=w, k=k, stride=s, pad=p,
+                        residual=res, act=act, bias_std=0.5)
+    # the only rounding on the GPU side is float32 accumulation (the output is written as float32), plus a
+    # 16-bit intermediate when the residual operand is itself a computed tensor
+    check(m, batch=2, tol=4e-3 if res else 2e-4)
+
+
+def test_conv_identity_kernel_returns_input_exactly():
+    c, h = 16, 10
+    m = wl.single_layer("conv", wl.DT_BF16, cin=c, cout=c, h=h, w=h, k=3, pad=1)
+    L = m.layers[0]
+    m.weights[:] = 0
+    for i in range(c):
+        m.weights[L.w_off + (i * c + i) * 9 + 4] = 1.0
+    x = wl.make_input(m, 1)
+    assert np.array_equal(run_gpu(m, x), x.astype(np.float64))
+
+
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+@pytest.mark.parametrize("c,h,s", [(32, 14, 1), (96, 15, 2), (20, 9, 1)])
+def test_depthwise_conv(c, h, s, dt):
+    m = wl.single_layer("conv", dt, seed=c, cin=c, cout=c, h=h, w=h, k=3, stride=s, pad=1, groups=c,
+                        act=wl.ACT_RELU6, bias_std=0.5)
+    check(m, batch=2, tol=1e-5 if dt == wl.DT_F32 else 4e-3)
+
+
+# ---------------- linear -------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("rows,k,n,act,res", [(128, 768, 2304, wl.ACT_NONE, False), (48, 512, 128, wl.ACT_GELU, False),
+                                              (100, 128, 128, wl.ACT_NONE, True), (1, 4096, 1000, wl.ACT_RELU, False),
+                                              (7, 64, 10, wl.ACT_NONE, False)])
+def test_linear(rows, k, n, act, res, dt):
+    m = wl.single_layer("linear", dt, seed=rows, rows=rows, k=k, n=n, act=act, residual=res and n == k, bias_std=0.3,
+                        std=1.0 / np.sqrt(k))
+    check(m, batch=2, tol=2e-4)
+
+
+# ---------------- pooling, row kernels, element-wise, embedding ------------------------------------------------
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+def test_maxpool_and_gap(dt):
+    for k, s, p, c, h in [(3, 2, 1, 64, 29), (2, 2, 0, 24, 16), (3, 2, 1, 12, 9)]:
+        m = wl.single_layer("maxpool", dt, c=c, h=h, w=h + 1, k=k, stride=s, pad=p)
+        x = wl.make_input(m, 2)
+        assert np.array_equal(run_gpu(m, x), orc.run_model(m, x))      # selection only: exact
+    for c, h in [(512, 7), (40, 5), (1280, 3)]:
+        m = wl.single_layer("gap", dt, c=c, h=h, w=h)
+        check(m, batch=3, tol=1e-5)
+
+
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+@pytest.mark.parametrize("rows,width", [(128, 768), (50, 1024), (9, 100), (3, 4096)])
+def test_layernorm(rows, width, dt):
+    m = wl.single_layer("layernorm", dt, seed=width, rows=rows, width=width, eps=1e-5, affine_std=0.2, residual=True)
+    check(m, batch=2, tol=4e-3 if dt != wl.DT_F32 else 1e-5)
+    m = wl.single_layer("layernorm", dt, seed=width, rows=rows, width=width, eps=1e-12)
+    x = wl.make_input(m, 1)
+    got = run_gpu(m, x)
+    np.testing.assert_allclose(got.mean(-1), 0, atol=1e-4)
+    np.testing.assert_allclose(got.var(-1), 1, atol=1e-3)
+    check(m, batch=1, tol=1e-5)
+
+
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+@pytest.mark.parametrize("rows,width", [(96, 128), (40, 384), (5, 30)])
+def test_softmax(rows, width, dt):
+    m = wl.single_layer("softmax", dt, seed=width, rows=rows, width=width)
+    x = wl.make_input(m, 2) * 4
+    x = wl.round_to_dtype(x, dt)
+    exp = orc.run_model(m, x)
+    got = run_gpu(m, x)
+    np.testing.assert_allclose(got.sum(-1), 1, atol=1e-5)
+    assert np.abs(got - exp).max() <= 5e-6
+
+
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+def test_eltwise_and_embed(dt):
+    for act in (wl.ACT_NONE, wl.ACT_RELU, wl.ACT_RELU6, wl.ACT_GELU):
+        m = wl.single_layer("eltwise", dt, seed=act, rows=37, width=72, act=act, residual=True, bias_std=1.0)
+        check(m, batch=2, tol=1e-5)
+    m = wl.single_layer("embed", dt, seed=3, hidden=64, seq=19, vocab=500, n_pos=32, std=1.0)
+    x = wl.make_input(m, 3)
+    exp = orc.run_model(m, x)
+    got = run_gpu(m, x)
+    assert np.abs(got - exp).max() <= (1e-6 if dt == wl.DT_F32 else 2.0 ** -7 * np.abs(exp).max())
+
+
+# ---------------- attention -----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("seq,hidden,heads,batch", [(128, 768, 12, 1), (48, 128, 4, 2), (384, 256, 4, 2), (17, 64, 2, 3),
+                                                    (512, 64, 1, 1)])
+def test_attention(seq, hidden, heads, batch, dt):
+    m = wl.single_layer("attention", dt, seed=seq, seq=seq, hidden=hidden, heads=heads)
+    check(m, batch=batch, tol=6e-3)
+
+
+def test_attention_equal_keys_gives_mean_of_values():
+    m = wl.single_layer("attention", wl.DT_F16, seq=40, hidden=64, heads=2)
+    x = wl.make_input(m, 1)
+    x[:, :, 64:128] = x[:, :1, 64:128]
+    got = run_gpu(m, x)
+    exp = np.broadcast_to(x[:, :, 128:].astype(np.float64).mean(1, keepdims=True), got.shape)
+    assert np.abs(got - exp).max() <= 2e-3
+
+
+# ---------------- whole models (small sizes, every layer type, several tiles, ragged tails) ------------------------
+def test_resnet18_small_bf16():
+    check(wl.resnet(18, seed=1, hw=64), batch=1)
+
+
+def test_resnet18_small_batch3_fp16():
+    check(wl.resnet(18, seed=2, hw=48, dtype=wl.DT_F16), batch=3)
+
+
+def test_resnet50_small_bf16():
+    check(wl.resnet(50, seed=3, hw=64), batch=2)
+
+
+def test_vgg16_small_bf16():
+    check(wl.vgg16(seed=6, hw=32, width=16, fc=256), batch=2)
+
+
+def test_mobilenetv2_small_bf16():
+    check(wl.mobilenetv2(seed=7, hw=64), batch=2)
+
+
+def test_bert_small_fp16_and_bf16():
+    check(wl.bert(2, 128, 4, 512, 48, vocab=1000, seed=4), batch=2)
+    check(wl.bert(2, 128, 2, 256, 40, vocab=1000, seed=9, dtype=wl.DT_BF16), batch=1)
+
+
+# ---------------- full-size configurations in the benchmark's launch configuration -----------------------------------
+def test_resnet18_full_size_config():
+    for seed in (1, 2):
+        check(wl.resnet(18, seed=seed), batch=1)
+
+
+def test_bert_base_layer_shapes_full_width():
+    # BERT-base shapes (hidden 768, 12 heads, FFN 3072, S = 128) with 2 of the 12 layers: the oracle finishes in seconds
+    check(wl.bert(2, 768, 12, 3072, 128, vocab=30522, seed=4), batch=1)

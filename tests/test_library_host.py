@@ -1,0 +1,189 @@
+"""Host-side tests of libeclip that need no GPU: exported symbols, the exact allocation solver against
+the exhaustive-search oracle (bit-exact decisions), the mask layout against the paper's worked example,
+descriptor validation and error paths."""
+import os
+import re
+
+import pytest
+
+import workloads as wl
+import paper_2506_12598_amd as ec
+from oracle import alloc as oa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "eclip.h")).read()
+    declared = set(re.findall(r"\b(eclip_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 15
+    for name in declared:
+        assert hasattr(ec.lib, name), f"{name} declared in eclip.h but not exported"
+    assert declared == set(ec.EXPORTS), "binding and header disagree on the entry points"
+
+
+def solve_lib(p):
+    return ec.eclip_alloc_solve(p.total_cus, p.configs, [w.n_kernels for w in p.workers], [w.beta for w in p.workers],
+                                p.switch_max, p.overlap_mode, p.alpha_ppm, p.granule)
+
+
+CASES = []
+for seed in range(12):
+    for mode in (oa.OVERLAP_EXCESS, oa.OVERLAP_LITERAL, oa.OVERLAP_TABLE):
+        CASES.append((seed, 2, [3, 3], [32, 64, 128, 192, 256], 256, 1 + seed % 2, mode, "scaling"))
+        CASES.append((50 + seed, 3, [2, 2, 2], [15, 30, 45, 60], 60, seed % 3, mode, "random"))
+        CASES.append((90 + seed, 2, [4, 2], [32, 64, 128], 128, 1, mode, "ties"))
+        CASES.append((130 + seed, 1, [6], [16, 48, 96, 256], 256, 2, mode, "scaling"))
+        CASES.append((170 + seed, 4, [1, 2, 1, 2], [64, 128, 256], 256, 1, mode, "scaling"))
+
+
+@pytest.mark.parametrize("seed,nw,units,configs,total,sm,mode,shape", CASES)
+def test_solver_matches_exhaustive_oracle_bit_exact(seed, nw, units, configs, total, sm, mode, shape):
+    p = wl.random_problem(seed, nw, units, configs, total, sm, mode, shape)
+    exp_assign, exp_obj, exp_sw = oa.solve_exhaustive(p)
+    got_assign, got_obj, got_sw = solve_lib(p)
+    assert got_assign == exp_assign
+    assert got_obj == exp_obj
+    assert got_sw == exp_sw
+
+
+def test_solver_hand_worked_example():
+    a = wl.Worker([1, 1], [[100, 60, 50, 45], [80, 70, 65, 64]])
+    b = wl.Worker([1], [[200, 110, 80, 60]])
+    assign, obj, sw = solve_lib(wl.AllocProblem(60, [15, 30, 45, 60], [a, b], 1, oa.OVERLAP_EXCESS))
+    assert (assign, obj, sw) == ([[1, 1], [1]], 28800, [0, 0])
+    assign, obj, sw = solve_lib(wl.AllocProblem(60, [15, 30, 45, 60], [a, b], 1, oa.OVERLAP_LITERAL))
+    assert (assign, obj, sw) == ([[1, 0], [2]], 56100, [1, 0])
+
+
+def test_solver_scales_to_config_sized_instances_and_respects_budget():
+    # four workers, 24 units each, five configurations: far beyond exhaustive search; check validity and
+    # that the result is no worse than simple feasible assignments evaluated by the oracle
+    p = wl.random_problem(7, 4, [24, 24, 7, 12], [32, 64, 128, 192, 256], 256, 14, oa.OVERLAP_EXCESS, max_kernels=9)
+    assign, obj, sw = solve_lib(p)
+    r = oa.evaluate(p, assign)
+    assert r is not None and r[0] == obj and r[2] == sw and all(s <= 14 for s in sw)
+    for c in range(5):
+        uni = [[c] * len(w.n_kernels) for w in p.workers]
+        assert obj <= oa.evaluate(p, uni)[0]
+
+
+def test_solver_rejects_malformed_problems():
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_solve(256, [64, 32], [[1]], [[[5, 5]]], 1)
+    assert e.value.status == ec.EINVAL and "increasing" in e.value.message
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_solve(256, [32, 64], [[0]], [[[5, 5]]], 1)
+    assert e.value.status == ec.EINVAL
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_solve(256, [32, 64], [[1]], [[[5, 5]]], 1, ec.OVERLAP_TABLE, None, 1)
+    assert e.value.status == ec.EINVAL
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_solve(256, [1, 256], [[4000] * 64], [[[5, 5]] * 64], 14)
+    assert e.value.status == ec.ELIMIT
+
+
+# ---- mask layout (Sec. III-A worked example) ------------------------------------------------------------
+def test_mask_layout_reproduces_paper_example():
+    gold = []
+    for line in open(os.path.join(ROOT, "tests", "golden", "mask_layout_example.txt")):
+        t = line.split()
+        if t and not t[0].startswith("#"):
+            gold.append((int(t[0]), int(t[1]), [int(v) for v in t[2:]]))
+    assert len(gold) == 6
+    for worker, n_cus, ses in gold:
+        words = ec.eclip_mask_layout(60, 15, 2, worker - 1, n_cus // 15)
+        bits = ec.mask_bits(words)
+        assert len(bits) == n_cus
+        assert sorted({b // 15 + 1 for b in bits}) == ses
+        for se in ses:          # whole shader engines only
+            assert all((se - 1) * 15 + j in bits for j in range(15))
+
+
+@pytest.mark.parametrize("total,granule,striped", [(60, 15, 0), (256, 32, 0), (256, 64, 8), (256, 32, 8), (60, 15, 1)])
+def test_mask_layout_two_workers_overlap_only_in_the_excess(total, granule, striped):
+    ng = total // granule
+    for a in range(1, ng + 1):
+        ma = set(ec.mask_bits(ec.eclip_mask_layout(total, granule, 2, 0, a, striped)))
+        assert len(ma) == a * granule
+        if a > 1:      # masks of one worker are nested
+            assert set(ec.mask_bits(ec.eclip_mask_layout(total, granule, 2, 0, a - 1, striped))) < ma
+        for b in range(1, ng + 1):
+            mb = set(ec.mask_bits(ec.eclip_mask_layout(total, granule, 2, 1, b, striped)))
+            assert len(ma & mb) == max(0, a + b - ng) * granule
+
+
+def test_mask_layout_striped_granules_keep_every_xcd_populated():
+    # MI355X: mask bit i lies in XCD i % 8 and shader engine (i / 8) % 4.  stripe = 8, granule = 64: one whole
+    # shader engine of every XCD per granule
+    for worker, se in ((0, 0), (1, 3)):
+        bits = ec.mask_bits(ec.eclip_mask_layout(256, 64, 2, worker, 1, stripe=8))
+        assert len(bits) == 64
+        assert {b % 8 for b in bits} == set(range(8))
+        assert {(b // 8) % 4 for b in bits} == {se}
+    # stripe = 0, granule = 32: one CU of every shader engine of every XCD per granule
+    bits = ec.mask_bits(ec.eclip_mask_layout(256, 32, 2, 0, 1))
+    assert bits == list(range(32))
+    bits = ec.mask_bits(ec.eclip_mask_layout(256, 32, 2, 1, 1))
+    assert bits == list(range(224, 256))
+
+
+def test_mask_layout_errors():
+    for args in [(60, 16, 2, 0, 1), (60, 15, 2, 2, 1), (60, 15, 2, 0, 5), (60, 15, 2, 0, 0), (256, 32, 2, 0, 1, 5)]:
+        with pytest.raises(ec.EclipError) as e:
+            ec.eclip_mask_layout(*args)
+        assert e.value.status == ec.EINVAL
+
+
+# ---- descriptor validation and error paths that need no device -----------------------------------------
+def load_expect(model, status, text=None, **kw):
+    with pytest.raises(ec.EclipError) as e:
+        ec.Model(None, model, wl.to_storage(model.weights, model.dtype), **kw)
+    assert e.value.status == status, e.value
+    if text:
+        assert text in e.value.message, e.value.message
+
+
+def test_valid_descriptors_pass_validation_and_stop_at_the_null_pool():
+    for m in [wl.tiny_cnn(), wl.resnet(18, hw=64), wl.resnet(50, hw=64), wl.vgg16(hw=32, width=16, fc=64),
+              wl.mobilenetv2(hw=64), wl.bert(2, 128, 4, 512, 48, vocab=1000)]:
+        load_expect(m, ec.EINVAL, "pool is null")
+
+
+def test_descriptor_errors():
+    m = wl.resnet(18, hw=64)
+    m.group_of_layer[5] = 3
+    load_expect(m, ec.EINVAL, "group_of_layer")
+    m = wl.resnet(18, hw=64)
+    m.layers[3].in0 = 7
+    load_expect(m, ec.EINVAL, "not an earlier layer")
+    m = wl.resnet(18, hw=64)
+    m.layers[2].h += 1
+    load_expect(m, ec.EINVAL, "expected")
+    m = wl.resnet(18, hw=64)
+    m.layers[4].w_off = len(m.weights) - 3
+    load_expect(m, ec.EINVAL, "outside the weight blob")
+    m = wl.resnet(18, hw=64)
+    load_expect(m, ec.EINVAL, "max_batch", max_batch=0)
+    m = wl.bert(1, 96, 2, 128, 16, vocab=100)        # head size 48
+    load_expect(m, ec.EINVAL, "head size")
+    m = wl.bert(1, 128, 4, 256, 16, vocab=100, dtype=wl.DT_F32)
+    load_expect(m, ec.EINVAL, "16-bit")
+    m = wl.single_layer("conv", cin=12, cout=16, h=8, w=8, k=3, pad=1)
+    load_expect(m, ec.EINVAL, "pool is null")          # the 12-channel network input is padded by the loader
+    m = wl.tiny_cnn(dtype=wl.DT_BF16)
+    m.layers[0].c = 12                                 # a 12-channel tensor feeding a 16-bit conv
+    m.layers[0].w_off = 0
+    load_expect(m, ec.EINVAL)
+
+
+def test_pool_errors_before_any_device_call():
+    with pytest.raises(ec.EclipError) as e:
+        ec.Pool([])
+    assert e.value.status == ec.EINVAL
+    with pytest.raises(ec.EclipError) as e:
+        ec.Pool([([0, 0], -1)])
+    assert e.value.status == ec.EINVAL and "no CU" in e.value.message
+    with pytest.raises(ec.EclipError) as e:
+        ec.Pool([([1], -1)] * 65)
+    assert e.value.status == ec.ELIMIT
