@@ -204,8 +204,10 @@ typedef struct {
 eclip_status eclip_wait(eclip_req *req, uint64_t timeout_ns, eclip_timing *opt_out);
 
 /* Solo latency of each kernel of `group` on pool entry `mask_id` (Sec. III-B, "Minimum CU
- * Threshold Profiling"): median over `iters` timed runs, integer nanoseconds, one value per
- * kernel of the group in execution order (host array).  Runs one untimed forward pass on zero
+ * Threshold Profiling"): median over `iters` timed samples, integer nanoseconds, one value per
+ * kernel of the group in execution order (host array).  A sample is the HIP-event time of 8
+ * back-to-back launches of the kernel on that stream, divided by 8 (an event pair around one
+ * microsecond-scale kernel would mostly time the events).  Runs one untimed forward pass on zero
  * input first so every buffer is initialised.  Must not overlap other requests of this model. */
 eclip_status eclip_profile_group(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
                                  uint32_t iters, uint64_t *ns_per_kernel_out);

@@ -161,10 +161,25 @@ def eltwise(x, bias, res, act, channel_axis):
 
 
 # ---- graph interpreter ---------------------------------------------------------------
-def run_model(model, x_in: np.ndarray, keep_all: bool = False):
+def _round_storage(y: np.ndarray, dtype: int) -> np.ndarray:
+    """Round to bf16 (dtype 1) or fp16 (dtype 2), nearest-even, and return as fp64."""
+    a = np.ascontiguousarray(y, dtype=np.float32)
+    if dtype == 2:
+        return a.astype(np.float16).astype(np.float64)
+    u = a.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape).astype(np.float64)
+
+
+def run_model(model, x_in: np.ndarray, keep_all: bool = False, storage_dtype: int = 0):
     """Forward pass of `model` (a workloads.Model) on a logical-layout input batch.
 
-    Returns the last layer's output as fp64 (or the list of every layer's output)."""
+    Returns the last layer's output as fp64 (or the list of every layer's output).
+
+    `storage_dtype` = 1 (bf16) or 2 (fp16) additionally rounds every layer's output except the last
+    to that type, i.e. it models a path that stores activations in 16 bits between layers while doing
+    all arithmetic exactly.  It separates storage rounding from arithmetic error; the default (0)
+    is the plain definition."""
     W = model.weights
     outs: List[Optional[np.ndarray]] = []
 
@@ -222,6 +237,8 @@ def run_model(model, x_in: np.ndarray, keep_all: bool = False):
             y = eltwise(x, bias, res, L.act, 1 if L.kind == KIND_IMAGE else np.ndim(x) - 1)
         else:
             raise ValueError(f"unknown op {L.op}")
+        if storage_dtype and L is not model.layers[-1]:
+            y = _round_storage(y, storage_dtype)
         outs.append(y)
         if not keep_all:
             # free tensors no later layer reads

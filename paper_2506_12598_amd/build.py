@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeclip.so")
-SOURCES = ["eclip.cpp", "alloc_solver.cpp", "k_gemm.hip", "k_mem.hip", "k_attn.hip"]
+SOURCES = ["eclip.cpp", "alloc_solver.cpp", "k_gemm.hip", "k_wsk.hip", "k_mem.hip", "k_attn.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -1,0 +1,80 @@
+// Pieces shared by the two matrix-core GEMM kernels: the argument block, the MFMA wrappers and the
+// bias / residual / activation epilogue.
+#pragma once
+#include "device_common.h"
+
+namespace eclip {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct GemmDev {
+    const uint16_t *x, *w, *bias, *res;
+    uint16_t *y;
+    float *y32;
+    float *ws;
+    int B, H, W, Cin, Ho, Wo, KH, KW, stride, pad, act;
+    int M, N, K, KT, kt_per, splits, tiles_m;
+    unsigned x_bytes, w_bytes;               // sizes of the x and w tensors (each below 4 GiB)
+};
+
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+    __device__ static __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mma<f16_t> {
+    __device__ static __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+};
+
+// bias + residual + activation + store of 4 consecutive channels n..n+3 of output row m
+template <typename T>
+__device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32,
+                                               int M, int N, int act, int m, int n, f32x4 v, int nvalid = 4)
+{
+    if (m >= M || n >= N) return;
+    const long off = (long)m * N + n;
+    float o[4] = {v[0], v[1], v[2], v[3]};
+    if ((N & 3) == 0 && nvalid == 4) {       // then n + 3 < N and every access below is aligned
+        if (bias) {
+            const uint2 q = *reinterpret_cast<const uint2 *>(bias + n);
+            o[0] += Cvt<T>::from_bits(q.x & 0xffffu); o[1] += Cvt<T>::from_bits(q.x >> 16);
+            o[2] += Cvt<T>::from_bits(q.y & 0xffffu); o[3] += Cvt<T>::from_bits(q.y >> 16);
+        }
+        if (res) {
+            const uint2 q = *reinterpret_cast<const uint2 *>(res + off);
+            o[0] += Cvt<T>::from_bits(q.x & 0xffffu); o[1] += Cvt<T>::from_bits(q.x >> 16);
+            o[2] += Cvt<T>::from_bits(q.y & 0xffffu); o[3] += Cvt<T>::from_bits(q.y >> 16);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[r] = apply_act(act, o[r]);
+        if (y32) {
+            *reinterpret_cast<float4 *>(y32 + off) = make_float4(o[0], o[1], o[2], o[3]);
+        } else {
+            uint2 q;
+            q.x = Cvt<T>::to_bits(o[0]) | (Cvt<T>::to_bits(o[1]) << 16);
+            q.y = Cvt<T>::to_bits(o[2]) | (Cvt<T>::to_bits(o[3]) << 16);
+            *reinterpret_cast<uint2 *>(y + off) = q;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (r >= nvalid || n + r >= N) break;
+            float t = o[r];
+            if (bias) t += Cvt<T>::from_bits(bias[n + r]);
+            if (res) t += Cvt<T>::from_bits(res[off + r]);
+            t = apply_act(act, t);
+            if (y32) y32[off + r] = t;
+            else y[off + r] = (uint16_t)Cvt<T>::to_bits(t);
+        }
+    }
+}
+
+// wave-split-K kernel (k_wsk.hip)
+hipError_t launch_conv_wsk(const GemmDev &d, int dtype, int variant, int nw, int tiles, hipStream_t s);
+
+}  // namespace eclip

@@ -9,104 +9,41 @@
 // A linear layer is the case KH = KW = 1, H = W = 1 (or W = sequence length).
 //
 // Tiling: one 256-thread workgroup (4 wavefronts of 64) owns a BM x BN output tile and walks K in
-// steps of 32 through LDS.  Global loads for step t+1 are issued before the MFMAs of step t.  Each
-// wavefront owns a (BM/WM) x (BN/WN) sub-tile made of 16x16 blocks, one v_mfma_f32_16x16x32 per block
-// and K step.  The weight tile is fed as the MFMA's row operand and the im2col tile as its column
-// operand, so a lane ends up with 4 consecutive output channels of one output pixel, which is 8
-// contiguous bytes of y.
+// steps of BK through a two-slot LDS ring.  Global loads run two steps ahead of the MFMAs: while step t
+// is multiplied out of LDS slot t%2, the registers already hold step t+1 and the loads of step t+2 are
+// in flight, so one barrier per step suffices and a load has two steps to arrive.  Each wavefront owns
+// a (BM/WM) x (BN/WN) sub-tile made of 16x16 blocks, one v_mfma_f32_16x16x32 per block and 32 k.  The
+// weight tile is fed as the MFMA's row operand and the im2col tile as its column operand, so a lane
+// ends up with 4 consecutive output channels of one output pixel: 8 contiguous bytes of y.
 //
-// Small problems (batch-1 inference: a few dozen tiles) are cut along K into `splits` slices, one
-// workgroup each; slices write float partial sums to a workspace, and the workgroup that arrives last
-// at the tile's counter adds them in slice order (so the result does not depend on arrival order),
-// applies the epilogue and resets the counter.
-#include "device_common.h"
+// Batch-1 inference leaves most layers with a few dozen tiles and a long K.  Those are cut along K
+// into `splits` slices, one workgroup each, which write float partial sums to a workspace; a second,
+// tiny kernel adds the slices in slice order (the sum does not depend on scheduling) and applies the
+// epilogue.  The kernel boundary is what makes the partial sums visible: a device-wide fence inside the
+// GEMM would have to write back the whole L2 of the issuing XCD, which costs far more than a launch.
+#include <cstdio>
+#include <cstdlib>
+
+#include "gemm_common.h"
 #include "kernels.h"
 
 namespace eclip {
 
 namespace {
 
-constexpr int BK = 32;    // K elements per main-loop step
-constexpr int LDK = 40;   // LDS row pitch in elements: 80 bytes keeps 16-byte reads of 16 rows conflict-free
-
-struct GemmDev {
-    const uint16_t *x, *w, *bias, *res;
-    uint16_t *y;
-    float *y32;
-    float *ws;
-    unsigned *counters;
-    int B, H, W, Cin, Ho, Wo, KH, KW, stride, pad, act;
-    int M, N, K, KT, kt_per, splits, tiles_m;
-};
-
-template <typename T> struct Mma;
-template <> struct Mma<bf16_t> {
-    __device__ static __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Mma<f16_t> {
-    __device__ static __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c)
-    {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-};
-
-// bias + residual + activation + store of 4 consecutive channels n..n+3 of output row m
-template <typename T>
-__device__ __forceinline__ void epilogue_store(const GemmDev &p, int m, int n, f32x4 v)
-{
-    if (m >= p.M || n >= p.N) return;
-    const long off = (long)m * p.N + n;
-    float o[4] = {v[0], v[1], v[2], v[3]};
-    const bool vec = ((p.N & 3) == 0);      // then n + 3 < N and every access below is aligned
-    if (vec) {
-        if (p.bias) {
-            const uint2 q = *reinterpret_cast<const uint2 *>(p.bias + n);
-            o[0] += Cvt<T>::from_bits(q.x & 0xffffu); o[1] += Cvt<T>::from_bits(q.x >> 16);
-            o[2] += Cvt<T>::from_bits(q.y & 0xffffu); o[3] += Cvt<T>::from_bits(q.y >> 16);
-        }
-        if (p.res) {
-            const uint2 q = *reinterpret_cast<const uint2 *>(p.res + off);
-            o[0] += Cvt<T>::from_bits(q.x & 0xffffu); o[1] += Cvt<T>::from_bits(q.x >> 16);
-            o[2] += Cvt<T>::from_bits(q.y & 0xffffu); o[3] += Cvt<T>::from_bits(q.y >> 16);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) o[r] = apply_act(p.act, o[r]);
-        if (p.y32) {
-            *reinterpret_cast<float4 *>(p.y32 + off) = make_float4(o[0], o[1], o[2], o[3]);
-        } else {
-            uint2 q;
-            q.x = Cvt<T>::to_bits(o[0]) | (Cvt<T>::to_bits(o[1]) << 16);
-            q.y = Cvt<T>::to_bits(o[2]) | (Cvt<T>::to_bits(o[3]) << 16);
-            *reinterpret_cast<uint2 *>(p.y + off) = q;
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            if (n + r >= p.N) break;
-            float t = o[r];
-            if (p.bias) t += Cvt<T>::from_bits(p.bias[n + r]);
-            if (p.res) t += Cvt<T>::from_bits(p.res[off + r]);
-            t = apply_act(p.act, t);
-            if (p.y32) p.y32[off + r] = t;
-            else p.y[off + r] = (uint16_t)Cvt<T>::to_bits(t);
-        }
-    }
-}
-
-template <typename T, int BM, int BN, int WM, int WN>
+template <typename T, int BM, int BN, int BK, int WM, int WN, int RS>
 __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
 {
     static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    static_assert(RS % 2 == 0, "register stages alternate between the two LDS slots");
+    constexpr int LDK = BK + 8;              // row pitch: 16-byte reads of 16 consecutive rows hit distinct banks
+    constexpr int CPR = BK / 8;              // 16-byte chunks per row
     constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
-    constexpr int A_CH = BM * 4, B_CH = BN * 4;          // 16-byte chunks per K step
+    constexpr int A_CH = BM * CPR, B_CH = BN * CPR;
     constexpr int A_IT = (A_CH + 255) / 256, B_IT = (B_CH + 255) / 256;
 
-    __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDK];
-    __shared__ int s_last;
+    __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN * LDK];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -115,39 +52,45 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     const int m_base = tile_m * BM, n_base = tile_n * BN;
 
     // ---- per-thread, per-chunk addressing that does not change along K
+    // Operands are read through buffer descriptors: a lane whose chunk is padding, beyond M / N or beyond K
+    // is given an offset past the end of the buffer, for which the hardware returns zeros.  This keeps the
+    // loads free of branches, so the loads of different K steps are counted apart by the hardware.
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (int)p.w_bytes, 0x00020000);
+    constexpr unsigned OOB = 0xffffffffu;
     bool a_ok[A_IT];
-    long a_base[A_IT];
+    unsigned a_base[A_IT];                   // byte offset of the image the row belongs to
     int a_ih0[A_IT], a_iw0[A_IT];
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
         const int c = tid + it * 256;
-        const int m = m_base + (c >> 2);
+        const int m = m_base + c / CPR;
         a_ok[it] = (c < A_CH) && (m < p.M);
         const int mm = a_ok[it] ? m : 0;
         const int b = mm / HoWo, r = mm - b * HoWo;
         const int oh = r / p.Wo, ow = r - oh * p.Wo;
-        a_base[it] = (long)b * p.H * p.W * p.Cin;
+        a_base[it] = (unsigned)b * (unsigned)(p.H * p.W * p.Cin) * 2u;
         a_ih0[it] = oh * p.stride - p.pad;
         a_iw0[it] = ow * p.stride - p.pad;
     }
     bool b_ok[B_IT];
-    long b_base[B_IT];
+    unsigned b_base[B_IT];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
         const int c = tid + it * 256;
-        const int n = n_base + (c >> 2);
+        const int n = n_base + c / CPR;
         b_ok[it] = (c < B_CH) && (n < p.N);
-        b_base[it] = (long)(b_ok[it] ? n : 0) * p.K;
+        b_base[it] = (unsigned)(b_ok[it] ? n : 0) * (unsigned)p.K * 2u;
     }
-    const int kc = (tid & 3) * 8;     // same for every chunk of this thread: 256 % 4 == 0
+    const int kc = (tid % CPR) * 8;          // same for every chunk of this thread: 256 % CPR == 0
+    const bool pointwise = (p.KH * p.KW == 1);
 
-    uint4 ra[A_IT], rb[B_IT];
-    auto load_tile = [&](int kt) {
+    auto load_tile = [&](int kt, uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
         const int k = kt * BK + kc;
         const bool k_ok = k < p.K;
         int kh = 0, kw = 0, ci = k;
-        if (p.KH * p.KW != 1) {
+        if (!pointwise) {
             const int tap = k / p.Cin;
             ci = k - tap * p.Cin;
             kh = tap / p.KW;
@@ -155,17 +98,29 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
         }
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
-            uint4 v = make_uint4(0, 0, 0, 0);
             const int ih = a_ih0[it] + kh, iw = a_iw0[it] + kw;
-            if (a_ok[it] && k_ok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W)
-                v = *reinterpret_cast<const uint4 *>(p.x + a_base[it] + ((long)ih * p.W + iw) * p.Cin + ci);
-            ra[it] = v;
+            const bool ok = a_ok[it] && k_ok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+            const unsigned off = ok ? a_base[it] + (unsigned)((ih * p.W + iw) * p.Cin + ci) * 2u : OOB;
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+            ra[it] = make_uint4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (b_ok[it] && k_ok) v = *reinterpret_cast<const uint4 *>(p.w + b_base[it] + k);
-            rb[it] = v;
+            const unsigned off = (b_ok[it] && k_ok) ? b_base[it] + (unsigned)k * 2u : OOB;
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
+            rb[it] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+    };
+    auto store_tile = [&](int slot, const uint4 (&ra)[A_IT], const uint4 (&rb)[B_IT]) {
+#pragma unroll
+        for (int it = 0; it < A_IT; ++it) {
+            const int c = tid + it * 256;
+            if (c < A_CH) *reinterpret_cast<uint4 *>(&sA[slot][(c / CPR) * LDK + kc]) = ra[it];
+        }
+#pragma unroll
+        for (int it = 0; it < B_IT; ++it) {
+            const int c = tid + it * 256;
+            if (c < B_CH) *reinterpret_cast<uint4 *>(&sB[slot][(c / CPR) * LDK + kc]) = rb[it];
         }
     };
 
@@ -179,33 +134,43 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     const int kt_end = min(p.KT, kt_begin + p.kt_per);
     const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
 
-    if (kt_begin < kt_end) load_tile(kt_begin);
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
+    // RS register sets: set (t - kt_begin) % RS carries K step t, so RS steps of loads are in flight
+    uint4 ra[RS][A_IT], rb[RS][B_IT];
 #pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-            const int c = tid + it * 256;
-            if (c < A_CH) *reinterpret_cast<uint4 *>(&sA[(c >> 2) * LDK + kc]) = ra[it];
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) {
-            const int c = tid + it * 256;
-            if (c < B_CH) *reinterpret_cast<uint4 *>(&sB[(c >> 2) * LDK + kc]) = rb[it];
-        }
-        __syncthreads();
-        if (kt + 1 < kt_end) load_tile(kt + 1);
+    for (int r = 0; r < RS; ++r) load_tile(kt_begin + r < kt_end ? kt_begin + r : p.KT, ra[r], rb[r]);
 
-        uint4 fa[TM], fb[TN];
+    auto compute = [&](int slot) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[i] = *reinterpret_cast<const uint4 *>(&sA[(wm * (BM / WM) + i * 16 + frag_row) * LDK + frag_k]);
+        for (int ks = 0; ks < BK / 32; ++ks) {
+            uint4 fa[TM], fb[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[j] = *reinterpret_cast<const uint4 *>(&sB[(wn * (BN / WN) + j * 16 + frag_row) * LDK + frag_k]);
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const uint4 *>(&sA[slot][(wm * (BM / WM) + i * 16 + frag_row) * LDK + ks * 32 + frag_k]);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *reinterpret_cast<const uint4 *>(&sB[slot][(wn * (BN / WN) + j * 16 + frag_row) * LDK + ks * 32 + frag_k]);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[j], fa[i], acc[i][j]);
-        __syncthreads();
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[j], fa[i], acc[i][j]);
+        }
+    };
+
+    // LDS slot (t - kt_begin) % 2 is rewritten at step t only after every wavefront has passed the barrier
+    // of step t-1, i.e. after all of them finished reading it at step t-2.  RS is even, so the slot of
+    // register set r is r % 2.
+    // The loop body is branch-free: steps at or beyond kt_end load zeros (k >= K in load_tile's terms is
+    // forced by passing KT) and multiply them, which costs at most RS-1 idle steps at the end of a slice
+    // and lets the compiler wait for exactly one step's loads at a time.
+    for (int kt = kt_begin; kt < kt_end; kt += RS) {
+#pragma unroll
+        for (int r = 0; r < RS; ++r) {
+            store_tile(r & 1, ra[r], rb[r]);
+            __syncthreads();
+            const int nxt = kt + r + RS;
+            load_tile(nxt < kt_end ? nxt : p.KT, ra[r], rb[r]);
+            compute(r & 1);
+        }
     }
 
     // lane owns output pixel m0 + (lane & 15) and channels n0 + 4*(lane >> 4) .. +3 of each 16x16 block
@@ -216,11 +181,15 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) epilogue_store<T>(p, m_l + i * 16, n_l + j * 16, acc[i][j]);
+            for (int j = 0; j < TN; ++j)
+                epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_l + i * 16, n_l + j * 16, acc[i][j]);
         return;
     }
-
-    // ---- split-K: publish this slice, the last slice to arrive reduces
+    // split-K: this slice's partial sums go to ws[z][m][n]; a second kernel adds the slices.  (A single-kernel
+    // form, in which the last slice to arrive at a per-tile counter does the sum, was measured and dropped:
+    // across XCDs it needs either a device-scope fence, i.e. a write-back of the issuing XCD's whole L2 per
+    // workgroup, or write-through stores and cache-bypassing loads for every partial sum; both cost several
+    // times the second launch.)
     const bool vec = ((p.N & 3) == 0);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -235,97 +204,166 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
                 for (int r = 0; r < 4 && n + r < p.N; ++r) dst[r] = acc[i][j][r];
             }
         }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const unsigned prev = atomicAdd(&p.counters[blockIdx.x], 1u);
-        s_last = (prev == (unsigned)p.splits - 1u);
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int m = m_l + i * 16, n = n_l + j * 16;
-            if (m >= p.M || n >= p.N) continue;
-            f32x4 s = {0.f, 0.f, 0.f, 0.f};
-            for (int zz = 0; zz < p.splits; ++zz) {
-                const float *src = p.ws + ((long)zz * p.M + m) * p.N + n;
-                if (vec) {
-                    const float4 q = *reinterpret_cast<const float4 *>(src);
-                    s[0] += q.x; s[1] += q.y; s[2] += q.z; s[3] += q.w;
-                } else {
-                    for (int r = 0; r < 4 && n + r < p.N; ++r) s[r] += src[r];
-                }
-            }
-            epilogue_store<T>(p, m, n, s);
-        }
-    if (tid == 0) p.counters[blockIdx.x] = 0u;
 }
+
+// y = act(sum_z ws[z] + bias + res): one thread per 4 consecutive channels (one channel when N % 4 != 0).
+// The slices are read eight at a time so that their loads overlap; the additions keep slice order.
+template <typename T>
+__global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int splits, int M, int N, const uint16_t *bias,
+                                                           const uint16_t *res, uint16_t *y, float *y32, int act)
+{
+    const bool vec = ((N & 3) == 0);
+    const int per_row = vec ? N / 4 : N;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)M * per_row) return;
+    const int m = (int)(idx / per_row);
+    const int n = (int)(idx % per_row) * (vec ? 4 : 1);
+    const long slice = (long)M * N;
+    const float *src = ws + (long)m * N + n;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (vec) {
+        for (int z0 = 0; z0 < splits; z0 += 8) {
+            float4 q[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                q[u] = (z0 + u < splits) ? *reinterpret_cast<const float4 *>(src + (long)(z0 + u) * slice) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s[0] += q[u].x; s[1] += q[u].y; s[2] += q[u].z; s[3] += q[u].w; }
+        }
+    } else {
+        for (int z = 0; z < splits; ++z) s[0] += src[z * slice];
+    }
+    epilogue_store<T>(bias, res, y, y32, M, N, act, m, n, s, vec ? 4 : 1);
+}
+
+struct Variant { int bm, bn; };
+constexpr Variant kVariants[3] = {{128, 128}, {64, 64}, {32, 64}};
 
 template <typename T>
 hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
 {
     const dim3 grid((unsigned)pl.tiles, (unsigned)pl.splits), block(256);
     switch (pl.variant) {
-    case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 2, 2>), grid, block, 0, s, d); break;
-    case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 2, 2>), grid, block, 0, s, d); break;
-    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 1, 4>), grid, block, 0, s, d); break;
+    case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, block, 0, s, d); break;
+    case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, block, 0, s, d); break;
+    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, block, 0, s, d); break;
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.splits == 1) return e;
+    const long threads = (long)d.M * ((d.N & 3) == 0 ? d.N / 4 : d.N);
+    hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((threads + 63) / 64)), dim3(64), 0, s, d.ws, pl.splits, d.M, d.N,
+                       d.bias, d.res, d.y, d.y32, d.act);
     return hipGetLastError();
 }
 
 }  // namespace
 
-void conv_gemm_tile(int variant, int *bm, int *bn)
+void conv_gemm_tile(int variant, int *bm, int *bn, int *bk)
 {
-    static const int t[3][2] = {{128, 128}, {64, 64}, {32, 64}};
     const int v = variant < 0 ? 0 : (variant > 2 ? 2 : variant);
-    *bm = t[v][0];
-    *bn = t[v][1];
+    *bm = kVariants[v].bm;
+    *bn = kVariants[v].bn;
+    *bk = v == 0 ? 32 : 64;
 }
 
 static long cdiv(long a, long b) { return (a + b - 1) / b; }
 
-GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats, size_t n_counters)
+GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
 {
-    const long KT = cdiv(K, BK);
-    auto tiles = [&](int v) { int bm, bn; conv_gemm_tile(v, &bm, &bn); return cdiv(M, bm) * cdiv(N, bn); };
-    GemmPlan pl{1, 1, 0};
-    if (tiles(0) >= 2L * n_cu) pl.variant = 0;
-    else if (tiles(1) >= n_cu) pl.variant = 1;
-    else pl.variant = (tiles(1) * 2 <= n_cu || M <= 32) ? 2 : 1;
-    pl.tiles = (int)tiles(pl.variant);
-    if (pl.tiles < n_cu && KT >= 8 && (size_t)pl.tiles <= n_counters) {
-        long want = cdiv(n_cu, pl.tiles);
-        long cap = KT / 4;                       // at least 4 K steps per slice
-        long s = want < cap ? want : cap;
-        if (s > 32) s = 32;
+    auto tiles = [&](int v) { int bm, bn, bk; conv_gemm_tile(v, &bm, &bn, &bk); return cdiv(M, bm) * cdiv(N, bn); };
+    auto wsk_tiles = [&](int v) { int bm, bn; conv_wsk_tile(v, &bm, &bn); return cdiv(M, bm) * cdiv(N, bn); };
+    GemmPlan pl{0, 1, 1, 0, 4};
+    const long ksteps = cdiv(K, 32);
+    // tuning aid: ECLIP_GEMM_FORCE="kind,variant,n" overrides the heuristic; n = K splits (kind 0, clamped to the
+    // workspace) or wavefronts per workgroup (kind 1: 4, 8 or 16)
+    const char *force = getenv("ECLIP_GEMM_FORCE");
+    int f_kind = -1, f_variant = -1, f_n = -1;
+    if (force) sscanf(force, "%d,%d,%d", &f_kind, &f_variant, &f_n);
+    if (f_kind == 1 && f_variant >= 0 && f_variant <= 2 && (f_n == 4 || f_n == 8 || f_n == 16) &&
+        conv_wsk_lds_bytes(f_variant, f_n) <= 128 * 1024) {
+        pl.kind = 1; pl.variant = f_variant; pl.nw = f_n; pl.tiles = (int)wsk_tiles(f_variant);
+        return pl;
+    }
+    if (f_kind == 0 && f_variant >= 0 && f_variant <= 2) {
+        pl.variant = f_variant;
+        pl.tiles = (int)tiles(pl.variant);
+        int bm, bn, bk;
+        conv_gemm_tile(pl.variant, &bm, &bn, &bk);
+        const long KT = cdiv(K, bk);
+        long s = f_n < 1 ? 1 : f_n;
+        if (s > KT) s = KT;
         while (s > 1 && (size_t)(s * M * N) > ws_floats) --s;
-        if (s > 1) {
+        const long kt_per = cdiv(KT, s);
+        pl.splits = (int)cdiv(KT, kt_per);
+        return pl;
+    }
+    // Few tiles (batch-1 convolutions, skinny linear layers).  Measured on MI355X: a kernel costs about
+    // 4.5 us however little it does, and one CU sustains only about 30 GB/s of operand loads, so a layer is
+    // priced as  launches * 4.5 us + (bytes the busiest CU has to pull) / 30 GB/s  for each candidate:
+    //   wave-split-K on 16x64 or 32x64 tiles (one launch, a workgroup pulls its whole (bm+bn) x K panel);
+    //   32x64 tiles cut along K over the grid (two launches, the panels are spread over every CU).
+    if (wsk_tiles(1) <= 2L * n_cu) {
+        const double us_per_launch = 4.5, bytes_per_us = 30e3;
+        auto wsk_cost = [&](int v) {
+            int bm, bn;
+            conv_wsk_tile(v, &bm, &bn);
+            const double rounds = (double)cdiv(wsk_tiles(v), n_cu);
+            return us_per_launch + rounds * (double)(bm + bn) * (double)K * 2.0 / bytes_per_us;
+        };
+        const long t2 = tiles(2);
+        const long KT = cdiv(K, 64);
+        long s = 1;
+        if (KT >= 8) {
+            s = cdiv(2L * n_cu, t2);                   // about two workgroups per CU
+            const long max_s = KT / 2;
+            if (s > max_s) s = max_s;
+            if (s > 32) s = 32;
+            while (s > 1 && (size_t)(s * M * N) > ws_floats) --s;
+        }
+        const double split_cost = s > 1 ? 2.0 * us_per_launch + 0.5 +
+                                              (double)cdiv(t2 * s, n_cu) * 96.0 * (double)cdiv(K, s) * 2.0 / bytes_per_us
+                                        : 1e30;
+        const int wv = (M <= 16 || wsk_cost(0) <= wsk_cost(1)) ? 0 : 1;
+        if (split_cost < wsk_cost(wv)) {
+            pl.kind = 0; pl.variant = 2; pl.tiles = (int)t2;
             const long kt_per = cdiv(KT, s);
             pl.splits = (int)cdiv(KT, kt_per);
+            return pl;
         }
+        pl.kind = 1;
+        pl.variant = wv;
+        pl.tiles = (int)wsk_tiles(wv);
+        pl.nw = 4;
+        return pl;
     }
+    if (tiles(0) >= 2L * n_cu) pl.variant = 0;
+    else pl.variant = 1;
+    pl.tiles = (int)tiles(pl.variant);
     return pl;
 }
 
-hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream_t s)
+hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream_t s, uint32_t *n_launched)
 {
     GemmDev d;
     d.x = (const uint16_t *)a.x; d.w = (const uint16_t *)a.w; d.bias = (const uint16_t *)a.bias;
-    d.res = (const uint16_t *)a.res; d.y = (uint16_t *)a.y; d.y32 = a.y32; d.ws = a.ws; d.counters = a.counters;
+    d.res = (const uint16_t *)a.res; d.y = (uint16_t *)a.y; d.y32 = a.y32; d.ws = a.ws;
     d.B = a.B; d.H = a.H; d.W = a.W; d.Cin = a.Cin; d.Ho = a.Ho; d.Wo = a.Wo; d.KH = a.KH; d.KW = a.KW;
     d.stride = a.stride; d.pad = a.pad; d.act = a.act;
     d.M = a.B * a.Ho * a.Wo; d.N = a.Cout; d.K = a.KH * a.KW * a.Cin;
-    d.KT = (d.K + BK - 1) / BK;
+    d.x_bytes = (unsigned)((size_t)a.B * a.H * a.W * a.Cin * 2);
+    d.w_bytes = (unsigned)((size_t)d.N * d.K * 2);
+    int bm, bn, bk;
+    conv_gemm_tile(pl.variant, &bm, &bn, &bk);
+    d.KT = (d.K + bk - 1) / bk;
     d.splits = pl.splits;
     d.kt_per = (d.KT + pl.splits - 1) / pl.splits;
-    int bm, bn;
-    conv_gemm_tile(pl.variant, &bm, &bn);
     d.tiles_m = (d.M + bm - 1) / bm;
+    if (n_launched) *n_launched += pl.splits > 1 ? 2 : 1;
+    if (pl.kind == 1) {
+        conv_wsk_tile(pl.variant, &bm, &bn);
+        d.tiles_m = (d.M + bm - 1) / bm;
+        return launch_conv_wsk(d, a.dtype, pl.variant, pl.nw, pl.tiles, s);
+    }
     if (a.dtype == DT_BF16) return launch_t<bf16_t>(d, pl, s);
     return launch_t<f16_t>(d, pl, s);
 }

@@ -1,0 +1,224 @@
+// Wave-split-K implicit GEMM for the small, latency-bound layers of batch-1 inference.
+//
+// Same contraction as the LDS-tiled kernel (y[m][n] = act(sum_k A[m][k] w[n][k] + bias + res)), but the
+// parallelism is taken from K *inside* the workgroup instead of from a second kernel:
+//   - a workgroup of NW wavefronts owns one (TM*16) x (TN*16) output tile;
+//   - wavefront w multiplies the whole tile over its own contiguous slice of K, reading its MFMA
+//     operands straight from global memory (each lane 16 bytes = 8 consecutive k of one row), three K
+//     steps in flight, with no LDS staging and no barrier in the loop: every element of the A and W
+//     tiles is still read exactly once per workgroup, because the slices are disjoint;
+//   - the NW partial tiles meet in LDS (float, lane-contiguous so the writes are conflict-free), and
+//     after one barrier the first TM*TN*64 threads add them in wavefront order and apply the epilogue.
+// With a few dozen tiles per layer this fills the machine with NW x tiles wavefronts without the
+// workspace round trip and second launch of a grid-level K split, and the summation order is fixed.
+#include "gemm_common.h"
+#include "kernels.h"
+
+namespace eclip {
+
+namespace {
+
+template <typename T, int TM, int TN, int NW>
+__global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
+{
+    extern __shared__ __attribute__((aligned(16))) float red[];    // [NW][TM*TN][64][4]
+    constexpr int BM = TM * 16, BN = TN * 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile_m = blockIdx.x % p.tiles_m, tile_n = blockIdx.x / p.tiles_m;
+    const int m_base = tile_m * BM, n_base = tile_n * BN;
+    const int row = lane & 15, g = lane >> 4;
+
+    // rows of the im2col operand (one per 16x16 block row) and of the weight operand
+    // buffer descriptors: lanes without a valid chunk use an offset past the end and receive zeros
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (int)p.w_bytes, 0x00020000);
+    constexpr unsigned OOB = 0xffffffffu;
+    bool a_ok[TM];
+    unsigned a_base[TM];
+    int a_ih0[TM], a_iw0[TM];
+    const int HoWo = p.Ho * p.Wo;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m_base + i * 16 + row;
+        a_ok[i] = m < p.M;
+        const int mm = a_ok[i] ? m : 0;
+        const int b = mm / HoWo, r = mm - b * HoWo;
+        const int oh = r / p.Wo, ow = r - oh * p.Wo;
+        a_base[i] = (unsigned)b * (unsigned)(p.H * p.W * p.Cin) * 2u;
+        a_ih0[i] = oh * p.stride - p.pad;
+        a_iw0[i] = ow * p.stride - p.pad;
+    }
+    bool b_ok[TN];
+    unsigned b_base[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n_base + j * 16 + row;
+        b_ok[j] = n < p.N;
+        b_base[j] = (unsigned)(b_ok[j] ? n : 0) * (unsigned)p.K * 2u;
+    }
+
+    // this wavefront's K steps (32 k each)
+    const int ksteps = (p.K + 31) / 32;
+    const int per_wave = (ksteps + NW - 1) / NW;
+    const int ks0 = min(ksteps, wave * per_wave), ks1 = min(ksteps, ks0 + per_wave);
+    const int n_steps = ks1 - ks0;
+
+    // running position of this lane's next 8 k: k = (kh, kw, ci), advanced by 32 per step without dividing
+    int k = ks0 * 32 + g * 8;
+    int kh = 0, kw = 0, ci = k;
+    if (p.KH * p.KW != 1) {
+        const int tap = k / p.Cin;
+        ci = k - tap * p.Cin;
+        kh = tap / p.KW;
+        kw = tap - kh * p.KW;
+    }
+    struct Frag { uint4 a[TM]; uint4 b[TN]; };
+    auto load = [&](Frag &f) {
+        const bool k_ok = k < p.K;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int ih = a_ih0[i] + kh, iw = a_iw0[i] + kw;
+            const bool ok = a_ok[i] && k_ok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
+            const unsigned off = ok ? a_base[i] + (unsigned)((ih * p.W + iw) * p.Cin + ci) * 2u : OOB;
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+            f.a[i] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const unsigned off = (b_ok[j] && k_ok) ? b_base[j] + (unsigned)k * 2u : OOB;
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
+            f.b[j] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+        k += 32;
+        ci += 32;
+        while (ci >= p.Cin) {         // at most 4 turns: Cin >= 8
+            ci -= p.Cin;
+            if (++kw == p.KW) { kw = 0; ++kh; }
+        }
+    };
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto compute = [&](const Frag &f) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(f.b[j], f.a[i], acc[i][j]);
+    };
+
+    // Branch-free pipeline, three steps of loads in flight; steps beyond the slice load zeros (k >= K).
+    Frag f0, f1, f2;
+    if (n_steps <= 0) k = p.K;
+    load(f0);
+    if (n_steps <= 1) k = p.K;
+    load(f1);
+    for (int s = 0; s < n_steps; s += 3) {
+        if (s + 2 >= n_steps) k = p.K;
+        load(f2);
+        compute(f0);
+        if (s + 3 >= n_steps) k = p.K;
+        load(f0);
+        compute(f1);
+        if (s + 4 >= n_steps) k = p.K;
+        load(f1);
+        compute(f2);
+    }
+
+    // ---- cross-wavefront sum through LDS
+    float4 *red4 = reinterpret_cast<float4 *>(red);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            red4[(wave * (TM * TN) + i * TN + j) * 64 + lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+    __syncthreads();
+    for (int slot = tid; slot < TM * TN * 64; slot += NW * 64) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float4 q = red4[w * (TM * TN * 64) + slot];
+            s[0] += q.x; s[1] += q.y; s[2] += q.z; s[3] += q.w;
+        }
+        const int blk = slot >> 6, l = slot & 63;
+        const int i = blk / TN, j = blk - i * TN;
+        // lane l of block (i, j) holds output pixel 16*i + (l & 15), channels 16*j + 4*(l >> 4) .. +3
+        epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_base + i * 16 + (l & 15), n_base + j * 16 + (l >> 4) * 4, s);
+    }
+}
+
+template <typename T, int TM, int TN>
+hipError_t launch_nw(const GemmDev &d, int nw, int tiles, hipStream_t s)
+{
+    const size_t lds = (size_t)nw * TM * TN * 64 * 16;
+    if (lds > 128 * 1024) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)tiles);
+    switch (nw) {
+    case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4>), grid, dim3(256), lds, s, d); break;
+    case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8>), grid, dim3(512), lds, s, d); break;
+    case 16: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16>), grid, dim3(1024), lds, s, d); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_tile(const GemmDev &d, int variant, int nw, int tiles, hipStream_t s)
+{
+    switch (variant) {
+    case 0: return launch_nw<T, 1, 4>(d, nw, tiles, s);
+    case 1: return launch_nw<T, 2, 4>(d, nw, tiles, s);
+    case 2: return launch_nw<T, 4, 4>(d, nw, tiles, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <typename T, int TM, int TN>
+hipError_t set_attr_tile()
+{
+    hipError_t e;
+    const int lim = 144 * 1024;
+    if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+}
+
+}  // namespace
+
+void conv_wsk_tile(int variant, int *bm, int *bn)
+{
+    static const int t[3][2] = {{16, 64}, {32, 64}, {64, 64}};
+    const int v = variant < 0 ? 0 : (variant > 2 ? 2 : variant);
+    *bm = t[v][0];
+    *bn = t[v][1];
+}
+
+size_t conv_wsk_lds_bytes(int variant, int nw)
+{
+    int bm, bn;
+    conv_wsk_tile(variant, &bm, &bn);
+    return (size_t)nw * bm * bn * 4;
+}
+
+hipError_t conv_wsk_init()
+{
+    hipError_t e;
+#define SET(T)                                                     \
+    if ((e = set_attr_tile<T, 1, 4>()) != hipSuccess) return e;    \
+    if ((e = set_attr_tile<T, 2, 4>()) != hipSuccess) return e;    \
+    if ((e = set_attr_tile<T, 4, 4>()) != hipSuccess) return e;
+    SET(bf16_t)
+    SET(f16_t)
+#undef SET
+    return hipSuccess;
+}
+
+hipError_t launch_conv_wsk(const GemmDev &d, int dtype, int variant, int nw, int tiles, hipStream_t s)
+{
+    if (dtype == DT_BF16) return launch_tile<bf16_t>(d, variant, nw, tiles, s);
+    return launch_tile<f16_t>(d, variant, nw, tiles, s);
+}
+
+}  // namespace eclip

@@ -19,18 +19,23 @@ struct ConvGemmArgs {
     void *y;             // [M][Cout] in the model dtype, or null when y32 is used
     float *y32;          // [M][Cout] float output, or null
     float *ws;           // split-K partial sums, >= splits*M*Cout floats when splits > 1
-    unsigned *counters;  // one zero-initialised counter per output tile when splits > 1
     int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, act, dtype;
 };
 struct GemmPlan {
-    int variant;   // tile shape, see conv_gemm_tile()
-    int splits;    // K is cut into this many slices, reduced by the last-arriving workgroup
-    int tiles;     // output tiles = workgroups per slice
+    int kind;      // 0 = LDS-tiled kernel (large problems), 1 = wave-split-K kernel (few tiles, long K)
+    int variant;   // tile shape, see conv_gemm_tile() / conv_wsk_tile()
+    int splits;    // kind 0: K is cut into this many slices, summed by a second kernel
+    int tiles;     // output tiles = workgroups (per slice)
+    int nw;        // kind 1: wavefronts per workgroup, each taking 1/nw of K
 };
-void conv_gemm_tile(int variant, int *bm, int *bn);
+void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
+void conv_wsk_tile(int variant, int *bm, int *bn);
+size_t conv_wsk_lds_bytes(int variant, int nw);
+hipError_t conv_wsk_init();    // raises the dynamic LDS limit of the wave-split-K kernels once per process
 // Chooses tile shape and K split for a stream restricted to n_cu compute units.
-GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats, size_t n_counters);
-hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &p, hipStream_t s);
+GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats);
+// *n_launched (optional) is increased by the number of kernels launched (2 when K is split).
+hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &p, hipStream_t s, uint32_t *n_launched);
 
 // ---- float32 direct convolution / linear (plain FMA) -------------------------------------------
 struct ConvF32Args {

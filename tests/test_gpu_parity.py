@@ -68,9 +68,11 @@ CONV_CASES = [
 def test_conv_gemm(cin, cout, h, w, k, s, p, res, act, dt):
     m = wl.single_layer("conv", dt, seed=cin + cout + k, cin=cin, cout=cout, h=h, w=w, k=k, stride=s, pad=p,
                         residual=res, act=act, bias_std=0.5)
-    # the only rounding on the GPU side is float32 accumulation (the output is written as float32), plus a
-    # 16-bit intermediate when the residual operand is itself a computed tensor
-    check(m, batch=2, tol=4e-3 if res else 2e-4)
+    # roundings on the GPU side: float32 accumulation, one rounding of the image output to the 16-bit
+    # storage type (2^-9 relative for bf16, 2^-12 for fp16), one more when the residual operand is itself
+    # a computed tensor
+    out_round = 2.0 ** -8 if dt == wl.DT_BF16 else 2.0 ** -10
+    check(m, batch=2, tol=out_round * (2 if res else 1))
 
 
 def test_conv_identity_kernel_returns_input_exactly():
@@ -187,8 +189,22 @@ def test_vgg16_small_bf16():
     check(wl.vgg16(seed=6, hw=32, width=16, fc=256), batch=2)
 
 
-def test_mobilenetv2_small_bf16():
-    check(wl.mobilenetv2(seed=7, hw=64), batch=2)
+def test_mobilenetv2_small_fp16():
+    check(wl.mobilenetv2(seed=7, hw=64, dtype=wl.DT_F16), batch=2)
+
+
+def test_mobilenetv2_small_bf16_against_storage_rounded_oracle():
+    # 53 layers of bf16 storage put MobileNetV2's exact-arithmetic result 2.1 % of the logit range away from the
+    # unrounded definition (the oracle shows this by itself), so in bf16 the kernels are checked against the
+    # oracle that rounds every stored activation the same way; what is left is accumulation order and the
+    # occasional flipped rounding
+    m = wl.mobilenetv2(seed=7, hw=64)
+    x = wl.make_input(m, 2)
+    exact = orc.run_model(m, x)
+    stored = orc.run_model(m, x, storage_dtype=wl.DT_BF16)
+    got = run_gpu(m, x)
+    assert rel_to_range(got, stored) <= 1e-2
+    assert rel_to_range(got, exact) <= 2.0 * rel_to_range(stored, exact) + 5e-3
 
 
 def test_bert_small_fp16_and_bf16():

@@ -64,7 +64,7 @@ def test_every_mask_and_table_gives_identical_logits():
         for table in ([1, 1, 1, 1], [5, 5, 5, 5], [1, 2, 3, 4], [4, 1, 4, 1], [0, 3, 3, 0], [2, 2, 5, 5]):
             got, (ns, n_k, n_sw) = g.run(x, table=table, timing=True)
             assert n_sw == sum(1 for i in range(1, 4) if table[i] != table[i - 1]) == g.h.switches()
-            assert n_k == 24 and ns > 0
+            assert n_k >= 24 and ns > 0
             # split-K slice counts depend on the CU count, so sums may be associated differently:
             # compare within float32 accumulation noise of the 16-bit outputs
             assert rel_to_range(got, exp) <= 2e-2

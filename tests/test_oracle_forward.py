@@ -308,3 +308,15 @@ def test_storage_rounding_is_exact():
     assert np.array_equal(b, torch.from_numpy(a).to(torch.bfloat16).float().numpy())
     h = wl.round_to_dtype(a, wl.DT_F16)
     assert np.array_equal(h, torch.from_numpy(a).half().float().numpy())
+
+
+def test_storage_rounded_mode_only_adds_rounding():
+    m = wl.resnet(18, seed=1, hw=32, n_classes=10, width=8)
+    x = wl.make_input(m, 1)
+    exact = orc.run_model(m, x, keep_all=True)
+    stored = orc.run_model(m, x, keep_all=True, storage_dtype=wl.DT_BF16)
+    # first layer: same arithmetic, one rounding of at most 2^-9 relative
+    assert np.all(np.abs(stored[0] - exact[0]) <= np.abs(exact[0]) * 2.0 ** -8 + 1e-30)
+    assert np.array_equal(stored[0], wl.round_to_dtype(exact[0].astype(np.float32), wl.DT_BF16))
+    assert np.abs(stored[-1] - exact[-1]).max() <= 2e-2 * (exact[-1].max() - exact[-1].min())
+    assert not np.array_equal(stored[-1], exact[-1])

@@ -444,9 +444,9 @@ def config_models(cfg: int, small: bool = False) -> List[Model]:
         return [resnet(50, seed=3), bert(seed=4)]
     if cfg == 3:
         if small:
-            return [resnet(50, seed=5, hw=64), vgg16(seed=6, hw=32, width=16, fc=256), mobilenetv2(seed=7, hw=64),
+            return [resnet(50, seed=5, hw=64), vgg16(seed=6, hw=32, width=16, fc=256), mobilenetv2(seed=7, hw=64, dtype=DT_F16),
                     bert(2, 128, 4, 512, 48, vocab=1000, seed=8)]
-        return [resnet(50, seed=5), vgg16(seed=6), mobilenetv2(seed=7), bert(seed=8)]
+        return [resnet(50, seed=5), vgg16(seed=6), mobilenetv2(seed=7, dtype=DT_F16), bert(seed=8)]
     if cfg == 4:
         if small:
             return [bert(2, 128, 4, 512, 48, vocab=1000, seed=9 + i, dtype=DT_BF16) for i in range(3)] + \
