@@ -215,6 +215,20 @@ eclip_status eclip_profile_group(eclip_model *model, uint32_t group, uint32_t ma
 /* Number of kernels in `group`. */
 eclip_status eclip_model_group_size(const eclip_model *model, uint32_t group, uint32_t *n_kernels);
 
+/* How layer `layer` would be launched for `batch` samples on pool entry `mask_id`: which kernel and
+ * with what shape.  For reporting; nothing is launched. */
+typedef struct {
+    char kernel[48];        /* kernel function name, e.g. "conv_wsk_kernel" */
+    uint32_t launches;      /* kernels launched for this layer (2 when K is split over the grid) */
+    uint32_t workgroups;    /* workgroups of the main kernel */
+    uint32_t threads;       /* threads per workgroup of the main kernel */
+    uint32_t tile_m, tile_n;/* output tile of a matrix-core kernel, else 0 */
+    uint32_t k_splits;      /* grid-level K slices (matrix-core LDS-tiled kernel), else 1 */
+    uint64_t m, n, k;       /* GEMM view of a CONV / LINEAR layer, else 0 */
+} eclip_kernel_info;
+eclip_status eclip_model_kernel_info(const eclip_model *model, uint32_t layer, uint32_t mask_id, uint32_t batch,
+                                     eclip_kernel_info *out);
+
 /* ------------------------------------------------------------------------------------------
  * Resource-allocation optimizer (Sec. III-B, "Optimization Formulation"); CPU only
  * ---------------------------------------------------------------------------------------- */

@@ -49,6 +49,12 @@ class eclip_timing(C.Structure):
     _fields_ = [("gpu_ns", C.c_uint64), ("n_kernels", C.c_uint32), ("n_switches", C.c_uint32)]
 
 
+class eclip_kernel_info(C.Structure):
+    _fields_ = [("kernel", C.c_char * 48), ("launches", C.c_uint32), ("workgroups", C.c_uint32), ("threads", C.c_uint32),
+                ("tile_m", C.c_uint32), ("tile_n", C.c_uint32), ("k_splits", C.c_uint32), ("m", C.c_uint64),
+                ("n", C.c_uint64), ("k", C.c_uint64)]
+
+
 class eclip_u128(C.Structure):
     _fields_ = [("lo", C.c_uint64), ("hi", C.c_uint64)]
 
@@ -76,6 +82,7 @@ EXPORTS = {
     "eclip_alloc_set": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.c_uint32]),
     "eclip_model_switches": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
     "eclip_model_group_size": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]),
+    "eclip_model_kernel_info": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(eclip_kernel_info)]),
     "eclip_submit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
     "eclip_wait": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(eclip_timing)]),
     "eclip_profile_group": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
@@ -224,6 +231,12 @@ class Model:
         n = C.c_uint32()
         check(lib.eclip_model_group_size(self.handle, group, C.byref(n)))
         return n.value
+
+    def kernel_info(self, layer: int, mask_id: int, batch: int = 1) -> dict:
+        k = eclip_kernel_info()
+        check(lib.eclip_model_kernel_info(self.handle, layer, mask_id, batch, C.byref(k)))
+        return {"kernel": k.kernel.decode(), "launches": k.launches, "workgroups": k.workgroups, "threads": k.threads,
+                "tile": (k.tile_m, k.tile_n), "k_splits": k.k_splits, "mnk": (k.m, k.n, k.k)}
 
     def submit(self, d_in: int, d_out: int, batch: int) -> Request:
         """d_in / d_out are device addresses (e.g. torch tensor .data_ptr())."""

@@ -682,6 +682,56 @@ extern "C" eclip_status eclip_model_group_size(const eclip_model *model, uint32_
     return ECLIP_OK;
 }
 
+extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32_t layer, uint32_t mask_id, uint32_t batch,
+                                                eclip_kernel_info *out)
+{
+    if (!model || !out) return fail(ECLIP_EINVAL, "null argument");
+    if (layer >= model->layers.size()) return fail(ECLIP_EINVAL, "unknown layer %u", layer);
+    if (mask_id >= model->pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
+    const LayerPlan &P = model->layers[layer];
+    memset(out, 0, sizeof *out);
+    out->launches = 1;
+    out->k_splits = 1;
+    out->threads = 256;
+    const char *name = "";
+    const long rows = (long)batch * P.out.h * P.out.w;
+    switch (P.L.op) {
+    case ECLIP_OP_CONV:
+    case ECLIP_OP_LINEAR: {
+        const GemmShape g = gemm_shape(P, (int)batch);
+        out->m = (uint64_t)g.B * g.Ho * g.Wo; out->n = (uint64_t)g.Cout; out->k = (uint64_t)g.KH * g.KW * g.Cin;
+        if (P.gemm) {
+            const GemmPlan pl = conv_gemm_plan((long)out->m, (long)out->n, (long)out->k, (int)model->pool->streams[mask_id].n_cu, model->ws_floats);
+            int bm, bn, bk;
+            if (pl.kind == 1) { conv_wsk_tile(pl.variant, &bm, &bn); name = "conv_wsk_kernel"; out->threads = (uint32_t)pl.nw * 64; }
+            else { conv_gemm_tile(pl.variant, &bm, &bn, &bk); name = "conv_gemm_kernel"; }
+            out->tile_m = (uint32_t)bm; out->tile_n = (uint32_t)bn;
+            out->k_splits = (uint32_t)pl.splits;
+            out->workgroups = (uint32_t)pl.tiles * (uint32_t)pl.splits;
+            out->launches = pl.splits > 1 ? 2 : 1;
+        } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1) {
+            name = "dwconv_kernel";
+            out->workgroups = (uint32_t)((rows * (P.L.c / ((P.L.c % 8 || model->dtype == ECLIP_F32) ? (model->dtype == ECLIP_F32 && P.L.c % 4 == 0 ? 4 : 1) : 8)) + 255) / 256);
+        } else {
+            name = "conv_f32_kernel";
+            out->workgroups = (uint32_t)((rows * P.L.c + 255) / 256);
+        }
+        break;
+    }
+    case ECLIP_OP_MAXPOOL: name = "maxpool_kernel"; break;
+    case ECLIP_OP_GAP: name = "gap_kernel"; break;
+    case ECLIP_OP_LAYERNORM: name = "row_kernel"; out->workgroups = (uint32_t)((rows + 3) / 4); break;
+    case ECLIP_OP_SOFTMAX: name = "row_kernel"; out->workgroups = (uint32_t)((rows + 3) / 4); break;
+    case ECLIP_OP_ATTENTION: name = "attention_kernel"; break;
+    case ECLIP_OP_EMBED: name = "embed_kernel"; break;
+    case ECLIP_OP_ELTWISE: name = "eltwise_kernel"; break;
+    default: break;
+    }
+    snprintf(out->kernel, sizeof out->kernel, "%s", name);
+    return ECLIP_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // executor
 // ------------------------------------------------------------------------------------------------

@@ -273,7 +273,6 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     auto tiles = [&](int v) { int bm, bn, bk; conv_gemm_tile(v, &bm, &bn, &bk); return cdiv(M, bm) * cdiv(N, bn); };
     auto wsk_tiles = [&](int v) { int bm, bn; conv_wsk_tile(v, &bm, &bn); return cdiv(M, bm) * cdiv(N, bn); };
     GemmPlan pl{0, 1, 1, 0, 4};
-    const long ksteps = cdiv(K, 32);
     // tuning aid: ECLIP_GEMM_FORCE="kind,variant,n" overrides the heuristic; n = K splits (kind 0, clamped to the
     // workspace) or wavefronts per workgroup (kind 1: 4, 8 or 16)
     const char *force = getenv("ECLIP_GEMM_FORCE");
