@@ -119,6 +119,7 @@ extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, u
             if (per[x] == 0) return fail(ECLIP_EINVAL, "mask %u leaves XCD %u (mask bits congruent to %u modulo %u) without a CU", i, x, x, n_xcc);
     }
     HIP_TRY(attention_init());
+    HIP_TRY(conv_gemm_init());
     HIP_TRY(conv_wsk_init());
     TRACE("kernel attributes set");
     eclip_pool *p = new (std::nothrow) eclip_pool;

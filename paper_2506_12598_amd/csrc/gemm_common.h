@@ -13,7 +13,7 @@ struct GemmDev {
     float *y32;
     float *ws;
     int B, H, W, Cin, Ho, Wo, KH, KW, stride, pad, act;
-    int M, N, K, KT, kt_per, splits, tiles_m;
+    int M, N, K, KT, kt_per, splits, tiles_m, tiles_n, raster;
     unsigned x_bytes, w_bytes;               // sizes of the x and w tensors (each below 4 GiB)
 };
 

@@ -31,23 +31,39 @@ namespace eclip {
 
 namespace {
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int RS>
-__global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
+template <typename T, int BM, int BN, int BK, int WM, int WN, int RS, bool OVERLAP = false>
+__global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
 {
-    static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    constexpr int NT = WM * WN * 64;         // threads per workgroup: 4 wavefronts, 8 for the 256x256 tile
     static_assert(RS % 2 == 0, "register stages alternate between the two LDS slots");
     constexpr int LDK = BK + 8;              // row pitch: 16-byte reads of 16 consecutive rows hit distinct banks
     constexpr int CPR = BK / 8;              // 16-byte chunks per row
     constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
     constexpr int A_CH = BM * CPR, B_CH = BN * CPR;
-    constexpr int A_IT = (A_CH + 255) / 256, B_IT = (B_CH + 255) / 256;
+    constexpr int A_IT = (A_CH + NT - 1) / NT, B_IT = (B_CH + NT - 1) / NT;
+    static_assert(NT % CPR == 0, "a thread keeps the same k chunk for all of its rows");
 
-    __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t sB[2][BN * LDK];
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];     // sA[2][BM*LDK] then sB[2][BN*LDK]
+    uint16_t *const sA0 = smem, *const sB0 = smem + 2 * BM * LDK;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int tile_m = blockIdx.x % p.tiles_m, tile_n = blockIdx.x / p.tiles_m;
+    // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), each XCD has its own
+    // L2, and the 32 CUs of an XCD run 32 consecutive workgroups of that XCD at a time.  With `raster` set
+    // (large problems) those 32 workgroups form an 8 x 4 block of tiles, so that one K step pulls 8 + 4
+    // operand tiles into the L2 instead of up to 32 + 1; blocks are dealt to the XCDs in row-major order.
+    int tile_m, tile_n;
+    if (p.raster) {
+        const int b = blockIdx.x, l = b >> 3, w = l & 31;
+        const int sb = (l >> 5) * 8 + (b & 7);
+        const int sbm = (p.tiles_m + 7) >> 3;
+        tile_m = (sb % sbm) * 8 + (w & 7);
+        tile_n = (sb / sbm) * 4 + (w >> 3);
+        if (tile_m >= p.tiles_m || tile_n >= p.tiles_n) return;
+    } else {
+        tile_m = blockIdx.x % p.tiles_m;
+        tile_n = blockIdx.x / p.tiles_m;
+    }
     const int z = blockIdx.y;
     const int m_base = tile_m * BM, n_base = tile_n * BN;
 
@@ -64,7 +80,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
-        const int c = tid + it * 256;
+        const int c = tid + it * NT;
         const int m = m_base + c / CPR;
         a_ok[it] = (c < A_CH) && (m < p.M);
         const int mm = a_ok[it] ? m : 0;
@@ -78,12 +94,12 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     unsigned b_base[B_IT];
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
-        const int c = tid + it * 256;
+        const int c = tid + it * NT;
         const int n = n_base + c / CPR;
         b_ok[it] = (c < B_CH) && (n < p.N);
         b_base[it] = (unsigned)(b_ok[it] ? n : 0) * (unsigned)p.K * 2u;
     }
-    const int kc = (tid % CPR) * 8;          // same for every chunk of this thread: 256 % CPR == 0
+    const int kc = (tid % CPR) * 8;          // same for every chunk of this thread: NT % CPR == 0
     const bool pointwise = (p.KH * p.KW == 1);
 
     auto load_tile = [&](int kt, uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
@@ -114,13 +130,13 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     auto store_tile = [&](int slot, const uint4 (&ra)[A_IT], const uint4 (&rb)[B_IT]) {
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
-            const int c = tid + it * 256;
-            if (c < A_CH) *reinterpret_cast<uint4 *>(&sA[slot][(c / CPR) * LDK + kc]) = ra[it];
+            const int c = tid + it * NT;
+            if (c < A_CH) *reinterpret_cast<uint4 *>(&sA0[slot * BM * LDK + (c / CPR) * LDK + kc]) = ra[it];
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
-            const int c = tid + it * 256;
-            if (c < B_CH) *reinterpret_cast<uint4 *>(&sB[slot][(c / CPR) * LDK + kc]) = rb[it];
+            const int c = tid + it * NT;
+            if (c < B_CH) *reinterpret_cast<uint4 *>(&sB0[slot * BN * LDK + (c / CPR) * LDK + kc]) = rb[it];
         }
     };
 
@@ -145,10 +161,10 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
             uint4 fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const uint4 *>(&sA[slot][(wm * (BM / WM) + i * 16 + frag_row) * LDK + ks * 32 + frag_k]);
+                fa[i] = *reinterpret_cast<const uint4 *>(&sA0[slot * BM * LDK + (wm * (BM / WM) + i * 16 + frag_row) * LDK + ks * 32 + frag_k]);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const uint4 *>(&sB[slot][(wn * (BN / WN) + j * 16 + frag_row) * LDK + ks * 32 + frag_k]);
+                fb[j] = *reinterpret_cast<const uint4 *>(&sB0[slot * BN * LDK + (wn * (BN / WN) + j * 16 + frag_row) * LDK + ks * 32 + frag_k]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -162,14 +178,33 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     // The loop body is branch-free: steps at or beyond kt_end load zeros (k >= K in load_tile's terms is
     // forced by passing KT) and multiply them, which costs at most RS-1 idle steps at the end of a slice
     // and lets the compiler wait for exactly one step's loads at a time.
-    for (int kt = kt_begin; kt < kt_end; kt += RS) {
+    if constexpr (!OVERLAP) {
+        for (int kt = kt_begin; kt < kt_end; kt += RS) {
 #pragma unroll
-        for (int r = 0; r < RS; ++r) {
-            store_tile(r & 1, ra[r], rb[r]);
+            for (int r = 0; r < RS; ++r) {
+                store_tile(r & 1, ra[r], rb[r]);
+                __syncthreads();
+                const int nxt = kt + r + RS;
+                load_tile(nxt < kt_end ? nxt : p.KT, ra[r], rb[r]);
+                compute(r & 1);
+            }
+        }
+    } else {
+        // Large tiles (RS == 2): the LDS stores of step t+1 share a basic block with the MFMAs of step t, so
+        // the scheduler can hide them behind the matrix pipe.  Safe with two slots: slot (t+1)%2 was last read
+        // at step t-1, and every wavefront has passed the barrier that ended that step.
+        static_assert(!OVERLAP || RS == 2, "the overlapped loop alternates two register sets");
+        store_tile(0, ra[0], rb[0]);
+        __syncthreads();
+        for (int kt = kt_begin; kt < kt_end; kt += 2) {
+            load_tile(kt + 2 < kt_end ? kt + 2 : p.KT, ra[0], rb[0]);
+            compute(0);
+            store_tile(1, ra[1], rb[1]);
             __syncthreads();
-            const int nxt = kt + r + RS;
-            load_tile(nxt < kt_end ? nxt : p.KT, ra[r], rb[r]);
-            compute(r & 1);
+            load_tile(kt + 3 < kt_end ? kt + 3 : p.KT, ra[1], rb[1]);
+            compute(1);
+            store_tile(0, ra[0], rb[0]);
+            __syncthreads();
         }
     }
 
@@ -178,11 +213,13 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
 
     if (p.splits == 1) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
+        static_for<TM>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            static_for<TN>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
                 epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_l + i * 16, n_l + j * 16, acc[i][j]);
+            });
+        });
         return;
     }
     // split-K: this slice's partial sums go to ws[z][m][n]; a second kernel adds the slices.  (A single-kernel
@@ -191,19 +228,23 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(GemmDev p)
     // workgroup, or write-through stores and cache-bypassing loads for every partial sum; both cost several
     // times the second launch.)
     const bool vec = ((p.N & 3) == 0);
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
+    static_for<TM>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        static_for<TN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
             const int m = m_l + i * 16, n = n_l + j * 16;
-            if (m >= p.M || n >= p.N) continue;
-            float *dst = p.ws + ((long)z * p.M + m) * p.N + n;
-            if (vec) {
-                *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-            } else {
-                for (int r = 0; r < 4 && n + r < p.N; ++r) dst[r] = acc[i][j][r];
+            if (m < p.M && n < p.N) {
+                float *dst = p.ws + ((long)z * p.M + m) * p.N + n;
+                if (vec) {
+                    *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (n + r < p.N) dst[r] = acc[i][j][r];
+                }
             }
-        }
+        });
+    });
 }
 
 // y = act(sum_z ws[z] + bias + res): one thread per 4 consecutive channels (one channel when N % 4 != 0).
@@ -236,17 +277,20 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
     epilogue_store<T>(bias, res, y, y32, M, N, act, m, n, s, vec ? 4 : 1);
 }
 
-struct Variant { int bm, bn; };
-constexpr Variant kVariants[3] = {{128, 128}, {64, 64}, {32, 64}};
+struct Variant { int bm, bn, bk; };
+constexpr Variant kVariants[4] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}};
+
+constexpr size_t lds_bytes(int bm, int bn, int bk) { return (size_t)2 * (bm + bn) * (bk + 8) * 2; }
 
 template <typename T>
 hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
 {
-    const dim3 grid((unsigned)pl.tiles, (unsigned)pl.splits), block(256);
+    const dim3 grid((unsigned)pl.tiles, (unsigned)pl.splits);
     switch (pl.variant) {
-    case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, block, 0, s, d); break;
-    case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, block, 0, s, d); break;
-    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, block, 0, s, d); break;
+    case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, dim3(256), lds_bytes(128, 128, 32), s, d); break;
+    case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, dim3(256), lds_bytes(64, 64, 64), s, d); break;
+    case 2: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, dim3(256), lds_bytes(32, 64, 64), s, d); break;
+    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 256, 256, 32, 2, 4, 2, true>), grid, dim3(512), lds_bytes(256, 256, 32), s, d); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
@@ -258,21 +302,42 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
 
 }  // namespace
 
+hipError_t conv_gemm_init()
+{
+    hipError_t e = hipFuncSetAttribute((const void *)conv_gemm_kernel<bf16_t, 256, 256, 32, 2, 4, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds_bytes(256, 256, 32));
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void *)conv_gemm_kernel<f16_t, 256, 256, 32, 2, 4, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)lds_bytes(256, 256, 32));
+}
+
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk)
 {
-    const int v = variant < 0 ? 0 : (variant > 2 ? 2 : variant);
+    const int v = variant < 0 ? 0 : (variant > 3 ? 3 : variant);
     *bm = kVariants[v].bm;
     *bn = kVariants[v].bn;
-    *bk = v == 0 ? 32 : 64;
+    *bk = kVariants[v].bk;
 }
 
 static long cdiv(long a, long b) { return (a + b - 1) / b; }
+
+// Large un-split problems are launched on the 8 x 4 block raster: the grid grows to whole blocks, 8 at a time.
+static void set_raster(GemmPlan &pl, long M, long N)
+{
+    int bm, bn, bk;
+    conv_gemm_tile(pl.variant, &bm, &bn, &bk);
+    const long tm = cdiv(M, bm), tn = cdiv(N, bn);
+    if (pl.kind != 0 || pl.splits != 1 || tm * tn < 256) return;
+    const long blocks = cdiv(tm, 8) * cdiv(tn, 4);
+    pl.raster = 1;
+    pl.tiles = (int)(cdiv(blocks, 8) * 8 * 32);
+}
 
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
 {
     auto tiles = [&](int v) { int bm, bn, bk; conv_gemm_tile(v, &bm, &bn, &bk); return cdiv(M, bm) * cdiv(N, bn); };
     auto wsk_tiles = [&](int v) { int bm, bn; conv_wsk_tile(v, &bm, &bn); return cdiv(M, bm) * cdiv(N, bn); };
-    GemmPlan pl{0, 1, 1, 0, 4};
+    GemmPlan pl{0, 1, 1, 0, 4, 0};
     // tuning aid: ECLIP_GEMM_FORCE="kind,variant,n" overrides the heuristic; n = K splits (kind 0, clamped to the
     // workspace) or wavefronts per workgroup (kind 1: 4, 8 or 16)
     const char *force = getenv("ECLIP_GEMM_FORCE");
@@ -283,7 +348,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         pl.kind = 1; pl.variant = f_variant; pl.nw = f_n; pl.tiles = (int)wsk_tiles(f_variant);
         return pl;
     }
-    if (f_kind == 0 && f_variant >= 0 && f_variant <= 2) {
+    if (f_kind == 0 && f_variant >= 0 && f_variant <= 3) {
         pl.variant = f_variant;
         pl.tiles = (int)tiles(pl.variant);
         int bm, bn, bk;
@@ -294,6 +359,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         while (s > 1 && (size_t)(s * M * N) > ws_floats) --s;
         const long kt_per = cdiv(KT, s);
         pl.splits = (int)cdiv(KT, kt_per);
+        set_raster(pl, M, N);
         return pl;
     }
     // Few tiles (batch-1 convolutions, skinny linear layers).  Measured on MI355X: a kernel costs about
@@ -335,9 +401,11 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         pl.nw = 4;
         return pl;
     }
-    if (tiles(0) >= 2L * n_cu) pl.variant = 0;
+    if (tiles(3) >= 2L * n_cu) pl.variant = 3;
+    else if (tiles(0) >= 2L * n_cu) pl.variant = 0;
     else pl.variant = 1;
     pl.tiles = (int)tiles(pl.variant);
+    set_raster(pl, M, N);
     return pl;
 }
 
@@ -357,6 +425,8 @@ hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream
     d.splits = pl.splits;
     d.kt_per = (d.KT + pl.splits - 1) / pl.splits;
     d.tiles_m = (d.M + bm - 1) / bm;
+    d.tiles_n = (d.N + bn - 1) / bn;
+    d.raster = pl.raster;
     if (n_launched) *n_launched += pl.splits > 1 ? 2 : 1;
     if (pl.kind == 1) {
         conv_wsk_tile(pl.variant, &bm, &bn);

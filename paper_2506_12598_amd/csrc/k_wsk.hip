@@ -158,7 +158,10 @@ hipError_t launch_nw(const GemmDev &d, int nw, int tiles, hipStream_t s)
     switch (nw) {
     case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4>), grid, dim3(256), lds, s, d); break;
     case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8>), grid, dim3(512), lds, s, d); break;
-    case 16: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16>), grid, dim3(1024), lds, s, d); break;
+    case 16:
+        if constexpr (TM * TN <= 8) hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16>), grid, dim3(1024), lds, s, d);
+        else return hipErrorInvalidValue;        // 16 partial 64x64 tiles would not fit in LDS
+        break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -182,7 +185,9 @@ hipError_t set_attr_tile()
     const int lim = 144 * 1024;
     if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
     if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+    if constexpr (TM * TN <= 8)
+        return hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+    return hipSuccess;
 }
 
 }  // namespace

@@ -27,10 +27,12 @@ struct GemmPlan {
     int splits;    // kind 0: K is cut into this many slices, summed by a second kernel
     int tiles;     // output tiles = workgroups (per slice)
     int nw;        // kind 1: wavefronts per workgroup, each taking 1/nw of K
+    int raster;    // kind 0: workgroups walk the tiles in 8 x 4 blocks per XCD (tiles then counts whole blocks)
 };
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
 void conv_wsk_tile(int variant, int *bm, int *bn);
 size_t conv_wsk_lds_bytes(int variant, int nw);
+hipError_t conv_gemm_init();   // raises the dynamic LDS limit of the 256x256 tile once per process
 hipError_t conv_wsk_init();    // raises the dynamic LDS limit of the wave-split-K kernels once per process
 // Chooses tile shape and K split for a stream restricted to n_cu compute units.
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats);

@@ -221,3 +221,27 @@ def test_resnet18_full_size_config():
 def test_bert_base_layer_shapes_full_width():
     # BERT-base shapes (hidden 768, 12 heads, FFN 3072, S = 128) with 2 of the 12 layers: the oracle finishes in seconds
     check(wl.bert(2, 768, 12, 3072, 128, vocab=30522, seed=4), batch=1)
+
+
+# ---------------- every GEMM kernel variant, forced, on ragged shapes ----------------------------------------------
+GEMM_FORCE = ["0,0,1", "0,0,3", "0,1,1", "0,1,2", "0,2,1", "0,2,5", "0,3,1", "0,3,2", "1,0,4", "1,0,8", "1,0,16", "1,1,4", "1,1,8",
+              "1,1,16", "1,2,4", "1,2,8"]
+
+
+@pytest.mark.parametrize("force", GEMM_FORCE)
+def test_every_gemm_variant_forced(force):
+    """The planner picks a tile shape, a K split or a wavefront count from the problem size; here each choice is
+    forced in turn (kind, variant, splits | wavefronts) on shapes with ragged M, N and K tails, including one large
+    enough to run on the 8 x 4 block raster."""
+    import os
+    os.environ["ECLIP_GEMM_FORCE"] = force
+    try:
+        m = wl.single_layer("conv", wl.DT_BF16, seed=11, cin=32, cout=96, h=20, w=20, k=3, stride=1, pad=1, act=wl.ACT_RELU,
+                            bias_std=0.5)
+        check(m, batch=2, tol=2.0 ** -8)
+        m = wl.single_layer("linear", wl.DT_F16, seed=12, rows=300, k=520, n=200, bias_std=0.3, std=0.05)
+        check(m, batch=1, tol=2e-4)
+        m = wl.single_layer("linear", wl.DT_BF16, seed=13, rows=1100, k=136, n=1100, std=0.1)
+        check(m, batch=1, tol=2e-4)
+    finally:
+        os.environ.pop("ECLIP_GEMM_FORCE", None)
