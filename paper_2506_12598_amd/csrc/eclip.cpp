@@ -604,6 +604,7 @@ extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_des
     // ---- split-K workspace: enough for the most demanding GEMM layer at any CU count, capped
     size_t ws = 0;
     for (const LayerPlan &P : m->layers) {
+        if (P.L.op == ECLIP_OP_GAP) ws = std::max(ws, (size_t)m->max_batch * 64 * (size_t)P.L.c);
         if (!P.gemm) continue;
         const GemmShape g = gemm_shape(P, (int)m->max_batch);
         const size_t MN = (size_t)g.B * g.Ho * g.Wo * g.Cout;
@@ -788,7 +789,8 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
     }
     case ECLIP_OP_GAP:
         if (d_out32) y32 = d_out32;
-        e = launch_gap(src(L.in0), y, y32, batch, P.in.h * P.in.w, L.c, dt, n_cu, s);
+        *n_launched -= 1;
+        e = launch_gap(src(L.in0), y, y32, m->d_ws, m->ws_floats, batch, P.in.h * P.in.w, L.c, dt, n_cu, s, n_launched);
         break;
     case ECLIP_OP_LAYERNORM:
     case ECLIP_OP_SOFTMAX: {

@@ -257,8 +257,8 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
     const int per_row = vec ? N / 4 : N;
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (long)M * per_row) return;
-    const int m = (int)(idx / per_row);
-    const int n = (int)(idx % per_row) * (vec ? 4 : 1);
+    const int m = (int)((unsigned)idx / (unsigned)per_row);
+    const int n = (int)((unsigned)idx % (unsigned)per_row) * (vec ? 4 : 1);
     const long slice = (long)M * N;
     const float *src = ws + (long)m * N + n;
     f32x4 s = {0.f, 0.f, 0.f, 0.f};

@@ -28,11 +28,13 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, long total
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    const int n = (int)(idx % a.Cout);
-    const long m = idx / a.Cout;
-    const int ow = (int)(m % a.Wo);
-    const int oh = (int)((m / a.Wo) % a.Ho);
-    const int b = (int)(m / ((long)a.Wo * a.Ho));
+    const unsigned ui = (unsigned)idx;
+    const int n = (int)(ui % (unsigned)a.Cout);
+    const unsigned m = ui / (unsigned)a.Cout;
+    const int ow = (int)(m % (unsigned)a.Wo);
+    const unsigned mh = m / (unsigned)a.Wo;
+    const int oh = (int)(mh % (unsigned)a.Ho);
+    const int b = (int)(mh / (unsigned)a.Ho);
     float acc = a.bias ? a.bias[n] : 0.0f;
     for (int kh = 0; kh < a.KH; ++kh) {
         const int ih = oh * a.stride - a.pad + kh;
@@ -50,37 +52,67 @@ __global__ __launch_bounds__(256) void conv_f32_kernel(ConvF32Args a, long total
 }
 
 // ---------------- depthwise convolution --------------------------------------------------------------
-template <typename T, int V>
+// One thread per (output pixel, V channels).  KS > 0 fixes the window size at compile time so that all taps'
+// loads are issued back to back; with 16-byte accesses on a 16-bit type the input is read through a buffer
+// descriptor and a padding tap simply gets an out-of-range offset (the hardware returns zeros), so there is
+// no branch between the loads.
+template <typename T, int V, int KS>
 __global__ __launch_bounds__(256) void dwconv_kernel(DwConvArgs a, long total)
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    const int cv = a.C / V;
-    const int c = (int)(idx % cv) * V;
-    const long m = idx / cv;
-    const int ow = (int)(m % a.Wo);
-    const int oh = (int)((m / a.Wo) % a.Ho);
-    const int b = (int)(m / ((long)a.Wo * a.Ho));
+    // tensors hold fewer than 2^30 elements, so 32-bit index arithmetic suffices (64-bit division is slow)
+    const unsigned cv = (unsigned)(a.C / V), ui = (unsigned)idx;
+    const int c = (int)(ui % cv) * V;
+    const unsigned m = ui / cv;
+    const int ow = (int)(m % (unsigned)a.Wo);
+    const unsigned mh = m / (unsigned)a.Wo;
+    const int oh = (int)(mh % (unsigned)a.Ho);
+    const int b = (int)(mh / (unsigned)a.Ho);
     const T *x = (const T *)a.x, *w = (const T *)a.w;
     float acc[V];
     if (a.bias) Pack<T, V>::load((const T *)a.bias + c, acc);
     else
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = 0.0f;
-    for (int kh = 0; kh < a.KH; ++kh) {
-        const int ih = oh * a.stride - a.pad + kh;
-        if ((unsigned)ih >= (unsigned)a.H) continue;
-        for (int kw = 0; kw < a.KW; ++kw) {
-            const int iw = ow * a.stride - a.pad + kw;
-            if ((unsigned)iw >= (unsigned)a.W) continue;
-            float xv[V], wv[V];
-            Pack<T, V>::load(x + (((long)b * a.H + ih) * a.W + iw) * a.C + c, xv);
-            Pack<T, V>::load(w + (long)(kh * a.KW + kw) * a.C + c, wv);
+    if constexpr (KS > 0 && V == 8 && sizeof(T) == 2) {
+        const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((unsigned)a.B * a.H * a.W * a.C * 2u), 0x00020000);
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+        u32x4 xq[KS * KS];
+        uint4 wq[KS * KS];
 #pragma unroll
-            for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+        for (int t = 0; t < KS * KS; ++t) {
+            const int ih = oh * a.stride - a.pad + t / KS, iw = ow * a.stride - a.pad + t % KS;
+            const bool ok = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+            const unsigned off = ok ? (unsigned)(((b * a.H + ih) * a.W + iw) * a.C + c) * 2u : 0xffffffffu;
+            xq[t] = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+            wq[t] = *reinterpret_cast<const uint4 *>(w + (long)t * a.C + c);
+        }
+#pragma unroll
+        for (int t = 0; t < KS * KS; ++t) {
+            const uint32_t xs[4] = {xq[t].x, xq[t].y, xq[t].z, xq[t].w}, ws[4] = {wq[t].x, wq[t].y, wq[t].z, wq[t].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[2 * i] = fmaf(Cvt<T>::from_bits(xs[i] & 0xffffu), Cvt<T>::from_bits(ws[i] & 0xffffu), acc[2 * i]);
+                acc[2 * i + 1] = fmaf(Cvt<T>::from_bits(xs[i] >> 16), Cvt<T>::from_bits(ws[i] >> 16), acc[2 * i + 1]);
+            }
+        }
+    } else {
+        for (int kh = 0; kh < a.KH; ++kh) {
+            const int ih = oh * a.stride - a.pad + kh;
+            if ((unsigned)ih >= (unsigned)a.H) continue;
+            for (int kw = 0; kw < a.KW; ++kw) {
+                const int iw = ow * a.stride - a.pad + kw;
+                if ((unsigned)iw >= (unsigned)a.W) continue;
+                float xv[V], wv[V];
+                Pack<T, V>::load(x + (((long)b * a.H + ih) * a.W + iw) * a.C + c, xv);
+                Pack<T, V>::load(w + (long)(kh * a.KW + kw) * a.C + c, wv);
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+            }
         }
     }
-    const long off = m * a.C + c;
+    const long off = (long)m * a.C + c;
     if (a.res) {
         float rv[V];
         Pack<T, V>::load((const T *)a.res + off, rv);
@@ -93,48 +125,61 @@ __global__ __launch_bounds__(256) void dwconv_kernel(DwConvArgs a, long total)
 }
 
 // ---------------- max pooling ---------------------------------------------------------------------------
-template <typename T, int V>
+// Window coordinates are clamped into the image instead of skipped: a clamped tap re-reads a pixel that is
+// already inside the window (2*pad <= window is checked at load), so the maximum is unchanged and the loads
+// need no branch.  KS > 0 fixes the (square) window at compile time.
+template <typename T, int V, int KS>
 __global__ __launch_bounds__(256) void maxpool_kernel(PoolArgs a, long total)
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    const int cv = a.C / V;
-    const int c = (int)(idx % cv) * V;
-    const long m = idx / cv;
-    const int ow = (int)(m % a.Wo);
-    const int oh = (int)((m / a.Wo) % a.Ho);
-    const int b = (int)(m / ((long)a.Wo * a.Ho));
+    // tensors hold fewer than 2^30 elements, so 32-bit index arithmetic suffices (64-bit division is slow)
+    const unsigned cv = (unsigned)(a.C / V), ui = (unsigned)idx;
+    const int c = (int)(ui % cv) * V;
+    const unsigned m = ui / cv;
+    const int ow = (int)(m % (unsigned)a.Wo);
+    const unsigned mh = m / (unsigned)a.Wo;
+    const int oh = (int)(mh % (unsigned)a.Ho);
+    const int b = (int)(mh / (unsigned)a.Ho);
+    const T *x = (const T *)a.x + (long)b * a.H * a.W * a.C + c;
     float best[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) best[i] = -INFINITY;
-    for (int kh = 0; kh < a.KH; ++kh) {
-        const int ih = oh * a.stride - a.pad + kh;
-        if ((unsigned)ih >= (unsigned)a.H) continue;
-        for (int kw = 0; kw < a.KW; ++kw) {
-            const int iw = ow * a.stride - a.pad + kw;
-            if ((unsigned)iw >= (unsigned)a.W) continue;
+    const int kh_n = KS > 0 ? KS : a.KH, kw_n = KS > 0 ? KS : a.KW;
+    const int ih0 = oh * a.stride - a.pad, iw0 = ow * a.stride - a.pad;
+#pragma unroll KS > 0 ? KS : 1
+    for (int kh = 0; kh < kh_n; ++kh) {
+        const int ih = min(max(ih0 + kh, 0), a.H - 1);
+#pragma unroll KS > 0 ? KS : 1
+        for (int kw = 0; kw < kw_n; ++kw) {
+            const int iw = min(max(iw0 + kw, 0), a.W - 1);
             float xv[V];
-            Pack<T, V>::load((const T *)a.x + (((long)b * a.H + ih) * a.W + iw) * a.C + c, xv);
+            Pack<T, V>::load(x + ((long)ih * a.W + iw) * a.C, xv);
 #pragma unroll
             for (int i = 0; i < V; ++i) best[i] = fmaxf(best[i], xv[i]);
         }
     }
-    Pack<T, V>::store((T *)a.y + m * a.C + c, best);
+    Pack<T, V>::store((T *)a.y + (long)m * a.C + c, best);
 }
 
 // ---------------- global average pooling: block = 32 channel chunks x 8 row slices -------------------------
+// grid = (channel blocks, B, hw_parts).  With hw_parts == 1 the block finishes its channels; otherwise it
+// writes the float sums of its share of the rows to part_out[b][part][C] and gap_finish_kernel adds the parts.
 template <typename T, int V>
-__global__ __launch_bounds__(256) void gap_kernel(const T *x, T *y, float *y32, int HW, int C)
+__global__ __launch_bounds__(256) void gap_kernel(const T *x, T *y, float *y32, float *part_out, int HW, int C)
 {
     __shared__ float part[8][32][V];
     const int b = blockIdx.y;
     const int lane_c = threadIdx.x & 31, slice = threadIdx.x >> 5;
     const int c = (blockIdx.x * 32 + lane_c) * V;
+    const int parts = gridDim.z;
+    const int per = (HW + parts - 1) / parts;
+    const int r0 = blockIdx.z * per, r1 = min(HW, r0 + per);
     float acc[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.0f;
     if (c < C)
-        for (int r = slice; r < HW; r += 8) {
+        for (int r = r0 + slice; r < r1; r += 8) {
             float xv[V];
             Pack<T, V>::load(x + ((long)b * HW + r) * C + c, xv);
 #pragma unroll
@@ -144,15 +189,22 @@ __global__ __launch_bounds__(256) void gap_kernel(const T *x, T *y, float *y32, 
     for (int i = 0; i < V; ++i) part[slice][lane_c][i] = acc[i];
     __syncthreads();
     if (slice == 0 && c < C) {
-        const float inv = 1.0f / (float)HW;
         float o[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             float s = 0.0f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) s += part[j][lane_c][i];
-            o[i] = s * inv;
+            o[i] = s;
         }
+        if (parts > 1) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) part_out[((long)b * parts + blockIdx.z) * C + c + i] = o[i];
+            return;
+        }
+        const float inv = 1.0f / (float)HW;
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] *= inv;
         if (y32) {
 #pragma unroll
             for (int i = 0; i < V; ++i) y32[(long)b * C + c + i] = o[i];
@@ -160,6 +212,18 @@ __global__ __launch_bounds__(256) void gap_kernel(const T *x, T *y, float *y32, 
             Pack<T, V>::store(y + (long)b * C + c, o);
         }
     }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void gap_finish_kernel(const float *part_in, T *y, float *y32, int parts, int HW, int C, long total)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;     // over B*C
+    if (idx >= total) return;
+    const long b = (unsigned)idx / (unsigned)C, c = (unsigned)idx % (unsigned)C;
+    float s = 0.0f;
+    for (int p = 0; p < parts; ++p) s += part_in[(b * parts + p) * C + c];
+    s *= 1.0f / (float)HW;
+    if (y32) y32[idx] = s;
+    else Cvt<T>::store(y + idx, s);
 }
 
 // ---------------- row kernels: one wavefront per row, the row lives in registers ----------------------------
@@ -251,9 +315,9 @@ __global__ __launch_bounds__(256) void eltwise_kernel(EltArgs a, long total)
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    const int cv = a.width / V;
-    const int c = (int)(idx % cv) * V;
-    const long off = (idx / cv) * a.width + c;
+    const unsigned cv = (unsigned)(a.width / V), ui = (unsigned)idx;
+    const int c = (int)(ui % cv) * V;
+    const long off = (long)(ui / cv) * a.width + c;
     float v[V];
     Pack<T, V>::load((const T *)a.x + off, v);
     if (a.bias) {
@@ -284,10 +348,10 @@ __global__ __launch_bounds__(256) void embed_kernel(EmbedArgs a, long total)
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
-    const int cv = a.Hd / V;
-    const int c = (int)(idx % cv) * V;
-    const long tokn = idx / cv;
-    const int s = (int)(tokn % a.S);
+    const unsigned cv = (unsigned)(a.Hd / V), ui = (unsigned)idx;
+    const int c = (int)(ui % cv) * V;
+    const long tokn = ui / cv;
+    const int s = (int)((unsigned)tokn % (unsigned)a.S);
     int id = a.ids[tokn];
     id = id < 0 ? 0 : (id >= a.vocab ? a.vocab - 1 : id);     // out-of-range ids are clamped, never read out of bounds
     float t[V], p[V], ty[V], o[V];
@@ -305,9 +369,10 @@ __global__ __launch_bounds__(256) void nchw_to_nhwc_kernel(const T *x, T *y, int
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;   // over B*HW*Cp
     if (idx >= total) return;
-    const int c = (int)(idx % Cp);
-    const long bp = idx / Cp;
-    const long b = bp / HW, pix = bp % HW;
+    const unsigned ui = (unsigned)idx;
+    const int c = (int)(ui % (unsigned)Cp);
+    const unsigned bp = ui / (unsigned)Cp;
+    const long b = bp / (unsigned)HW, pix = bp % (unsigned)HW;
     T v;
     if (c < C) v = x[(b * C + c) * HW + pix];
     else Cvt<T>::store(&v, 0.0f);
@@ -318,9 +383,10 @@ __global__ __launch_bounds__(256) void nhwc_to_nchw_f32_kernel(const T *x, float
 {
     const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;   // over B*C*HW (output order)
     if (idx >= total) return;
-    const int pix = (int)(idx % HW);
-    const long bc = idx / HW;
-    const long b = bc / C, c = bc % C;
+    const unsigned ui = (unsigned)idx;
+    const int pix = (int)(ui % (unsigned)HW);
+    const unsigned bc = ui / (unsigned)HW;
+    const long b = bc / (unsigned)C, c = bc % (unsigned)C;
     y[idx] = Cvt<T>::load(x + (b * HW + pix) * C + c);
 }
 template <typename T>
@@ -365,10 +431,12 @@ hipError_t launch_conv_f32(const ConvF32Args &a, hipStream_t s)
 
 hipError_t launch_dwconv(const DwConvArgs &a, int, hipStream_t s)
 {
-#define CALL(T, V)                                                                                          \
-    {                                                                                                       \
-        const long total = (long)a.B * a.Ho * a.Wo * (a.C / V);                                             \
-        hipLaunchKernelGGL((dwconv_kernel<T, V>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a, total); \
+#define CALL(T, V)                                                                                              \
+    {                                                                                                           \
+        const long total = (long)a.B * a.Ho * a.Wo * (a.C / V);                                                 \
+        const dim3 grid(blocks_for(total, 256));                                                                \
+        if (a.KH == 3 && a.KW == 3) hipLaunchKernelGGL((dwconv_kernel<T, V, 3>), grid, dim3(256), 0, s, a, total); \
+        else hipLaunchKernelGGL((dwconv_kernel<T, V, 0>), grid, dim3(256), 0, s, a, total);                     \
     }
     ECLIP_DISPATCH(a.dtype, a.C, CALL);
 #undef CALL
@@ -377,22 +445,44 @@ hipError_t launch_dwconv(const DwConvArgs &a, int, hipStream_t s)
 
 hipError_t launch_maxpool(const PoolArgs &a, int, hipStream_t s)
 {
-#define CALL(T, V)                                                                                           \
-    {                                                                                                        \
-        const long total = (long)a.B * a.Ho * a.Wo * (a.C / V);                                              \
-        hipLaunchKernelGGL((maxpool_kernel<T, V>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a, total); \
+#define CALL(T, V)                                                                                               \
+    {                                                                                                            \
+        const long total = (long)a.B * a.Ho * a.Wo * (a.C / V);                                                  \
+        const dim3 grid(blocks_for(total, 256));                                                                 \
+        if (a.KH == 3 && a.KW == 3) hipLaunchKernelGGL((maxpool_kernel<T, V, 3>), grid, dim3(256), 0, s, a, total); \
+        else if (a.KH == 2 && a.KW == 2) hipLaunchKernelGGL((maxpool_kernel<T, V, 2>), grid, dim3(256), 0, s, a, total); \
+        else hipLaunchKernelGGL((maxpool_kernel<T, V, 0>), grid, dim3(256), 0, s, a, total);                     \
     }
     ECLIP_DISPATCH(a.dtype, a.C, CALL);
 #undef CALL
     return hipGetLastError();
 }
 
-hipError_t launch_gap(const void *x, void *y, float *y32, int B, int HW, int C, int dtype, int, hipStream_t s)
+int gap_parts(int B, int HW, int C, int n_cu)
 {
-#define CALL(T, V)                                                                                     \
-    {                                                                                                  \
-        const dim3 grid(blocks_for(C / V, 32), (unsigned)B);                                           \
-        hipLaunchKernelGGL((gap_kernel<T, V>), grid, dim3(256), 0, s, (const T *)x, (T *)y, y32, HW, C); \
+    // enough workgroups to cover the CUs twice, at least 64 rows per part
+    const long base = (long)B * ((C + 255) / 256);
+    long parts = (2L * n_cu + base - 1) / base;
+    const long cap = HW / 64 > 0 ? HW / 64 : 1;
+    if (parts > cap) parts = cap;
+    if (parts > 64) parts = 64;
+    return parts < 1 ? 1 : (int)parts;
+}
+
+hipError_t launch_gap(const void *x, void *y, float *y32, float *ws, size_t ws_floats, int B, int HW, int C, int dtype, int n_cu,
+                      hipStream_t s, uint32_t *n_launched)
+{
+    int parts = gap_parts(B, HW, C, n_cu);
+    if ((size_t)B * parts * C > ws_floats) parts = 1;
+    if (n_launched) *n_launched += parts > 1 ? 2 : 1;
+#define CALL(T, V)                                                                                                     \
+    {                                                                                                                  \
+        const dim3 grid(blocks_for(C / V, 32), (unsigned)B, (unsigned)parts);                                          \
+        hipLaunchKernelGGL((gap_kernel<T, V>), grid, dim3(256), 0, s, (const T *)x, (T *)y, y32, ws, HW, C);           \
+        if (parts > 1) {                                                                                               \
+            const long total = (long)B * C;                                                                            \
+            hipLaunchKernelGGL((gap_finish_kernel<T>), dim3(blocks_for(total, 256)), dim3(256), 0, s, ws, (T *)y, y32, parts, HW, C, total); \
+        }                                                                                                              \
     }
     ECLIP_DISPATCH(dtype, C, CALL);
 #undef CALL

@@ -62,8 +62,11 @@ struct PoolArgs {
     int B, H, W, C, Ho, Wo, KH, KW, stride, pad, dtype;
 };
 hipError_t launch_maxpool(const PoolArgs &a, int n_cu, hipStream_t s);
-// mean over HW: x [B][HW][C] -> y [B][C] (model dtype) or y32 (float)
-hipError_t launch_gap(const void *x, void *y, float *y32, int B, int HW, int C, int dtype, int n_cu, hipStream_t s);
+// mean over HW: x [B][HW][C] -> y [B][C] (model dtype) or y32 (float).  Large HW is cut into parts whose float sums
+// go through ws (>= B*parts*C floats) and a second kernel; *n_launched grows by the kernels launched.
+int gap_parts(int B, int HW, int C, int n_cu);
+hipError_t launch_gap(const void *x, void *y, float *y32, float *ws, size_t ws_floats, int B, int HW, int C, int dtype, int n_cu,
+                      hipStream_t s, uint32_t *n_launched);
 
 struct RowArgs {
     const void *x, *res, *gamma, *beta;

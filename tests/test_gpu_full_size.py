@@ -1,0 +1,58 @@
+"""GPU parity at the configurations' full sizes, through the same entry points and launch configuration the
+benchmark uses (batch, dtype, kernel groups on masked streams).  The oracle's whole forward pass is affordable at
+these sizes on the GPU machine's host cores (0.3 - 20 s each), so every output element is compared."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import forward as orc
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("no GPU", allow_module_level=True)
+
+from gpu_util import GpuModel, rel_to_range  # noqa: E402
+
+
+def full_check(model, batch, table, tol=2e-2):
+    x = wl.make_input(model, batch)
+    g = GpuModel(model, max_batch=batch)
+    try:
+        got = g.run(x, table=table)
+    finally:
+        g.free()
+    exp = orc.run_model(model, x)
+    assert got.shape == exp.shape and np.isfinite(got).all()
+    err = rel_to_range(got, exp)
+    assert err <= tol, f"{model.name}: err/range {err}"
+    return err
+
+
+def test_config3_resnet50_bf16_and_bert_base_fp16():
+    r50, bert = wl.config_models(2)
+    assert len(r50.layers) == 56 and [r50.group_of_layer.count(g) for g in range(4)] == [12, 13, 19, 12]
+    full_check(r50, 1, [3, 2, 4, 1])
+    assert bert.n_groups == 4 and bert.layers[-1].c == 768 and bert.in_w == 128
+    full_check(bert, 1, [2, 5, 3, 0])
+
+
+def test_config4_vgg16_and_mobilenetv2_batch_range():
+    _, vgg, mbv2, _ = wl.config_models(3)
+    assert vgg.n_groups == 6 and mbv2.n_groups == 7 and len(mbv2.layers) == 54
+    full_check(vgg, 2, [5, 5, 4, 3, 2, 1])
+    full_check(mbv2, 8, [1, 2, 3, 4, 5, 0, 3])
+
+
+def test_config5_resnet152_batch8_bf16():
+    m = wl.config_models(4)[3]
+    assert [m.group_of_layer.count(g) for g in range(4)] == [12, 25, 109, 12]
+    full_check(m, 8, [5, 4, 5, 3])
+
+
+def test_config5_bert_large_seq384_batch4_bf16_six_layers():
+    # the configuration's encoder (hidden 1024, 16 heads, FFN 4096, S = 384, batch 4) with 6 of its 24 layers:
+    # every kernel runs at its full shape (M = 1536) and the oracle needs a quarter of the 16 s of the full stack
+    m = wl.bert(6, 1024, 16, 4096, 384, seed=9, dtype=wl.DT_BF16)
+    full_check(m, 4, [3, 5])
