@@ -1,17 +1,22 @@
 #!/usr/bin/env python3
 """Co-located inference benchmark on one MI355X.
 
-Workload (default): two ResNet-18-style CNNs, bf16, batch 1, 3x224x224 N(0,1) inputs, He-normal weights
-(seeds 1 and 2), each cut into 4 kernel groups (its stages), served by one worker thread per model on a
-pre-allocated pool of CU-masked streams {32,64,128,192,256 CUs} per worker plus one shared unmasked stream.
-The CU share of every group comes from the library's exact solver of the paper's allocation model, fed with
-latency-vs-CU tables profiled here.
+Default workload (`--config 1`, the one the headline metric is quoted on): two ResNet-18-style CNNs, bf16,
+batch 1, 3x224x224 N(0,1) inputs, He-normal weights (seeds 1 and 2), each cut into 4 kernel groups (its stages),
+served by one worker thread per model on a pre-allocated pool of CU-masked streams {32,64,128,192,256 CUs} per
+worker plus unmasked streams.  The CU share of every group comes from the library's exact solver of the paper's
+allocation model (Sec. III-B), fed with latency-vs-CU tables profiled here.  `--config 2|3|4` run the other
+co-location mixes (ResNet-50 + BERT-base; ResNet-50 + VGG-16 + MobileNetV2 + BERT-base with batch 1-8;
+3 x BERT-large + ResNet-152 stress) through the same code.
 
-One step = one inference on every co-located model.  The timed region is exactly `--steps` steps under the
-ECLIP policy with inputs resident in HBM; `value` is total inferences per second.  Around it, untimed:
-the same closed loop under the two unpartitioned policies, an open-loop Poisson run (200 requests/s per
-model) for p99 latency and inferences per joule, per-kernel HIP-event timings of the dominant kernel for
-the roofline entry, and the CPU oracle timed on the host cores.
+One step = one request on every co-located model.  The timed region is exactly `--steps` steps under the ECLIP
+policy with inputs resident in HBM; `value` is total inferences per second (a request of batch b counts b).
+Around it, untimed: the same closed loop under the two unpartitioned policies, an open-loop Poisson run for
+p50/p99 latency and inferences per joule, per-kernel HIP-event timings for the roofline entry, and the CPU
+oracle timed on the host cores.
+
+`--kernels` instead times single kernels at roofline shapes (operands far larger than the 256 MB last-level
+cache) and prints a table; it is the command behind profiles/kernels_roofline_shapes.txt.
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
@@ -31,8 +36,16 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-CONFIGS = [32, 64, 128, 192, 256]
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0
+RIDGE = MFMA_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS       # FLOP per byte
+
+WORKLOADS = {
+    1: "2x ResNet-18-style bf16 batch 1 3x224x224, 4 kernel groups each",
+    2: "ResNet-50-style bf16 batch 1 + BERT-base-style fp16 seq 128 batch 1, 4 kernel groups each",
+    3: "ResNet-50 bf16 + VGG-16 bf16 + MobileNetV2 fp16 + BERT-base fp16, batch 1-8 uniform per request",
+    4: "3x BERT-large-style bf16 seq 384 batch 4 + ResNet-152-style bf16 batch 8 (stress)",
+}
 
 
 def log(*a):
@@ -57,7 +70,7 @@ class PowerSampler:
     def read(self):
         if self.paths:
             try:
-                return sum(int(open(p).read()) for p in self.paths[:1]) / 1e6
+                return int(open(self.paths[0]).read()) / 1e6
             except (OSError, ValueError):
                 return None
         try:
@@ -99,10 +112,11 @@ class PowerSampler:
 # ---------------------------------------------------------------------------------------------------
 # workload
 # ---------------------------------------------------------------------------------------------------
-def conv_gemm_bytes(model, batch):
-    """Algorithmic HBM bytes of every matrix-core conv/linear layer: input + weights + output (+ residual),
-    2 bytes per element; im2col duplication is not traffic."""
+def gemm_work(model, batch):
+    """(algorithmic bytes, flops) of every matrix-core conv/linear layer, None for other layers.  Bytes: input +
+    weights + output (+ residual) once each, at the storage width; im2col duplication is not traffic."""
     import workloads as wl
+    e = 4 if model.dtype == wl.DT_F32 else 2
     out = []
     for L in model.layers:
         if L.op not in (wl.OP_CONV, wl.OP_LINEAR) or L.groups != 1:
@@ -118,45 +132,60 @@ def conv_gemm_bytes(model, batch):
         taps = L.kh * L.kw if L.op == wl.OP_CONV else (h * w if image else 1)
         n_w = L.c * cin * taps
         flops = 2.0 * n_out * (n_w / L.c)
-        out.append((2.0 * (n_in + n_w + n_out + (n_out if L.in1 != -2 else 0)), flops))
+        out.append((float(e) * (n_in + n_w + n_out + (n_out if L.in1 != -2 else 0)), flops))
     return out
 
 
 class Worker:
     """One model = one worker: holds the device buffers and runs closed-loop or scheduled requests."""
 
-    def __init__(self, ec, torch, pool, model, index, depth):
+    def __init__(self, ec, torch, pool, model, index, depth, batches):
         import workloads as wl
         self.model, self.index, self.depth = model, index, depth
-        self.h = ec.Model(pool, model, wl.to_storage(model.weights, model.dtype), max_batch=1, max_inflight=depth)
-        x = wl.make_input(model, 1)
-        s = wl.to_storage(x, model.dtype)
+        self.batches = batches                       # per-request batch sizes, cycled
+        self.max_batch = max(batches)
+        self.h = ec.Model(pool, model, wl.to_storage(model.weights, model.dtype), max_batch=self.max_batch,
+                          max_inflight=depth)
+        x = wl.make_input(model, self.max_batch)
         self.x = x
-        self.d_in = torch.from_numpy(s.view(np.int16) if s.dtype == np.uint16 else s).cuda()
-        self.d_out = [torch.zeros(model.out_shape(1), dtype=torch.float32, device="cuda") for _ in range(depth)]
+        if model.in_kind == wl.IN_TOKENS:
+            self.d_in = torch.from_numpy(x).cuda()
+        else:
+            s = wl.to_storage(x, model.dtype)
+            self.d_in = torch.from_numpy(s.view(np.int16) if s.dtype == np.uint16 else s).cuda()
+        self.d_out = [torch.zeros(model.out_shape(self.max_batch), dtype=torch.float32, device="cuda") for _ in range(depth)]
+        self.served = 0
 
     def closed_loop(self, n, barrier=None):
-        """n inferences, up to `depth` in flight."""
+        """n requests, up to `depth` in flight; records the number of inferences served."""
         if barrier is not None:
             barrier.wait()
         q = []
+        served = 0
         for i in range(n):
             if len(q) == self.depth:
                 q.pop(0).wait()
-            q.append(self.h.submit(self.d_in.data_ptr(), self.d_out[i % self.depth].data_ptr(), 1))
+            b = self.batches[i % len(self.batches)]
+            q.append(self.h.submit(self.d_in.data_ptr(), self.d_out[i % self.depth].data_ptr(), b))
+            served += b
         for r in q:
             r.wait()
+        self.served = served
 
     def open_loop(self, arrivals, t_start, lat_out):
         """Serve requests at their scheduled arrival times (seconds after t_start); latency = completion - arrival."""
-        for a in arrivals:
+        served = 0
+        for i, a in enumerate(arrivals):
             now = time.perf_counter() - t_start
             if a > now:
                 time.sleep(max(0.0, a - now - 50e-6))
                 while time.perf_counter() - t_start < a:
                     pass
-            self.h.submit(self.d_in.data_ptr(), self.d_out[0].data_ptr(), 1).wait()
+            b = self.batches[i % len(self.batches)]
+            self.h.submit(self.d_in.data_ptr(), self.d_out[0].data_ptr(), b).wait()
             lat_out.append(time.perf_counter() - t_start - a)
+            served += b
+        self.served = served
 
 
 def run_closed(workers, steps):
@@ -166,19 +195,79 @@ def run_closed(workers, steps):
     bar.wait()
     t0 = time.perf_counter()
     [t.join() for t in th]
-    return time.perf_counter() - t0
+    return time.perf_counter() - t0, sum(w.served for w in workers)
 
 
+# ---------------------------------------------------------------------------------------------------
+# single kernels at roofline shapes
+# ---------------------------------------------------------------------------------------------------
+def kernels_mode():
+    import workloads as wl
+    import workloads.graphs as G
+    import paper_2506_12598_amd as ec
+    pool = ec.Pool([(None, -1)])
+    B = wl.DT_BF16
+    rows = []
+
+    def time_first(model, batch=1):
+        h = ec.Model(pool, model, wl.to_storage(model.weights, model.dtype), max_batch=batch)
+        h.alloc_set([0] * model.n_groups)
+        ns = h.profile_group(0, 0, batch, 5)[0]
+        info = h.kernel_info(0, 0, batch)
+        h.free()
+        return ns, info
+
+    def mem(name, model, nbytes, batch=1):
+        ns, info = time_first(model, batch)
+        rows.append((name, info["kernel"], "hbm", nbytes / ns, HBM_PEAK_GBS, "GB/s", ns / 1e3))
+
+    def gemm(name, m_, k_, n_):
+        bb = G._Builder(name, B, 0, G.IN_SEQ, k_, 1, m_)
+        x = bb.linear(-1, n_, std=0.02)
+        bb.eltwise(x)                       # keeps the GEMM's output in the 16-bit type
+        ns, info = time_first(bb.finish())
+        tf = 2.0 * m_ * k_ * n_ / ns / 1e3
+        rows.append((f"{name} M{m_} N{n_} K{k_} tile {info['tile'][0]}x{info['tile'][1]}", info["kernel"], "mfma", tf,
+                     MFMA_PEAK_TFLOPS, "TFLOP/s", ns / 1e3))
+
+    # every case is a two-layer model whose first layer is the kernel under test (so that it writes the 16-bit type)
+    bb = G._Builder("ln", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.layernorm(-1); bb.softmax(x)
+    mem("LayerNorm, 480000 rows x 1024", bb.finish(), 480000 * 1024 * 4)
+    bb = G._Builder("sm", B, 0, G.IN_SEQ, 384, 1, 960000); x = bb.softmax(-1); bb.softmax(x)
+    mem("softmax, 960000 rows x 384", bb.finish(), 960000 * 384 * 4)
+    bb = G._Builder("mp", B, 0, G.IN_IMAGE, 64, 1792, 1792); x = bb.maxpool(-1, 3, 2, 1); bb.gap(x)
+    mem("max-pool 3x3 s2, 64 x 1792 x 1792", bb.finish(), 64 * 1792 * 1792 * 2 + 64 * 896 * 896 * 2)
+    bb = G._Builder("dw", B, 0, G.IN_IMAGE, 192, 1120, 1120); x = bb.conv(-1, 192, 3, 1, 1, G.ACT_RELU6, groups=192); bb.gap(x)
+    mem("depthwise 3x3 + ReLU6, 192 x 1120 x 1120", bb.finish(), 192 * 1120 * 1120 * 4)
+    bb = G._Builder("gap", B, 0, G.IN_IMAGE, 2048, 224, 224); x = bb.gap(-1); bb.softmax(x)
+    mem("global average pool, 4 x 2048 x 224 x 224", bb.finish(), 4 * 2048 * 224 * 224 * 2, batch=4)
+    bb = G._Builder("el", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.eltwise(-1, G.ACT_GELU, bias_std=1.0); bb.eltwise(x)
+    mem("bias + GELU, 480000 x 1024", bb.finish(), 480000 * 1024 * 4)
+    gemm("linear", 8192, 8192, 8192)
+    gemm("linear", 4096, 4096, 4096)
+    gemm("BERT-large FFN1 b4", 1536, 1024, 4096)
+    gemm("BERT-large FFN2 b4", 1536, 4096, 1024)
+    pool.destroy()
+    print(f"{'case':62s} {'kernel':18s} {'bound':5s} {'achieved':>10s} {'peak':>8s} {'unit':8s} {'frac':>6s} {'us/launch':>10s}")
+    for name, kern, bound, ach, peak, unit, us in rows:
+        print(f"{name:62s} {kern:18s} {bound:5s} {ach:10.1f} {peak:8.0f} {unit:8s} {ach / peak:6.3f} {us:10.1f}")
+
+
+# ---------------------------------------------------------------------------------------------------
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", type=int, default=1, choices=[1, 2, 3, 4], help="co-location mix (1 = headline workload)")
     ap.add_argument("--depth", type=int, default=2, help="requests each worker keeps in flight")
     ap.add_argument("--window", type=float, default=10.0, help="seconds of open-loop Poisson load per policy (0 = skip)")
-    ap.add_argument("--rate", type=float, default=200.0, help="Poisson arrivals per second per model")
+    ap.add_argument("--rate", type=float, default=None, help="Poisson arrivals/s per model (default: 200 for config 1, "
+                                                             "else 70%% of the measured closed-loop rate)")
+    ap.add_argument("--switch-max", type=int, default=14)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--policy", default="eclip", choices=["eclip", "unpart_a", "unpart_b"], help="policy of the timed region")
+    ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; co-located models are independent workers and would be "
@@ -190,40 +279,73 @@ def main():
     import paper_2506_12598_amd as ec
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.init()
+    if args.kernels:
+        kernels_mode()
+        return
     time.sleep(0.5)
     idle_w = PowerSampler().read()          # board power before any kernel of this process has run
 
-    models = wl.config_models(1)
+    cfg = args.config
+    steps = args.steps if args.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 30}[cfg]
+    warmup = args.warmup if args.warmup is not None else {1: 200, 2: 100, 3: 30, 4: 3}[cfg]
+    configs = [32, 64, 128, 192, 256] if cfg != 4 else [32, 64, 96, 128, 160, 192, 224, 256]
+    models = wl.config_models(cfg)
     n_w = len(models)
-    # pool: id 0 = shared unmasked stream; ids 1..n_w = one private unmasked stream per worker (policy
-    # unpart_b); then for worker w the 5 masked streams, laid out from opposite ends of the CU range
+    if cfg == 3:
+        rng = np.random.default_rng(77)
+        batches = [[int(b) for b in rng.integers(1, 9, size=64)] for _ in models]
+    elif cfg == 4:
+        batches = [[4]] * 3 + [[8]]
+    else:
+        batches = [[1]] * n_w
+    prof_batch = [max(1, int(round(np.mean(b)))) for b in batches]
+
+    # ---- profiling pool: every configuration of every worker, laid out per worker as in Sec. III-A
+    masks = []
+    prof_id = {}
+    for w in range(n_w):
+        for ci, c in enumerate(configs):
+            prof_id[(w, ci)] = len(masks)
+            masks.append((ec.eclip_mask_layout(256, 32, n_w, w, c // 32), w))
+    prof_pool = ec.Pool(masks)
+    workers = [Worker(ec, torch, prof_pool, m, i, args.depth, batches[i]) for i, m in enumerate(models)]
+    log(f"config {cfg}: loaded {n_w} models, profiling pool of {len(masks)} masked streams")
+
+    # ---- latency-vs-CU tables (Sec. III-B profiling), the measured cost of a switch, and the allocation.
+    # The GPU serves one queue per compute pipe at a time (4 pipes), so at most 4 masked streams may be in use:
+    # each worker is limited to 4 // n_w distinct configurations (at least one).
+    t0 = time.perf_counter()
+    beta, nk = [], []
+    for w, wk in enumerate(workers):
+        rows, counts = [], []
+        for g in range(wk.model.n_groups):
+            rows.append([int(sum(wk.h.profile_group(g, prof_id[(w, ci)], batch=prof_batch[w], iters=10 if cfg < 4 else 3)))
+                         for ci in range(len(configs))])
+            counts.append(wk.h.group_size(g))
+        beta.append(rows); nk.append(counts)
+    same_ns, pooled_ns, _ = prof_pool.bench_switch(0, 1, 2000, with_create=False)
+    switch_cost_ns = max(0, int(pooled_ns - same_ns))
+    max_configs = max(1, 4 // n_w)
+    assign, objective, switches = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, max_configs=max_configs,
+                                                       switch_cost_ns=switch_cost_ns)
+    log(f"profiled in {time.perf_counter() - t0:.1f}s; switch cost {switch_cost_ns} ns; allocation (CUs) "
+        f"{[[configs[c] for c in a] for a in assign]} switches {switches}")
+
+    # ---- serving pool: id 0 = shared unmasked stream (policy unpart_a); ids 1..n_w = one private unmasked stream per
+    # worker (policy unpart_b); then only the masked streams the allocation uses, created back to back so that they
+    # land on distinct pipes
     masks = [(None, -1)] + [(None, w) for w in range(n_w)]
     mask_id = {}
     for w in range(n_w):
-        for ci, c in enumerate(CONFIGS):
-            mask_id[(w, ci)] = len(masks)
-            masks.append((ec.eclip_mask_layout(256, 32, n_w, w, c // 32), w))
+        for c in sorted(set(assign[w])):
+            mask_id[(w, c)] = len(masks)
+            masks.append((ec.eclip_mask_layout(256, 32, n_w, w, configs[c] // 32), w))
     pool = ec.Pool(masks)
-    workers = [Worker(ec, torch, pool, m, i, args.depth) for i, m in enumerate(models)]
-    log(f"loaded {n_w} models, pool of {len(masks)} streams")
-
-    # ---- latency-vs-CU tables (Sec. III-B profiling) and the allocation
-    t0 = time.perf_counter()
-    beta, nk, per_kernel = [], [], []
-    for w, wk in enumerate(workers):
-        rows, counts, pk = [], [], []
-        for g in range(wk.model.n_groups):
-            row = []
-            for ci in range(len(CONFIGS)):
-                ns = wk.h.profile_group(g, mask_id[(w, ci)], batch=1, iters=15)
-                row.append(int(sum(ns)))
-                if ci == len(CONFIGS) - 1:
-                    pk.extend(ns)
-            rows.append(row)
-            counts.append(wk.h.group_size(g))
-        beta.append(rows); nk.append(counts); per_kernel.append(pk)
-    assign, objective, switches = ec.eclip_alloc_solve(256, CONFIGS, nk, beta, 14)
-    log(f"profiled in {time.perf_counter() - t0:.1f}s; allocation {assign} switches {switches}")
+    pipes = [pool.pipe(i) for i in range(1 + n_w, len(masks))]
+    assert len(set(pipes)) == len(pipes) or len(pipes) > 4, f"serving streams share a pipe: {pipes}"
+    for wk in workers:
+        wk.h.rebind(pool)
+    prof_pool.destroy()
     tables = {
         "eclip": [[mask_id[(w, c)] for c in assign[w]] for w in range(n_w)],
         "unpart_a": [[0] * m.n_groups for m in models],
@@ -234,30 +356,32 @@ def main():
         for wk, t in zip(workers, tables[name]):
             wk.h.alloc_set(t)
 
-    # ---- closed-loop throughput: the timed region
+    # ---- closed-loop throughput: the timed region is the last policy run
     closed = {}
     order = [p for p in ("unpart_a", "unpart_b", "eclip") if p != args.policy] + [args.policy]
     for pol in order:
         set_policy(pol)
-        run_closed(workers, args.warmup)
+        run_closed(workers, warmup)
         torch.cuda.synchronize()
-        dt = run_closed(workers, args.steps)
+        dt, served = run_closed(workers, steps)
         torch.cuda.synchronize()
-        closed[pol] = {"inferences_per_s": n_w * args.steps / dt, "ms_per_step": 1e3 * dt / args.steps}
-        log(f"closed loop {pol}: {closed[pol]['inferences_per_s']:.0f} inf/s")
+        closed[pol] = {"inferences_per_s": served / dt, "ms_per_step": 1e3 * dt / steps}
+        log(f"closed loop {pol}: {closed[pol]['inferences_per_s']:.0f} inf/s, {closed[pol]['ms_per_step']:.3f} ms/step")
     value = closed[args.policy]["inferences_per_s"]
     ms_per_step = closed[args.policy]["ms_per_step"]
 
-    # ---- parity spot check in this launch configuration
-    from_gpu = workers[0].d_out[0].cpu().numpy().astype(np.float64)
+    # ---- parity spot check in this launch configuration (last request of worker 0)
+    last_b = batches[0][(steps - 1) % len(batches[0])]
+    from_gpu = workers[0].d_out[(steps - 1) % args.depth][:last_b].cpu().numpy().astype(np.float64)
 
     # ---- open loop: Poisson arrivals, p99 latency, energy
     open_res = {}
     if args.window > 0:
         sampler = PowerSampler()
+        rate = args.rate if args.rate is not None else (200.0 if cfg == 1 else 0.7 * 1e3 / ms_per_step)
         for pol in ("unpart_a", "unpart_b", "eclip"):
             set_policy(pol)
-            arr = [wl.poisson_arrivals(args.rate, args.window, i) for i in range(n_w)]
+            arr = [wl.poisson_arrivals(rate, args.window, i) for i in range(n_w)]
             lats = [[] for _ in workers]
             sampler.start()
             t_start = time.perf_counter() + 0.05
@@ -267,69 +391,83 @@ def main():
             t_end = time.perf_counter()
             sampler.stop()
             allv = np.concatenate([np.array(l) for l in lats])
+            served = sum(wk.served for wk in workers)
             e = sampler.energy_j(t_start, t_end)
             open_res[pol] = {
-                "offered_per_s": args.rate * n_w,
-                "completed": int(allv.size),
-                "inferences_per_s": float(allv.size / (t_end - t_start)),
+                "offered_requests_per_s": rate * n_w,
+                "completed_requests": int(allv.size),
+                "inferences_per_s": float(served / (t_end - t_start)),
                 "p50_latency_ms": float(np.percentile(allv, 50) * 1e3),
                 "p99_latency_ms": float(np.percentile(allv, 99) * 1e3),
+                "p99_latency_ms_per_model": [float(np.percentile(np.array(l), 99) * 1e3) for l in lats],
                 "avg_power_w": None if e is None else e / (t_end - t_start),
-                "inferences_per_joule": None if e is None else float(allv.size / e),
+                "inferences_per_joule": None if e is None else float(served / e),
             }
-            log(f"open loop {pol}: p99 {open_res[pol]['p99_latency_ms']:.3f} ms, "
-                f"{open_res[pol]['inferences_per_joule']} inf/J")
+            log(f"open loop {pol}: p99 {open_res[pol]['p99_latency_ms']:.3f} ms, {open_res[pol]['inferences_per_joule']} inf/J")
         open_res["idle_power_w"] = idle_w
         open_res["power_source"] = sampler.source
 
     # ---- roofline of the dominant kernel: HIP-event timings on the stream the kernels run on.  Each layer of each
     # model is timed on that worker's unpartitioned stream (8 back-to-back launches per sample, see
-    # eclip_profile_group); layers are grouped by the kernel function that runs them and the function with the
-    # largest total time is reported against the roofline that bounds it at these shapes (HBM: the convolutions
-    # of a batch-1 ResNet-18 have 43-230 FLOP/B, below the 315 FLOP/B ridge of the matrix cores).
+    # eclip_profile_group); layers are grouped by the kernel function that runs them; the matrix-core function
+    # with the largest launch-weighted time is reported against the roofline that bounds its work.
     set_policy("unpart_b")
     per_kernel = {}
     for w, wk in enumerate(workers):
         ns_all = []
         for g in range(wk.model.n_groups):
-            ns_all.extend(wk.h.profile_group(g, 1 + w, batch=1, iters=30))
-        lb = conv_gemm_bytes(wk.model, 1)
+            ns_all.extend(wk.h.profile_group(g, 1 + w, batch=prof_batch[w], iters=20 if cfg < 4 else 3))
+        work = gemm_work(wk.model, prof_batch[w])
         for li, ns in enumerate(ns_all):
-            info = wk.h.kernel_info(li, 1 + w, 1)
+            info = wk.h.kernel_info(li, 1 + w, prof_batch[w])
             e = per_kernel.setdefault(info["kernel"], {"ns": 0.0, "bytes": 0.0, "flops": 0.0, "launches": 0, "layers": 0})
             e["ns"] += ns
             e["launches"] += info["launches"]
             e["layers"] += 1
-            if lb[li] is not None:
-                e["bytes"] += lb[li][0]
-                e["flops"] += lb[li][1]
+            if work[li] is not None:
+                e["bytes"] += work[li][0]
+                e["flops"] += work[li][1]
+    total_ns = sum(v["ns"] for v in per_kernel.values())
     # a layer whose K is cut over the grid runs two kernels (GEMM + slice sum): its time is attributed per launch
     dom = max((k for k in per_kernel if per_kernel[k]["bytes"] > 0),
               key=lambda k: per_kernel[k]["ns"] * per_kernel[k]["layers"] / per_kernel[k]["launches"])
     d = per_kernel[dom]
-    achieved = d["bytes"] / d["ns"]          # bytes per ns = GB/s
-    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": dom,
-                "layers_per_step": d["layers"], "launches_per_step": d["launches"], "avg_layer_us": d["ns"] / d["layers"] / 1e3,
-                "avg_bytes_per_layer": d["bytes"] / d["layers"], "achieved_tflops": d["flops"] / d["ns"] / 1e3,
-                "time_share_by_kernel": {k: v["ns"] / sum(x["ns"] for x in per_kernel.values()) for k, v in per_kernel.items()}}
+    ai = d["flops"] / d["bytes"]
+    if ai > RIDGE:
+        ach, peak, unit, bound = d["flops"] / d["ns"] / 1e3, MFMA_PEAK_TFLOPS, "TFLOP/s", "mfma"
+    else:
+        ach, peak, unit, bound = d["bytes"] / d["ns"], HBM_PEAK_GBS, "GB/s", "hbm"
+    roofline = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak, "traffic": None,
+                "kernel": dom, "flop_per_byte": ai, "layers_per_step": d["layers"], "launches_per_step": d["launches"],
+                "avg_layer_us": d["ns"] / d["layers"] / 1e3, "avg_bytes_per_layer": d["bytes"] / d["layers"],
+                "achieved_tflops": d["flops"] / d["ns"] / 1e3, "achieved_gbs": d["bytes"] / d["ns"],
+                "time_share_by_kernel": {k: v["ns"] / total_ns for k, v in per_kernel.items()}}
 
     # ---- CPU oracle on the host cores, same models and inputs
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import forward as orc
-        orc.run_model(models[0], workers[0].x)              # builds / warms the library
+        x0 = workers[0].x[:last_b]
+        exp0 = orc.run_model(models[0], x0)              # also builds / warms the library
         t0 = time.perf_counter()
-        n = 0
-        exp0 = None
-        while time.perf_counter() - t0 < 10.0 or n < n_w:
-            y = orc.run_model(models[n % n_w], workers[n % n_w].x)
-            if n == 0:
-                exp0 = y
-            n += 1
-        dt = time.perf_counter() - t0
-        cpu = {"value": n / dt, "unit": "inferences/s", "cores": orc.num_threads(), "kind": "oracle",
-               "sample": f"{n} full forward passes of the {n_w} models (batch 1), {dt:.1f} s"}
+        n = served = 0
+        if cfg < 4:
+            while time.perf_counter() - t0 < 10.0 or n < n_w:
+                b = batches[n % n_w][0]
+                orc.run_model(models[n % n_w], workers[n % n_w].x[:b])
+                served += b
+                n += 1
+            dt = time.perf_counter() - t0
+            sample = f"{n} full forward passes cycling over the {n_w} models, {dt:.1f} s"
+        else:
+            # 986 GFLOP per BERT-large request: time 2 of the 24 encoder layers and the ResNet at batch 1 and
+            # scale by layers and batch
+            sl = wl.bert(2, 1024, 16, 4096, 384, seed=9, dtype=wl.DT_BF16)
+            t1 = time.perf_counter(); orc.run_model(sl, wl.make_input(sl, 1)); t_b = (time.perf_counter() - t1) * 12
+            t1 = time.perf_counter(); orc.run_model(models[3], workers[3].x[:1]); t_r = time.perf_counter() - t1
+            served, dt = 3 * 4 + 8, 3 * 4 * t_b + 8 * t_r
+            sample = "extrapolated: 2 of 24 BERT-large layers at batch 1 (x12 layers x4 batch x3 models) + ResNet-152 at batch 1 (x8)"
+        cpu = {"value": served / dt, "unit": "inferences/s", "cores": orc.num_threads(), "kind": "oracle", "sample": sample}
         err = float(np.abs(from_gpu - exp0).max() / (exp0.max() - exp0.min()))
         assert err <= 2e-2, f"GPU logits differ from the oracle: {err}"
         log(f"cpu oracle {cpu['value']:.2f} inf/s on {cpu['cores']} threads; GPU vs oracle err/range {err:.2e}")
@@ -338,15 +476,16 @@ def main():
         wk.h.free()
     pool.destroy()
 
+    dts = sorted({wl.DT_NAMES[m.dtype] for m in models})
     out = {
-        "metric": "co-located inferences/s (closed loop, 2 workers) on 1xMI355X",
-        "value": value, "unit": "inferences/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": f"co-located inferences/s (closed loop, {n_w} workers) on 1xMI355X",
+        "value": value, "unit": "inferences/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "2x ResNet-18-style bf16 batch 1 3x224x224, 4 kernel groups each, CU-mask pool "
-                               "{32,64,128,192,256} per worker, switchMax 14", "policy": args.policy,
-                   "inflight_per_worker": args.depth, "allocation_cus": [[CONFIGS[c] for c in a] for a in assign],
-                   "switches": switches},
+        "dtype": "+".join(dts), "data": "synthetic",
+        "config": {"workload": WORKLOADS[cfg] + f", CU-mask pool {configs} per worker, switchMax {args.switch_max}",
+                   "policy": args.policy, "inflight_per_worker": args.depth,
+                   "allocation_cus": [[configs[c] for c in a] for a in assign], "switches": switches,
+                   "max_configs_per_worker": max_configs, "switch_cost_ns": switch_cost_ns},
         "closed_loop": closed,
         "open_loop_poisson": open_res,
         "roofline": roofline,

@@ -88,6 +88,24 @@ eclip_status eclip_pool_device_cus(const eclip_pool *pool, uint32_t *n_cu);
 /* Destroys every stream.  ESTATE while models loaded on the pool are still alive. */
 eclip_status eclip_pool_destroy(eclip_pool *pool);
 
+/* Hardware-queue sharing (Sec. II-C, Observation 2, as measured on MI355X).  Every masked stream owns an
+ * HSA queue; the queues are dealt to the compute pipes of the command processor in creation order, and a
+ * pipe serves one queue at a time: a queue that sits on a barrier (waiting for an event of another stream)
+ * keeps its pipe, so two streams of one pipe that are in use in the same period slow each other down by
+ * 3-5x (measured: two co-located ResNet-18 workers, 193 us per step on 4 distinct pipes, 600-930 us with
+ * two active streams on one pipe).  *pipe receives the creation rank of the masked stream among the
+ * pool's masked streams modulo ECLIP_N_PIPES, UINT32_MAX for an unmasked stream (it uses one of the
+ * runtime's shared queues).  Tables installed with eclip_alloc_set on co-located models should use streams of
+ * pairwise different pipes. */
+#define ECLIP_N_PIPES 4u
+eclip_status eclip_pool_pipe(const eclip_pool *pool, uint32_t mask_id, uint32_t *pipe);
+
+/* Observation 2's experiment: a chain of `iters` dependent, trivially short kernels dealt round-robin to the
+ * n pool entries mask_ids[0..n), each kernel waiting for its predecessor through an event.  *ns_per_kernel
+ * receives the wall-clock time per kernel.  Host pointers. */
+eclip_status eclip_bench_streams(eclip_pool *pool, const uint32_t *mask_ids, uint32_t n, uint32_t iters,
+                                 double *ns_per_kernel);
+
 /* Host-only helper: the per-worker mask layout of Sec. III-A.  The device's CUs are cut into
  * n_granules = total_cus / granule equal granules (the paper: 4 shader engines of 15 CUs).
  * Worker `worker` of `n_workers` claims granules in a fixed order chosen so that two workers
@@ -176,6 +194,12 @@ eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_desc *desc, co
 /* ESTATE while requests are in flight. */
 eclip_status eclip_model_free(eclip_model *model);
 
+/* Move a loaded model to another pool of the same device (weights and buffers stay where they are; only the
+ * streams change).  The group -> stream table is cleared: call eclip_alloc_set again.  Lets a serving pool of
+ * a few streams on distinct pipes replace the wide pool used for profiling.  ESTATE while requests are in
+ * flight, EINVAL for a pool on another device. */
+eclip_status eclip_model_rebind(eclip_model *model, eclip_pool *new_pool);
+
 /* Install the lookup table group -> pooled stream (the optimizer's output, Sec. III-B).  Takes
  * effect for the next eclip_submit; no stream is created or re-masked.  EINVAL: n_groups differs
  * from the model's, unknown mask id. */
@@ -263,6 +287,15 @@ typedef struct {
     const uint64_t *alpha_ppm;
     uint32_t n_alpha;
     uint32_t granule;
+    /* Extensions, 0 = the model as printed.
+     * max_configs:    a worker may use at most this many distinct configurations in one request.  Every
+     *                 (worker, configuration) pair in use is one pooled stream, and only a few streams run
+     *                 without oversubscribing the hardware queues (Sec. II-C, Observation 2: 7 on MI50;
+     *                 on MI355X 4, one per compute pipe, see eclip_bench_streams).
+     * switch_cost_ns: added to a worker's solo time at every configuration switch (factor (iii) of
+     *                 Sec. III-B, which the printed model bounds through switch_max only). */
+    uint32_t max_configs;
+    uint64_t switch_cost_ns;
 } eclip_alloc_problem;
 
 /* Exact minimiser.  cfg_idx_out[sum units] receives the configuration index of every unit

@@ -28,6 +28,16 @@ Readings where the text is ambiguous (each is a mode or rule below, never silent
   Ties: smaller sum of CU averages first (fewer CUs), then the lexicographically
   smallest vector of configuration indices, worker-major, unit order.
 
+Two extensions beyond the printed model, both off (0) by default so that the paper's model is the
+special case:
+  max_configs  a worker may use at most this many *distinct* configurations in one request.  It is the
+               stream-pool limit of Sec. III-A turned into a constraint: every (worker, configuration)
+               pair in use is one pooled stream, and the GPU runs only a few streams without
+               oversubscribing its hardware queues (7 on the paper's MI50; 4 on MI355X, one per pipe).
+  switch_cost  nanoseconds added to a worker's solo time per configuration switch: factor (iii) of
+               Sec. III-B ("the overhead of CU configuration switches"), which the paper bounds with the
+               budget only; with a cost the optimizer stops switching for gains smaller than a switch.
+
 All arithmetic is exact (Python integers).  With D = lcm_w(N_w), S_D = D * sum_w
 CUAverage_w is an integer, and the objective is compared through the integer
   EXCESS/LITERAL:  (sum_w B_w) * (T*D + Ov_D)        (= objective * T * D)
@@ -70,6 +80,10 @@ def evaluate(p, assign: Sequence[Sequence[int]]):
     switches = [switch_total(a) for a in assign]
     if any(s > p.switch_max for s in switches):
         return None
+    max_configs = getattr(p, "max_configs", 0)
+    if max_configs and any(len(set(a)) > max_configs for a in assign):
+        return None
+    switch_cost = getattr(p, "switch_cost", 0)
     T = p.total_cus
     n_tot = [sum(w.n_kernels) for w in p.workers]
     D = 1
@@ -78,7 +92,7 @@ def evaluate(p, assign: Sequence[Sequence[int]]):
     sum_b = 0
     s_d = 0
     for w, a, n_w in zip(p.workers, assign, n_tot):
-        b_w = sum(w.beta[g][c] for g, c in enumerate(a))
+        b_w = sum(w.beta[g][c] for g, c in enumerate(a)) + switch_cost * switch_total(a)
         u_w = sum(w.n_kernels[g] * p.configs[c] for g, c in enumerate(a))
         sum_b += b_w
         s_d += u_w * (D // n_w)

@@ -64,7 +64,7 @@ class eclip_alloc_problem(C.Structure):
                 ("n_workers", C.c_uint32), ("units_of_worker", C.POINTER(C.c_uint32)),
                 ("n_kernels", C.POINTER(C.c_uint32)), ("beta", C.POINTER(C.c_uint64)), ("switch_max", C.c_uint32),
                 ("overlap_mode", C.c_uint32), ("alpha_ppm", C.POINTER(C.c_uint64)), ("n_alpha", C.c_uint32),
-                ("granule", C.c_uint32)]
+                ("granule", C.c_uint32), ("max_configs", C.c_uint32), ("switch_cost_ns", C.c_uint64)]
 
 
 EXPORTS = {
@@ -73,6 +73,9 @@ EXPORTS = {
     "eclip_pool_stream": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p), C.POINTER(C.c_uint32)]),
     "eclip_pool_device_cus": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
     "eclip_pool_destroy": (C.c_int, [C.c_void_p]),
+    "eclip_pool_pipe": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]),
+    "eclip_bench_streams": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32), C.c_uint32, C.c_uint32, C.POINTER(C.c_double)]),
+    "eclip_model_rebind": (C.c_int, [C.c_void_p, C.c_void_p]),
     "eclip_mask_layout": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                     C.POINTER(C.c_uint32), C.c_uint32]),
     "eclip_pool_probe": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32)]),
@@ -164,6 +167,16 @@ class Pool:
         check(lib.eclip_pool_device_cus(self.handle, C.byref(n)))
         return n.value
 
+    def pipe(self, mask_id: int) -> int:
+        n = C.c_uint32()
+        check(lib.eclip_pool_pipe(self.handle, mask_id, C.byref(n)))
+        return n.value
+
+    def bench_streams(self, mask_ids: Sequence[int], iters: int) -> float:
+        out = C.c_double()
+        check(lib.eclip_bench_streams(self.handle, _u32(mask_ids), len(mask_ids), iters, C.byref(out)))
+        return out.value
+
     def probe(self, mask_id: int, n_blocks: int) -> np.ndarray:
         out = np.zeros(n_blocks, np.uint32)
         check(lib.eclip_pool_probe(self.handle, mask_id, n_blocks, out.ctypes.data_as(C.POINTER(C.c_uint32))))
@@ -219,6 +232,10 @@ class Model:
                                    storage.ctypes.data_as(C.c_void_p), storage.nbytes, 0, C.byref(self.handle)))
         self.n_groups = model.n_groups
 
+    def rebind(self, pool: "Pool"):
+        check(lib.eclip_model_rebind(self.handle, pool.handle))
+        self.pool = pool
+
     def alloc_set(self, mask_id_of_group: Sequence[int]):
         check(lib.eclip_alloc_set(self.handle, _u32(mask_id_of_group), len(mask_id_of_group)))
 
@@ -259,7 +276,8 @@ class Model:
 # ---- allocator -------------------------------------------------------------------------------------
 def eclip_alloc_solve(total_cus: int, configs: Sequence[int], n_kernels: Sequence[Sequence[int]],
                       beta: Sequence[Sequence[Sequence[int]]], switch_max: int, overlap_mode: int = OVERLAP_EXCESS,
-                      alpha_ppm: Optional[Sequence[int]] = None, granule: int = 1):
+                      alpha_ppm: Optional[Sequence[int]] = None, granule: int = 1, max_configs: int = 0,
+                      switch_cost_ns: int = 0):
     """n_kernels[w][g], beta[w][g][c] -> (cfg_idx[w][g], objective:int, switches[w])."""
     units = [len(x) for x in n_kernels]
     flat_n = [v for w in n_kernels for v in w]
@@ -270,7 +288,7 @@ def eclip_alloc_solve(total_cus: int, configs: Sequence[int], n_kernels: Sequenc
     bb = (C.c_uint64 * len(flat_b))(*[int(v) for v in flat_b])
     ap = (C.c_uint64 * len(alpha_ppm))(*[int(v) for v in alpha_ppm]) if alpha_ppm else None
     p = eclip_alloc_problem(total_cus, cfg, len(configs), len(units), uo, nk, bb, switch_max, overlap_mode,
-                            ap, len(alpha_ppm) if alpha_ppm else 0, granule)
+                            ap, len(alpha_ppm) if alpha_ppm else 0, granule, max_configs, switch_cost_ns)
     out = (C.c_uint32 * max(1, sum(units)))()
     obj = eclip_u128()
     sw = (C.c_uint32 * max(1, len(units)))()

@@ -14,6 +14,7 @@
 //      is still reachable exactly.
 #include <algorithm>
 #include <cstdint>
+#include <functional>
 #include <limits>
 #include <map>
 #include <numeric>
@@ -45,6 +46,8 @@ struct WorkerDP {
     std::vector<uint32_t> n;                  // kernels per unit
     std::vector<uint32_t> cq;                 // config CU counts divided by their gcd
     const uint64_t *beta = nullptr;           // [G][C]
+    uint64_t switch_cost = 0;                 // added to the latency at every configuration switch
+    std::vector<int> allowed;                 // configurations this run may use (all, or a subset)
     uint32_t umax = 0;                        // largest reduced CU sum
     // h[g][c_prev][s_left][u] = min latency of units g..G-1 given unit g-1 used c_prev, s_left switches
     // remain and the units g..G-1 must add up to reduced CU sum u.  g = 0 uses c_prev = C ("none").
@@ -54,6 +57,7 @@ struct WorkerDP {
     {
         return (((size_t)g * (C + 1) + cp) * (SM + 1) + sl) * (umax + 1) + u;
     }
+    bool is_allowed(int c) const { return std::find(allowed.begin(), allowed.end(), c) != allowed.end(); }
     size_t states() const { return (size_t)(G + 1) * (C + 1) * (SM + 1) * ((size_t)umax + 1); }
 
     void run()
@@ -64,18 +68,18 @@ struct WorkerDP {
         for (int g = G - 1; g >= 0; --g)
             for (int cp = 0; cp <= C; ++cp) {
                 if (g == 0 && cp != C) continue;
-                if (g > 0 && cp == C) continue;
+                if (g > 0 && (cp == C || !is_allowed(cp))) continue;
                 for (int sl = 0; sl <= SM; ++sl)
                     for (uint32_t u = 0; u <= rem_max[g]; ++u) {
                         uint64_t best = INF;
-                        for (int c = 0; c < C; ++c) {
+                        for (int c : allowed) {
                             const bool sw = (g > 0 && c != cp);
                             if (sw && sl == 0) continue;
                             const uint32_t du = n[g] * cq[c];
                             if (du > u) continue;
                             const uint64_t t = h[idx(g + 1, c, sl - (sw ? 1 : 0), u - du)];
                             if (t == INF) continue;
-                            const uint64_t v = t + beta[(size_t)g * C + c];
+                            const uint64_t v = t + beta[(size_t)g * C + c] + (sw ? switch_cost : 0);
                             if (v < best) best = v;
                         }
                         h[idx(g, cp, sl, u)] = best;
@@ -90,13 +94,13 @@ struct WorkerDP {
         uint32_t sw_count = 0;
         for (int g = 0; g < G; ++g) {
             const uint64_t target = h[idx(g, cp, sl, u)];
-            for (int c = 0; c < C; ++c) {
+            for (int c : allowed) {                 // ascending: the first match is the lexicographic minimum
                 const bool sw = (g > 0 && c != cp);
                 if (sw && sl == 0) continue;
                 const uint32_t du = n[g] * cq[c];
                 if (du > u) continue;
                 const uint64_t t = h[idx(g + 1, c, sl - (sw ? 1 : 0), u - du)];
-                if (t == INF || t + beta[(size_t)g * C + c] != target) continue;
+                if (t == INF || t + beta[(size_t)g * C + c] + (sw ? switch_cost : 0) != target) continue;
                 out[g] = (uint32_t)c;
                 if (sw) { --sl; ++sw_count; }
                 cp = c;
@@ -130,6 +134,25 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
             if (p->alpha_ppm[i] < p->alpha_ppm[i - 1]) return "alpha_ppm must be non-decreasing";
     }
     const int W = (int)p->n_workers, C = (int)p->n_configs;
+    // configuration subsets a worker may draw from: all of them, or every subset of at most max_configs
+    std::vector<std::vector<int>> subsets;
+    {
+        const int K = (p->max_configs == 0 || (int)p->max_configs >= C) ? C : (int)p->max_configs;
+        if (K == C) {
+            std::vector<int> all(C);
+            std::iota(all.begin(), all.end(), 0);
+            subsets.push_back(all);
+        } else {
+            std::vector<int> cur;
+            // subsets of exactly K configurations (smaller ones are contained in them), in lexicographic order
+            std::function<void(int)> rec = [&](int start) {
+                if ((int)cur.size() == K) { subsets.push_back(cur); return; }
+                for (int c = start; c < C; ++c) { cur.push_back(c); rec(c + 1); cur.pop_back(); }
+            };
+            rec(0);
+            if (subsets.size() > 4096) { *limit = true; return "too many configuration subsets (max_configs)"; }
+        }
+    }
     uint32_t cg = 0;
     for (int c = 0; c < C; ++c) cg = std::gcd(cg, p->configs[c]);
 
@@ -146,6 +169,7 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
         d.SM = (int)std::min<uint32_t>(p->switch_max, (uint32_t)(d.G - 1));
         d.n.assign(p->n_kernels + unit0, p->n_kernels + unit0 + d.G);
         d.beta = p->beta + unit0 * C;
+        d.switch_cost = p->switch_cost_ns;
         d.cq.resize(C);
         for (int c = 0; c < C; ++c) d.cq[c] = p->configs[c] / cg;
         uint64_t nsum = 0, bmax = 0;
@@ -156,6 +180,10 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
             for (int c = 0; c < C; ++c) m = std::max(m, d.beta[(size_t)g * C + c]);
             if (bmax > INF - m) { *limit = true; return "latency sum overflows 64 bits"; }
             bmax += m;
+            if (g > 0) {
+                if (bmax > INF - p->switch_cost_ns) { *limit = true; return "latency sum overflows 64 bits"; }
+                bmax += p->switch_cost_ns;
+            }
         }
         if (beta_total_max > INF - bmax) { *limit = true; return "latency sum overflows 64 bits"; }
         beta_total_max += bmax;
@@ -176,17 +204,20 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
         const u128 fac = (u128)p->total_cus * D + smax;
         if (smax >> 62 || fac >> 63) { *limit = true; return "scaled CU sums exceed 62 bits"; }
     }
-    for (int w = 0; w < W; ++w) dp[w].run();
-
-    // per-worker fronts in the common scale: s = U_reduced * cg * (D / N_w)
+    // per-worker fronts in the common scale: s = U_reduced * cg * (D / N_w); with a subset limit the front is the
+    // Pareto union over the subsets
     std::vector<std::vector<Point>> front(W);
     std::vector<uint64_t> mult(W);
     for (int w = 0; w < W; ++w) {
         mult[w] = (uint64_t)cg * (D / Nw[w]);
         std::vector<Point> v;
-        for (uint32_t u = 0; u <= dp[w].umax; ++u) {
-            const uint64_t b = dp[w].f(u);
-            if (b != INF) v.push_back(Point{(uint64_t)u * mult[w], b});
+        for (const std::vector<int> &sub : subsets) {
+            dp[w].allowed = sub;
+            dp[w].run();
+            for (uint32_t u = 0; u <= dp[w].umax; ++u) {
+                const uint64_t b = dp[w].f(u);
+                if (b != INF) v.push_back(Point{(uint64_t)u * mult[w], b});
+            }
         }
         front[w] = prune(std::move(v));
     }
@@ -237,8 +268,14 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
             auto it = std::lower_bound(R[w + 1].begin(), R[w + 1].end(), need,
                                        [](const Point &x, const Point &y) { return x.s < y.s; });
             if (it == R[w + 1].end() || it->s != need.s || it->b != need.b) continue;
-            dp[w].rebuild((uint32_t)(a.s / mult[w]), cur.data(), &cur_sw);
-            if (!found || cur < best_assign) { best_assign = cur; best_sw = cur_sw; chosen = a; found = true; }
+            for (const std::vector<int> &sub : subsets) {
+                dp[w].allowed = sub;
+                dp[w].run();
+                const uint32_t u = (uint32_t)(a.s / mult[w]);
+                if (dp[w].f(u) != a.b) continue;
+                dp[w].rebuild(u, cur.data(), &cur_sw);
+                if (!found || cur < best_assign) { best_assign = cur; best_sw = cur_sw; chosen = a; found = true; }
+            }
         }
         if (!found) return "internal error: optimum not reconstructible";
         for (int g = 0; g < dp[w].G; ++g) cfg_out[unit0 + g] = best_assign[g];

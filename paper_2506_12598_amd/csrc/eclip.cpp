@@ -62,6 +62,7 @@ static bool trace_on()
 struct PoolStream {
     hipStream_t stream = nullptr;
     uint32_t n_cu = 0;
+    uint32_t pipe = UINT32_MAX;          // creation rank among the pool's masked streams, modulo ECLIP_N_PIPES
     std::vector<uint32_t> words;
     int32_t owner = -1;
 };
@@ -127,9 +128,11 @@ extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, u
     p->device = device;
     p->device_cus = cus;
     p->streams.resize(n_masks);
+    uint32_t n_masked = 0;
     for (uint32_t i = 0; i < n_masks; ++i) {
         PoolStream &s = p->streams[i];
         s.owner = masks[i].owner;
+        if (masks[i].n_words) s.pipe = n_masked++ % ECLIP_N_PIPES;
         hipError_t e;
         if (masks[i].n_words == 0) {
             s.n_cu = cus;
@@ -163,6 +166,52 @@ extern "C" eclip_status eclip_pool_device_cus(const eclip_pool *pool, uint32_t *
 {
     if (!pool || !n_cu) return fail(ECLIP_EINVAL, "null argument");
     *n_cu = pool->device_cus;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_pool_pipe(const eclip_pool *pool, uint32_t mask_id, uint32_t *pipe)
+{
+    if (!pool || !pipe) return fail(ECLIP_EINVAL, "null argument");
+    if (mask_id >= pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    *pipe = pool->streams[mask_id].pipe;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_bench_streams(eclip_pool *pool, const uint32_t *mask_ids, uint32_t n, uint32_t iters,
+                                            double *ns_per_kernel)
+{
+    if (!pool || !mask_ids || !ns_per_kernel) return fail(ECLIP_EINVAL, "null argument");
+    if (n == 0 || n > ECLIP_MAX_POOL_STREAMS) return fail(ECLIP_EINVAL, "n must be 1..%u", ECLIP_MAX_POOL_STREAMS);
+    if (iters == 0 || iters > 100000) return fail(ECLIP_EINVAL, "iters must be 1..100000");
+    for (uint32_t i = 0; i < n; ++i)
+        if (mask_ids[i] >= pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_ids[i]);
+    HIP_TRY(hipSetDevice(pool->device));
+    uint32_t *d = nullptr;
+    HIP_TRY(hipMalloc(&d, 256));
+    hipError_t e = hipMemset(d, 0, 256);
+    std::vector<hipEvent_t> ev(n, nullptr);
+    for (uint32_t i = 0; i < n && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming);
+    double result = 0.0;
+    for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {          // pass 0 warms every queue up
+        const uint32_t count = pass == 0 ? std::min<uint32_t>(iters, 4 * n) : iters;
+        const auto t0 = std::chrono::steady_clock::now();
+        for (uint32_t i = 0; i < count && e == hipSuccess; ++i) {
+            const hipStream_t cur = pool->streams[mask_ids[i % n]].stream;
+            if (i && n > 1) {
+                const hipStream_t prev = pool->streams[mask_ids[(i - 1) % n]].stream;
+                e = hipEventRecord(ev[i % n], prev);
+                if (e == hipSuccess) e = hipStreamWaitEvent(cur, ev[i % n], 0);
+            }
+            if (e == hipSuccess) e = launch_tick(d, cur);
+        }
+        for (uint32_t i = 0; i < n && e == hipSuccess; ++i) e = hipStreamSynchronize(pool->streams[mask_ids[i]].stream);
+        result = (double)std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now() - t0).count() / count;
+    }
+    for (hipEvent_t x : ev)
+        if (x) (void)hipEventDestroy(x);
+    (void)hipFree(d);
+    if (e != hipSuccess) return fail(ECLIP_EHIP, "stream bench failed: %s", hipGetErrorString(e));
+    *ns_per_kernel = result;
     return ECLIP_OK;
 }
 
@@ -650,6 +699,27 @@ extern "C" eclip_status eclip_model_free(eclip_model *model)
     free_model(model);
     std::lock_guard<std::mutex> lk(pool->mu);
     pool->n_models--;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_model_rebind(eclip_model *model, eclip_pool *new_pool)
+{
+    if (!model || !new_pool) return fail(ECLIP_EINVAL, "null argument");
+    if (new_pool->device != model->pool->device) return fail(ECLIP_EINVAL, "the new pool is on another device");
+    std::lock_guard<std::mutex> lk(model->mu);
+    if (model->inflight) return fail(ECLIP_ESTATE, "%u requests still in flight", model->inflight);
+    HIP_TRY(hipSetDevice(new_pool->device));
+    HIP_TRY(hipDeviceSynchronize());
+    eclip_pool *old = model->pool;
+    if (old != new_pool) {
+        { std::lock_guard<std::mutex> l2(old->mu); old->n_models--; }
+        { std::lock_guard<std::mutex> l2(new_pool->mu); new_pool->n_models++; }
+        model->pool = new_pool;
+    }
+    model->has_alloc = false;
+    model->mask_of_group.clear();
+    model->last_done = nullptr;
+    model->last_stream = nullptr;
     return ECLIP_OK;
 }
 

@@ -212,3 +212,30 @@ def test_wait_timeout_then_success():
             r.wait()
     finally:
         g.free()
+
+
+def test_pipes_rebind_and_stream_chain():
+    pool = shared_pool()
+    assert pool.pipe(0) == 2 ** 32 - 1                      # unmasked stream: one of the runtime's shared queues
+    assert [pool.pipe(i) for i in range(1, 6)] == [0, 1, 2, 3, 0]
+    t1 = pool.bench_streams([1], 200)
+    t4 = pool.bench_streams([1, 2, 3, 4], 200)
+    assert t1 > 0 and t4 > 0
+    # a model moves to a second pool and still computes the same logits
+    m = wl.resnet(18, seed=1, hw=64)
+    x = wl.make_input(m, 1)
+    g = GpuModel(m)
+    try:
+        ref = g.run(x, table=[1, 1, 2, 2])
+        small = ec.Pool([(ec.eclip_mask_layout(256, 32, 2, 0, 4), 0), (ec.eclip_mask_layout(256, 32, 2, 0, 2), 0)])
+        g.h.rebind(small)
+        with pytest.raises(ec.EclipError) as e:
+            g.run(x)                                         # the table was cleared by the move
+        assert e.value.status == ec.ESTATE
+        got = g.run(x, table=[0, 0, 1, 1])
+        assert np.abs(got - ref).max() <= 2e-2 * (ref.max() - ref.min())
+        g.h.rebind(pool)
+        small.destroy()
+        g.h.alloc_set([0, 0, 0, 0])
+    finally:
+        g.free()

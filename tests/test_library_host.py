@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 
 def solve_lib(p):
     return ec.eclip_alloc_solve(p.total_cus, p.configs, [w.n_kernels for w in p.workers], [w.beta for w in p.workers],
-                                p.switch_max, p.overlap_mode, p.alpha_ppm, p.granule)
+                                p.switch_max, p.overlap_mode, p.alpha_ppm, p.granule, p.max_configs, p.switch_cost)
 
 
 CASES = []
@@ -45,6 +45,24 @@ def test_solver_matches_exhaustive_oracle_bit_exact(seed, nw, units, configs, to
     assert got_assign == exp_assign
     assert got_obj == exp_obj
     assert got_sw == exp_sw
+
+
+EXT_CASES = [(seed, mc, sc, mode) for seed in range(8) for mc, sc in ((1, 0), (2, 0), (0, 700), (2, 3000), (1, 50))
+             for mode in (oa.OVERLAP_EXCESS, oa.OVERLAP_TABLE)]
+
+
+@pytest.mark.parametrize("seed,max_configs,switch_cost,mode", EXT_CASES)
+def test_solver_extensions_match_exhaustive_oracle_bit_exact(seed, max_configs, switch_cost, mode):
+    for units, configs, total, sm, shape in (([3, 3], [32, 64, 128, 192, 256], 256, 2, "scaling"),
+                                             ([2, 2, 2], [15, 30, 45, 60], 60, 1, "random"),
+                                             ([4, 2], [32, 64, 128], 128, 3, "ties")):
+        p = wl.random_problem(300 + seed, len(units), units, configs, total, sm, mode, shape)
+        p.max_configs, p.switch_cost = max_configs, switch_cost
+        exp = oa.solve_exhaustive(p)
+        got = solve_lib(p)
+        assert got[0] == exp[0] and got[1] == exp[1] and got[2] == exp[2]
+        if max_configs:
+            assert all(len(set(a)) <= max_configs for a in got[0])
 
 
 def test_solver_hand_worked_example():

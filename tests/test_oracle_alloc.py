@@ -120,3 +120,25 @@ def test_table_mode_uses_excess_granules():
     # (64,64): excess 64 -> granule 2 -> 100*(1.9) = 190 ; (32,64): excess 32 -> 150*1.3 = 195 ; (32,32): 200
     assign, num, _ = oa.solve_exhaustive(p)
     assert assign == [[1], [1]] and num == 100 * 1_900_000
+
+
+def test_extension_max_configs_and_switch_cost_hand_checked():
+    # worked instance again (EXCESS): optimum without limits is (30,30 | 30) = 28800 with no switch at all, so neither
+    # extension changes it ...
+    p = worked_problem(oa.OVERLAP_EXCESS)
+    p.max_configs, p.switch_cost = 1, 1000
+    assert oa.solve_exhaustive(p)[0] == [[1, 1], [1]]
+    # ... LITERAL optimum (30,15 | 45) = 220 * 255 = 56100 uses one switch: a switch cost of 10 ns makes it
+    # (220 + 10) * 255 = 58650, worse than the best switch-free choice:
+    #   (30,30 | 45): 210 * (120 + 150) = 56700 ; (30,30 | 30): 240 * 240 = 57600 ; (15,15 | 45): 260 * 240 = 62400
+    #   (45,45 | 60): 175 * (120 + 210) = 57750 ; (30,30 | 60): 190 * 300 = 57000 ; (45,45 | 45): 195 * 300 = 58500
+    p = worked_problem(oa.OVERLAP_LITERAL)
+    p.switch_cost = 10
+    assert oa.evaluate(p, [[1, 0], [2]])[0] == 58650
+    assign, num, sw = oa.solve_exhaustive(p)
+    assert (assign, num, sw) == ([[1, 1], [2]], 56700, [0, 0])
+    # the same answer is forced by allowing one configuration per worker
+    p = worked_problem(oa.OVERLAP_LITERAL)
+    p.max_configs = 1
+    assert oa.solve_exhaustive(p)[0] == [[1, 1], [2]]
+    assert oa.evaluate(p, [[1, 0], [2]]) is None

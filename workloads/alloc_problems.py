@@ -28,6 +28,8 @@ class AllocProblem:
     overlap_mode: int = OVERLAP_EXCESS
     alpha_ppm: Optional[List[int]] = None   # TABLE mode: non-decreasing slowdown (ppm) per overlap granule
     granule: int = 1                        # TABLE mode: CUs per granule
+    max_configs: int = 0                    # distinct configurations a worker may use (0 = no limit)
+    switch_cost: int = 0                    # ns added to a worker's time per configuration switch
 
 
 def random_problem(seed: int, n_workers: int, units: List[int], configs: List[int], total_cus: int,
