@@ -254,6 +254,56 @@ def kernels_mode():
 
 
 # ---------------------------------------------------------------------------------------------------
+# hardware characterisation (the paper's Sec. II-C experiments, on this GPU)
+# ---------------------------------------------------------------------------------------------------
+def characterize_mode():
+    import collections
+    import paper_2506_12598_amd as ec
+
+    def words(bits):
+        return ec.words_of_bits(bits, 8)
+
+    print("== CU-mask geometry (eclip_pool_probe: hardware ids of 4096 one-wave workgroups per mask)")
+    cases = [("unmasked", None), ("bits 0-31", words(range(32))), ("bits 0-7", words(range(8))),
+             ("bits i with i%16<8", words([i for i in range(256) if i % 16 < 8])), ("bits 128-255", words(range(128, 256))),
+             ("layout worker 0, 2 granules of 32", ec.eclip_mask_layout(256, 32, 2, 0, 2)),
+             ("layout worker 1, 2 granules of 32", ec.eclip_mask_layout(256, 32, 2, 1, 2)),
+             ("layout worker 0, 1 granule of 64, stripe 8", ec.eclip_mask_layout(256, 64, 2, 0, 1, 8))]
+    pool = ec.Pool([(w, -1) for _, w in cases])
+    for i, (name, _) in enumerate(cases):
+        ids = pool.probe(i, 4096).tolist()
+        cus = set(ids)
+        per_xcd = collections.Counter(v >> 16 for v in cus)
+        ses = sorted({(v >> 8) & 0xff for v in cus})
+        wg_xcd = collections.Counter(v >> 16 for v in ids)
+        print(f"  {name:44s} distinct CUs {len(cus):3d}; CUs per XCD {sorted(per_xcd.values())}; shader engines used {ses}; "
+              f"workgroups per XCD {min(wg_xcd.values())}..{max(wg_xcd.values())}")
+    print("  (a mask that leaves an XCD without a CU is refused by eclip_pool_create: the runtime crashes on it)")
+    pool.destroy()
+
+    print("== repartitioning cost (Observation 1): wall time per kernel of a dependent chain of trivial kernels")
+    pool = ec.Pool([(words(range(32 * g, 32 * g + 32)), -1) for g in range(4)])
+    same, pooled, create = pool.bench_switch(0, 1, 3000)
+    print(f"  same stream {same / 1e3:8.2f} us | alternating two pooled masked streams {pooled / 1e3:8.2f} us | "
+          f"a new masked stream per kernel {create / 1e3:10.2f} us")
+    pool.destroy()
+
+    print("== number of masked streams vs latency (Observation 2): chain dealt round-robin over n streams of 8 CUs")
+    pool = ec.Pool([(words(range(8 * g, 8 * g + 8)), -1) for g in range(12)])
+    for n in range(1, 13):
+        t = pool.bench_streams(list(range(n)), 1500)
+        print(f"  n = {n:2d}: {t / 1e3:9.2f} us per kernel")
+    print("== pairs of streams: chain alternating between streams i and j (creation ranks), us per kernel")
+    print("       " + " ".join(f"j={j:<5d}" for j in range(1, 9)))
+    for i in range(0, 8):
+        row = []
+        for j in range(1, 9):
+            row.append(f"{pool.bench_streams([i, j], 600) / 1e3:7.1f}" if j > i else "      .")
+        print(f"  i={i}  " + " ".join(row))
+    pool.destroy()
+
+
+# ---------------------------------------------------------------------------------------------------
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -268,6 +318,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--policy", default="eclip", choices=["eclip", "unpart_a", "unpart_b"], help="policy of the timed region")
     ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
+    ap.add_argument("--characterize", action="store_true", help="CU-mask geometry, switch cost and stream-count sweep")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; co-located models are independent workers and would be "
@@ -281,6 +332,9 @@ def main():
     torch.cuda.init()
     if args.kernels:
         kernels_mode()
+        return
+    if args.characterize:
+        characterize_mode()
         return
     time.sleep(0.5)
     idle_w = PowerSampler().read()          # board power before any kernel of this process has run
