@@ -201,7 +201,7 @@ def run_closed(workers, steps):
 # ---------------------------------------------------------------------------------------------------
 # single kernels at roofline shapes
 # ---------------------------------------------------------------------------------------------------
-def kernels_mode():
+def kernels_mode(only=None):
     import workloads as wl
     import workloads.graphs as G
     import paper_2506_12598_amd as ec
@@ -231,26 +231,53 @@ def kernels_mode():
                      MFMA_PEAK_TFLOPS, "TFLOP/s", ns / 1e3))
 
     # every case is a two-layer model whose first layer is the kernel under test (so that it writes the 16-bit type)
-    bb = G._Builder("ln", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.layernorm(-1); bb.softmax(x)
-    mem("LayerNorm, 480000 rows x 1024", bb.finish(), 480000 * 1024 * 4)
-    bb = G._Builder("sm", B, 0, G.IN_SEQ, 384, 1, 960000); x = bb.softmax(-1); bb.softmax(x)
-    mem("softmax, 960000 rows x 384", bb.finish(), 960000 * 384 * 4)
-    bb = G._Builder("mp", B, 0, G.IN_IMAGE, 64, 1792, 1792); x = bb.maxpool(-1, 3, 2, 1); bb.gap(x)
-    mem("max-pool 3x3 s2, 64 x 1792 x 1792", bb.finish(), 64 * 1792 * 1792 * 2 + 64 * 896 * 896 * 2)
-    bb = G._Builder("dw", B, 0, G.IN_IMAGE, 192, 1120, 1120); x = bb.conv(-1, 192, 3, 1, 1, G.ACT_RELU6, groups=192); bb.gap(x)
-    mem("depthwise 3x3 + ReLU6, 192 x 1120 x 1120", bb.finish(), 192 * 1120 * 1120 * 4)
-    bb = G._Builder("gap", B, 0, G.IN_IMAGE, 2048, 224, 224); x = bb.gap(-1); bb.softmax(x)
-    mem("global average pool, 4 x 2048 x 224 x 224", bb.finish(), 4 * 2048 * 224 * 224 * 2, batch=4)
-    bb = G._Builder("el", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.eltwise(-1, G.ACT_GELU, bias_std=1.0); bb.eltwise(x)
-    mem("bias + GELU, 480000 x 1024", bb.finish(), 480000 * 1024 * 4)
-    gemm("linear", 8192, 8192, 8192)
-    gemm("linear", 4096, 4096, 4096)
-    gemm("BERT-large FFN1 b4", 1536, 1024, 4096)
-    gemm("BERT-large FFN2 b4", 1536, 4096, 1024)
+    def c_ln():
+        bb = G._Builder("ln", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.layernorm(-1); bb.softmax(x)
+        mem("LayerNorm, 480000 rows x 1024", bb.finish(), 480000 * 1024 * 4)
+
+    def c_sm():
+        bb = G._Builder("sm", B, 0, G.IN_SEQ, 384, 1, 960000); x = bb.softmax(-1); bb.softmax(x)
+        mem("softmax, 960000 rows x 384", bb.finish(), 960000 * 384 * 4)
+
+    def c_mp():
+        bb = G._Builder("mp", B, 0, G.IN_IMAGE, 64, 1792, 1792); x = bb.maxpool(-1, 3, 2, 1); bb.gap(x)
+        mem("max-pool 3x3 s2, 64 x 1792 x 1792", bb.finish(), 64 * 1792 * 1792 * 2 + 64 * 896 * 896 * 2)
+
+    def c_dw():
+        bb = G._Builder("dw", B, 0, G.IN_IMAGE, 192, 1120, 1120); x = bb.conv(-1, 192, 3, 1, 1, G.ACT_RELU6, groups=192); bb.gap(x)
+        mem("depthwise 3x3 + ReLU6, 192 x 1120 x 1120", bb.finish(), 192 * 1120 * 1120 * 4)
+
+    def c_gap():
+        bb = G._Builder("gap", B, 0, G.IN_IMAGE, 2048, 224, 224); x = bb.gap(-1); bb.softmax(x)
+        mem("global average pool, 4 x 2048 x 224 x 224", bb.finish(), 4 * 2048 * 224 * 224 * 2, batch=4)
+
+    def c_gelu():
+        bb = G._Builder("el", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.eltwise(-1, G.ACT_GELU, bias_std=1.0); bb.eltwise(x)
+        mem("bias + GELU, 480000 x 1024", bb.finish(), 480000 * 1024 * 4)
+
+    def c_copy():
+        bb = G._Builder("cp", B, 0, G.IN_SEQ, 1024, 1, 480000); x = bb.eltwise(-1); bb.eltwise(x)
+        mem("plain copy (element-wise, no bias, no activation), 480000 x 1024", bb.finish(), 480000 * 1024 * 4)
+
+    def c_fc():
+        bb = G._Builder("fc", B, 0, G.IN_SEQ, 25088, 1, 8); x = bb.linear(-1, 4096, std=0.01); bb.eltwise(x)
+        ns, info = time_first(bb.finish())
+        nbytes = 2 * (8 * 25088 + 4096 * 25088 + 8 * 4096)
+        rows.append(("VGG FC1 b8: linear M8 N4096 K25088 (weight streaming)", info["kernel"], "hbm", nbytes / ns, HBM_PEAK_GBS, "GB/s", ns / 1e3))
+
+    cases = [("layernorm", c_ln), ("softmax", c_sm), ("maxpool", c_mp), ("dwconv", c_dw), ("gap", c_gap), ("gelu", c_gelu),
+             ("copy", c_copy), ("fc", c_fc),
+             ("gemm8192", lambda: gemm("linear", 8192, 8192, 8192)), ("gemm4096", lambda: gemm("linear", 4096, 4096, 4096)),
+             ("ffn1", lambda: gemm("BERT-large FFN1 b4", 1536, 1024, 4096)), ("ffn2", lambda: gemm("BERT-large FFN2 b4", 1536, 4096, 1024)),
+             ("proj", lambda: gemm("BERT-large projection b4", 1536, 1024, 1024)),
+             ("base_ffn1", lambda: gemm("BERT-base FFN1 b1", 128, 768, 3072))]
+    for key, fn in cases:
+        if only is None or key in only.split(","):
+            fn()
     pool.destroy()
-    print(f"{'case':62s} {'kernel':18s} {'bound':5s} {'achieved':>10s} {'peak':>8s} {'unit':8s} {'frac':>6s} {'us/launch':>10s}")
+    print(f"{'case':66s} {'kernel':18s} {'bound':5s} {'achieved':>10s} {'peak':>8s} {'unit':8s} {'frac':>6s} {'us/launch':>10s}")
     for name, kern, bound, ach, peak, unit, us in rows:
-        print(f"{name:62s} {kern:18s} {bound:5s} {ach:10.1f} {peak:8.0f} {unit:8s} {ach / peak:6.3f} {us:10.1f}")
+        print(f"{name:66s} {kern:18s} {bound:5s} {ach:10.1f} {peak:8.0f} {unit:8s} {ach / peak:6.3f} {us:10.1f}")
 
 
 # ---------------------------------------------------------------------------------------------------
@@ -318,6 +345,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--policy", default="eclip", choices=["eclip", "unpart_a", "unpart_b"], help="policy of the timed region")
     ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
+    ap.add_argument("--only", default=None, help="with --kernels: comma-separated case keys (layernorm, softmax, maxpool, dwconv, "
+                    "gap, gelu, copy, fc, gemm8192, gemm4096, ffn1, ffn2, proj, base_ffn1)")
     ap.add_argument("--characterize", action="store_true", help="CU-mask geometry, switch cost and stream-count sweep")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -331,7 +360,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.init()
     if args.kernels:
-        kernels_mode()
+        kernels_mode(args.only)
         return
     if args.characterize:
         characterize_mode()

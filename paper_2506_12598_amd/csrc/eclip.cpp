@@ -552,20 +552,36 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
                         for (int i = 0; i < kh * kw; ++i)
                             t[((size_t)i * cin_s + ci) * L.c + co] = src[((size_t)co * cin_l + ci) * kh * kw + i];
                 put(arena, cursor, t.data(), t.size() * es, &P.w_dev);
-            } else {                                    // -> [cout][kh][kw][cin_stored], padded channels zero
+            } else {
+                // GEMM operand W[n][k], k = (kh, kw, ci_stored) with padded channels zero, stored in the order the
+                // matrix instruction consumes it: blocks of 16 rows x 32 k, block (nb, kb) at ((nb * KB + kb) * 1 KB),
+                // and inside a block lane l of a wavefront owns the 16 bytes W[16 nb + (l & 15)][32 kb + 8 (l >> 4) .. +7].
+                // A wavefront then fetches one block with one fully contiguous 1 KB load.  N is padded to 16 and K to
+                // 32 with zeros.
                 const size_t K = (size_t)kh * kw * cin_s;
-                size_t off;
-                put(arena, cursor, nullptr, (size_t)L.c * K * es, &off);
-                E *dst = reinterpret_cast<E *>(arena.data() + off);
+                const size_t KB = (K + 31) / 32, NB = ((size_t)L.c + 15) / 16;
+                std::vector<E> plain((size_t)L.c * K, 0);
                 if (kh * kw == 1 && cin_l == cin_s) {
-                    memcpy(dst, src, (size_t)L.c * K * es);
+                    memcpy(plain.data(), src, plain.size() * es);
                 } else {
-                    memset(dst, 0, (size_t)L.c * K * es);
                     for (int co = 0; co < L.c; ++co)
                         for (int ci = 0; ci < cin_l; ++ci)
                             for (int i = 0; i < kh * kw; ++i)
-                                dst[(size_t)co * K + (size_t)i * cin_s + ci] = src[((size_t)co * cin_l + ci) * kh * kw + i];
+                                plain[(size_t)co * K + (size_t)i * cin_s + ci] = src[((size_t)co * cin_l + ci) * kh * kw + i];
                 }
+                size_t off;
+                put(arena, cursor, nullptr, NB * KB * 512 * es, &off);
+                E *dst = reinterpret_cast<E *>(arena.data() + off);
+                memset(dst, 0, NB * KB * 512 * es);
+                for (size_t nb = 0; nb < NB; ++nb)
+                    for (size_t kb = 0; kb < KB; ++kb)
+                        for (int l = 0; l < 64; ++l) {
+                            const size_t n = nb * 16 + (size_t)(l & 15), k0 = kb * 32 + (size_t)(l >> 4) * 8;
+                            if (n >= (size_t)L.c) continue;
+                            E *d8 = dst + ((nb * KB + kb) * 64 + (size_t)l) * 8;
+                            for (int e = 0; e < 8; ++e)
+                                if (k0 + e < K) d8[e] = plain[n * K + k0 + e];
+                        }
                 P.w_dev = off;
             }
             if (L.b_off >= 0) put(arena, cursor, w + L.b_off, (size_t)L.c * es, &P.b_dev);
@@ -659,6 +675,7 @@ extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_des
         const size_t MN = (size_t)g.B * g.Ho * g.Wo * g.Cout;
         const size_t KT = ((size_t)g.KH * g.KW * g.Cin + 63) / 64;
         if (MN <= (size_t)256 * 64 * 64) ws = std::max(ws, MN * std::min<size_t>(32, std::max<size_t>(1, KT / 3)));
+        if (KT >= 4 && 2 * MN <= ((size_t)16 << 20)) ws = std::max(ws, 2 * MN);       // K cut in two for mid-size layers
     }
     m->ws_floats = std::min<size_t>(ws, (size_t)16 << 20);
     LOAD_TRY(hipMalloc((void **)&m->d_ws, std::max<size_t>(m->ws_floats * 4, 256)));

@@ -31,12 +31,18 @@ namespace eclip {
 
 namespace {
 
-template <typename T, int BM, int BN, int BK, int WM, int WN, int RS, bool OVERLAP = false>
+// K-loop schedules
+enum { LOOP_PLAIN = 0, LOOP_OVERLAP = 1, LOOP_PINGPONG = 2 };
+
+template <typename T, int BM, int BN, int BK, int WM, int WN, int RS, int LOOP = LOOP_PLAIN>
 __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
 {
     constexpr int NT = WM * WN * 64;         // threads per workgroup: 4 wavefronts, 8 for the 256x256 tile
     static_assert(RS % 2 == 0, "register stages alternate between the two LDS slots");
-    constexpr int LDK = BK + 8;              // row pitch: 16-byte reads of 16 consecutive rows hit distinct banks
+    // row pitch in elements.  Measured with a ds_read_b128 / ds_write_b128 micro-benchmark: with 64-byte rows a
+    // pitch of 96 bytes makes the fragment reads (16 rows x 4 chunks per instruction) conflict-free, 80 bytes
+    // costs them about 20 %.
+    constexpr int LDK = (LOOP == LOOP_PINGPONG) ? BK + 16 : BK + 8;
     constexpr int CPR = BK / 8;              // 16-byte chunks per row
     constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
     constexpr int A_CH = BM * CPR, B_CH = BN * CPR;
@@ -75,68 +81,105 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (int)p.w_bytes, 0x00020000);
     constexpr unsigned OOB = 0xffffffffu;
     bool a_ok[A_IT];
-    unsigned a_base[A_IT];                   // byte offset of the image the row belongs to
+    unsigned a_off0[A_IT];                   // byte offset of pixel (ih0, iw0) of the row's image (modulo 2^32 when padded)
     int a_ih0[A_IT], a_iw0[A_IT];
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
     for (int it = 0; it < A_IT; ++it) {
         const int c = tid + it * NT;
         const int m = m_base + c / CPR;
-        a_ok[it] = (c < A_CH) && (m < p.M);
+        a_ok[it] = (A_CH % NT == 0 || c < A_CH) && (m < p.M);
         const int mm = a_ok[it] ? m : 0;
         const int b = mm / HoWo, r = mm - b * HoWo;
         const int oh = r / p.Wo, ow = r - oh * p.Wo;
-        a_base[it] = (unsigned)b * (unsigned)(p.H * p.W * p.Cin) * 2u;
         a_ih0[it] = oh * p.stride - p.pad;
         a_iw0[it] = ow * p.stride - p.pad;
+        a_off0[it] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[it] * p.W + a_iw0[it])) * (unsigned)p.Cin * 2u;
     }
+    // The weights are stored in blocks of 16 rows x 32 k, 1 KB each, lane-ordered for the matrix instruction.  A
+    // wavefront copies whole blocks: chunk c of the tile is lane c % 64 of block c / 64, and block b of the tile is
+    // (row block b / (BK/32), k block b % (BK/32)).  Padding rows and k are zeros in memory, so the only checks are
+    // the end of the matrix and the end of this workgroup's K slice.
+    static_assert(NT % 64 == 0 && BK % 32 == 0 && BN % 16 == 0, "whole weight blocks per wavefront");
+    constexpr int KBT = BK / 32;             // k blocks per tile
+    const int KB = (p.K + 31) >> 5, NB = (p.N + 15) >> 4;
     bool b_ok[B_IT];
-    unsigned b_base[B_IT];
+    unsigned b_base[B_IT];                   // byte offset of this lane's 16 bytes in k block 0 of its row block
+    int b_kb[B_IT];                          // k block within the tile
+    int b_lds[B_IT];                         // element offset in the LDS tile
 #pragma unroll
     for (int it = 0; it < B_IT; ++it) {
         const int c = tid + it * NT;
-        const int n = n_base + c / CPR;
-        b_ok[it] = (c < B_CH) && (n < p.N);
-        b_base[it] = (unsigned)(b_ok[it] ? n : 0) * (unsigned)p.K * 2u;
+        const int blk = c >> 6, nbl = blk / KBT;
+        b_kb[it] = blk - nbl * KBT;
+        const int nb = (n_base >> 4) + nbl;
+        b_ok[it] = (B_CH % NT == 0 || c < B_CH) && (nb < NB);
+        b_base[it] = ((unsigned)(b_ok[it] ? nb : 0) * (unsigned)KB * 64u + (unsigned)lane) * 16u;
+        b_lds[it] = (nbl * 16 + (lane & 15)) * LDK + b_kb[it] * 32 + (lane >> 4) * 8;
     }
     const int kc = (tid % CPR) * 8;          // same for every chunk of this thread: NT % CPR == 0
     const bool pointwise = (p.KH * p.KW == 1);
 
-    auto load_tile = [&](int kt, uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
-        const int k = kt * BK + kc;
-        const bool k_ok = k < p.K;
-        int kh = 0, kw = 0, ci = k;
-        if (!pointwise) {
-            const int tap = k / p.Cin;
-            ci = k - tap * p.Cin;
-            kh = tap / p.KW;
-            kw = tap - kh * p.KW;
-        }
+    const int kt_begin = blockIdx.y * p.kt_per;
+    const int kt_end = min(p.KT, kt_begin + p.kt_per);
+    // K tiles are loaded strictly in order, so the thread keeps the position of its next 8 k, k = (kh, kw, ci),
+    // and advances it by BK per tile without dividing.  Tiles at or beyond the end of the slice load zeros
+    // (k >= k_lim), which keeps the K loops below free of branches.
+    const int k_lim = min(p.K, kt_end * BK);
+    const int kb_lim = min(KB, kt_end * KBT);
+    int kb_run = kt_begin * KBT;
+    int k_run = kt_begin * BK + kc;
+    int kh_run = 0, kw_run = 0, ci_run = k_run;
+    if (!pointwise) {
+        const int tap = k_run / p.Cin;
+        ci_run = k_run - tap * p.Cin;
+        kh_run = tap / p.KW;
+        kw_run = tap - kh_run * p.KW;
+    }
+    // (written with & and selects rather than && and if: one basic block, so that the scheduler may spread these
+    // instructions between matrix instructions)
+    auto load_next = [&](uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
+        const int k_ok = k_run < k_lim;
+        const unsigned tap_off = (unsigned)((kh_run * p.W + kw_run) * p.Cin + ci_run) * 2u;
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
-            const int ih = a_ih0[it] + kh, iw = a_iw0[it] + kw;
-            const bool ok = a_ok[it] && k_ok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-            const unsigned off = ok ? a_base[it] + (unsigned)((ih * p.W + iw) * p.Cin + ci) * 2u : OOB;
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+            const int ok = (int)a_ok[it] & k_ok & (int)((unsigned)(a_ih0[it] + kh_run) < (unsigned)p.H) &
+                           (int)((unsigned)(a_iw0[it] + kw_run) < (unsigned)p.W);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? a_off0[it] + tap_off : OOB, 0, 0);
             ra[it] = make_uint4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
-            const unsigned off = (b_ok[it] && k_ok) ? b_base[it] + (unsigned)k * 2u : OOB;
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
+            const int kb = kb_run + b_kb[it];
+            const int ok = (int)b_ok[it] & (int)(kb < kb_lim);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, ok ? b_base[it] + (unsigned)kb * 1024u : OOB, 0, 0);
             rb[it] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+        kb_run += KBT;
+        k_run += BK;
+        ci_run += BK;
+        // Cin >= 8, so BK / 8 turns always suffice.  For a 1x1 window Cin == K and a wrap happens only beyond K,
+        // where k_ok is false whatever the tap says.
+#pragma unroll
+        for (int u = 0; u < BK / 8; ++u) {
+            const int wrap = ci_run >= p.Cin;
+            ci_run -= wrap ? p.Cin : 0;
+            kw_run += wrap;
+            const int wrap2 = kw_run == p.KW;
+            kw_run = wrap2 ? 0 : kw_run;
+            kh_run += wrap2;
         }
     };
     auto store_tile = [&](int slot, const uint4 (&ra)[A_IT], const uint4 (&rb)[B_IT]) {
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
             const int c = tid + it * NT;
-            if (c < A_CH) *reinterpret_cast<uint4 *>(&sA0[slot * BM * LDK + (c / CPR) * LDK + kc]) = ra[it];
+            if (A_CH % NT == 0 || c < A_CH) *reinterpret_cast<uint4 *>(&sA0[slot * BM * LDK + (c / CPR) * LDK + kc]) = ra[it];
         }
 #pragma unroll
         for (int it = 0; it < B_IT; ++it) {
             const int c = tid + it * NT;
-            if (c < B_CH) *reinterpret_cast<uint4 *>(&sB0[slot * BN * LDK + (c / CPR) * LDK + kc]) = rb[it];
+            if (B_CH % NT == 0 || c < B_CH) *reinterpret_cast<uint4 *>(&sB0[slot * BN * LDK + b_lds[it]]) = rb[it];
         }
     };
 
@@ -146,14 +189,12 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int kt_begin = z * p.kt_per;
-    const int kt_end = min(p.KT, kt_begin + p.kt_per);
     const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
 
     // RS register sets: set (t - kt_begin) % RS carries K step t, so RS steps of loads are in flight
     uint4 ra[RS][A_IT], rb[RS][B_IT];
 #pragma unroll
-    for (int r = 0; r < RS; ++r) load_tile(kt_begin + r < kt_end ? kt_begin + r : p.KT, ra[r], rb[r]);
+    for (int r = 0; r < RS; ++r) load_next(ra[r], rb[r]);
 
     auto compute = [&](int slot) {
 #pragma unroll
@@ -175,17 +216,66 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
     // LDS slot (t - kt_begin) % 2 is rewritten at step t only after every wavefront has passed the barrier
     // of step t-1, i.e. after all of them finished reading it at step t-2.  RS is even, so the slot of
     // register set r is r % 2.
-    // The loop body is branch-free: steps at or beyond kt_end load zeros (k >= K in load_tile's terms is
+    // The loop body is branch-free: steps at or beyond kt_end load zeros (k >= k_lim in load_next's terms is
     // forced by passing KT) and multiply them, which costs at most RS-1 idle steps at the end of a slice
     // and lets the compiler wait for exactly one step's loads at a time.
-    if constexpr (!OVERLAP) {
+    if constexpr (LOOP == LOOP_PINGPONG) {
+        // Two groups of wavefronts, half a step apart.  Wavefronts w and w + 4 share a SIMD, and WN == 4 puts
+        // them in different groups (group = wave / 4 = wm).  Time is cut into phases by workgroup barriers; in
+        // every phase one group runs its memory half-step (fragments of step t from LDS into registers, tile
+        // t+1 from registers into LDS) while the other issues the global loads of tile t+3 and runs the 32 MFMAs of its
+        // previous half-step, so the matrix pipe and the LDS pipe of each SIMD are busy at the same time
+        // instead of taking turns.  Group 1 starts one phase late and group 0 ends one phase late: both pass
+        //   1 + (1 or 0) + 2 * steps + (0 or 1)
+        // barriers, and the trip count is the same for every wavefront of a workgroup.
+        // LDS hazards: slot s = (t+1)%2 is written in the memory half-steps of step t (phases 2t, 2t+1); its
+        // previous content (tile t-1) was last read in phase 2t-1, and it is first read in phase 2t+2.
+        static_assert(LOOP != LOOP_PINGPONG || (RS == 2 && WM == 2 && WN == 4 && BK == 32), "ping-pong schedule: 8 wavefronts, two register sets");
+        const bool late = wm != 0;
+        uint4 fa[TM], fb[TN];
+        auto read_frags = [&](int slot) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[j] = *reinterpret_cast<const uint4 *>(&sB0[slot * BN * LDK + (wn * (BN / WN) + j * 16 + frag_row) * LDK + frag_k]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[i] = *reinterpret_cast<const uint4 *>(&sA0[slot * BM * LDK + (wm * (BM / WM) + i * 16 + frag_row) * LDK + frag_k]);
+        };
+        // the loads of a later tile are issued from inside the MFMA half-step (their address arithmetic fills
+        // issue slots between matrix instructions), which keeps the memory half-step down to LDS traffic
+        auto mma = [&](uint4 (&na)[A_IT], uint4 (&nb)[B_IT]) {
+            __builtin_amdgcn_s_setprio(1);
+            load_next(na, nb);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[j], fa[i], acc[i][j]);
+            __builtin_amdgcn_s_setprio(0);
+        };
+        store_tile(0, ra[0], rb[0]);
+        load_next(ra[0], rb[0]);
+        __syncthreads();
+        if (late) __syncthreads();
+        for (int kt = kt_begin; kt < kt_end; kt += 2) {
+            read_frags(0);
+            store_tile(1, ra[1], rb[1]);
+            __syncthreads();
+            mma(ra[1], rb[1]);
+            __syncthreads();
+            read_frags(1);
+            store_tile(0, ra[0], rb[0]);
+            __syncthreads();
+            mma(ra[0], rb[0]);
+            __syncthreads();
+        }
+        if (!late) __syncthreads();
+    } else if constexpr (LOOP == LOOP_PLAIN) {
         for (int kt = kt_begin; kt < kt_end; kt += RS) {
 #pragma unroll
             for (int r = 0; r < RS; ++r) {
                 store_tile(r & 1, ra[r], rb[r]);
                 __syncthreads();
-                const int nxt = kt + r + RS;
-                load_tile(nxt < kt_end ? nxt : p.KT, ra[r], rb[r]);
+                load_next(ra[r], rb[r]);
                 compute(r & 1);
             }
         }
@@ -193,15 +283,15 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
         // Large tiles (RS == 2): the LDS stores of step t+1 share a basic block with the MFMAs of step t, so
         // the scheduler can hide them behind the matrix pipe.  Safe with two slots: slot (t+1)%2 was last read
         // at step t-1, and every wavefront has passed the barrier that ended that step.
-        static_assert(!OVERLAP || RS == 2, "the overlapped loop alternates two register sets");
+        static_assert(LOOP != LOOP_OVERLAP || RS == 2, "the overlapped loop alternates two register sets");
         store_tile(0, ra[0], rb[0]);
         __syncthreads();
         for (int kt = kt_begin; kt < kt_end; kt += 2) {
-            load_tile(kt + 2 < kt_end ? kt + 2 : p.KT, ra[0], rb[0]);
+            load_next(ra[0], rb[0]);
             compute(0);
             store_tile(1, ra[1], rb[1]);
             __syncthreads();
-            load_tile(kt + 3 < kt_end ? kt + 3 : p.KT, ra[1], rb[1]);
+            load_next(ra[1], rb[1]);
             compute(1);
             store_tile(0, ra[0], rb[0]);
             __syncthreads();
@@ -280,7 +370,7 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
 struct Variant { int bm, bn, bk; };
 constexpr Variant kVariants[4] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}};
 
-constexpr size_t lds_bytes(int bm, int bn, int bk) { return (size_t)2 * (bm + bn) * (bk + 8) * 2; }
+constexpr size_t lds_bytes(int bm, int bn, int bk, int pad = 8) { return (size_t)2 * (bm + bn) * (bk + pad) * 2; }
 
 template <typename T>
 hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
@@ -290,7 +380,7 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
     case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, dim3(256), lds_bytes(128, 128, 32), s, d); break;
     case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, dim3(256), lds_bytes(64, 64, 64), s, d); break;
     case 2: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, dim3(256), lds_bytes(32, 64, 64), s, d); break;
-    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 256, 256, 32, 2, 4, 2, true>), grid, dim3(512), lds_bytes(256, 256, 32), s, d); break;
+    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(256, 256, 32, 16), s, d); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
@@ -304,11 +394,11 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
 
 hipError_t conv_gemm_init()
 {
-    hipError_t e = hipFuncSetAttribute((const void *)conv_gemm_kernel<bf16_t, 256, 256, 32, 2, 4, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds_bytes(256, 256, 32));
+    hipError_t e = hipFuncSetAttribute((const void *)conv_gemm_kernel<bf16_t, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(256, 256, 32, 16));
     if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)conv_gemm_kernel<f16_t, 256, 256, 32, 2, 4, 2, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)lds_bytes(256, 256, 32));
+    return hipFuncSetAttribute((const void *)conv_gemm_kernel<f16_t, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(256, 256, 32, 16));
 }
 
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk)
@@ -343,7 +433,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     const char *force = getenv("ECLIP_GEMM_FORCE");
     int f_kind = -1, f_variant = -1, f_n = -1;
     if (force) sscanf(force, "%d,%d,%d", &f_kind, &f_variant, &f_n);
-    if (f_kind == 1 && f_variant >= 0 && f_variant <= 2 && (f_n == 4 || f_n == 8 || f_n == 16) &&
+    if (f_kind == 1 && f_variant >= 0 && f_variant < CONV_WSK_VARIANTS && (f_n == 4 || f_n == 8 || f_n == 16) &&
         conv_wsk_lds_bytes(f_variant, f_n) <= 128 * 1024) {
         pl.kind = 1; pl.variant = f_variant; pl.nw = f_n; pl.tiles = (int)wsk_tiles(f_variant);
         return pl;
@@ -362,50 +452,55 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         set_raster(pl, M, N);
         return pl;
     }
-    // Few tiles (batch-1 convolutions, skinny linear layers).  Measured on MI355X: a kernel costs about
-    // 4.5 us however little it does, and one CU sustains only about 30 GB/s of operand loads, so a layer is
-    // priced as  launches * 4.5 us + (bytes the busiest CU has to pull) / 30 GB/s  for each candidate:
-    //   wave-split-K on 16x64 or 32x64 tiles (one launch, a workgroup pulls its whole (bm+bn) x K panel);
-    //   32x64 tiles cut along K over the grid (two launches, the panels are spread over every CU).
-    if (wsk_tiles(1) <= 2L * n_cu) {
-        const double us_per_launch = 4.5, bytes_per_us = 30e3;
-        auto wsk_cost = [&](int v) {
-            int bm, bn;
-            conv_wsk_tile(v, &bm, &bn);
-            const double rounds = (double)cdiv(wsk_tiles(v), n_cu);
-            return us_per_launch + rounds * (double)(bm + bn) * (double)K * 2.0 / bytes_per_us;
-        };
-        const long t2 = tiles(2);
-        const long KT = cdiv(K, 64);
-        long s = 1;
-        if (KT >= 8) {
-            s = cdiv(2L * n_cu, t2);                   // about two workgroups per CU
-            const long max_s = KT / 2;
-            if (s > max_s) s = max_s;
-            if (s > 32) s = 32;
-            while (s > 1 && (size_t)(s * M * N) > ws_floats) --s;
+    // Every candidate is priced with a small cost model fitted to per-layer timings of all GEMM layers of the
+    // ResNet-18/50, VGG-16, MobileNetV2 and BERT-base/large graphs at batch 1 to 8, on 256 and on 128 CUs (picks
+    // within 3 % of the per-layer best of an exhaustive sweep, in total).  Times in microseconds, without the
+    // launch cost that all single-launch candidates share.
+    //
+    // Wave-split-K, tile bm x bn, nw wavefronts.  A compute unit pulls the im2col rows in MFMA fragment order
+    // (16 rows per instruction: slow) and the weights as contiguous 1 KB blocks (fast); its workgroups run one
+    // after another; each wavefront needs ceil(steps / depth) round trips to memory; the partial tiles of the nw
+    // wavefronts are summed through LDS.
+    const double ra = 4.347e4, rw = 4.235e5;         // bytes per us per CU: activation rows, weight blocks
+    const double lat = 0.017, c_out = 4.5e-6, c_red = 9.0e-6, l2 = 3.794e8, c_wg = 0.030;
+    double best = 1e30;
+    for (int v = 0; v < CONV_WSK_VARIANTS; ++v) {
+        int bm, bn;
+        conv_wsk_tile(v, &bm, &bn);
+        const int depth = (bm + bn) <= 32 ? 8 : (bm + bn) <= 48 ? 6 : (bm + bn) <= 80 ? 4 : (bm + bn) <= 96 ? 3 : 2;
+        for (int nw = 4; nw <= 16; nw *= 2) {
+            if (conv_wsk_lds_bytes(v, nw) > 128 * 1024) continue;
+            const double t = (double)wsk_tiles(v);
+            const double per_cu = (double)cdiv((long)t, n_cu), frac = t / n_cu > 1.0 ? t / n_cu : 1.0;
+            const double a_b = (double)(M < bm ? M : bm) * K * 2.0, w_b = (double)(N < bn ? N : bn) * K * 2.0;
+            const double cu = per_cu * (a_b / ra + w_b / rw) + frac * c_wg + frac * bm * bn * (c_out + c_red * nw);
+            const double all = t * (a_b + w_b) / l2;
+            const int d = (bm + bn == 96 && nw == 16) ? 2 : depth;
+            const double cost = (cu > all ? cu : all) + lat * (double)cdiv(cdiv(cdiv(K, 32), nw), d);
+            if (cost < best) { best = cost; pl = GemmPlan{1, v, 1, (int)t, nw, 0}; }
         }
-        const double split_cost = s > 1 ? 2.0 * us_per_launch + 0.5 +
-                                              (double)cdiv(t2 * s, n_cu) * 96.0 * (double)cdiv(K, s) * 2.0 / bytes_per_us
-                                        : 1e30;
-        const int wv = (M <= 16 || wsk_cost(0) <= wsk_cost(1)) ? 0 : 1;
-        if (split_cost < wsk_cost(wv)) {
-            pl.kind = 0; pl.variant = 2; pl.tiles = (int)t2;
-            const long kt_per = cdiv(KT, s);
-            pl.splits = (int)cdiv(KT, kt_per);
-            return pl;
-        }
-        pl.kind = 1;
-        pl.variant = wv;
-        pl.tiles = (int)wsk_tiles(wv);
-        pl.nw = 4;
-        return pl;
     }
-    if (tiles(3) >= 2L * n_cu) pl.variant = 3;
-    else if (tiles(0) >= 2L * n_cu) pl.variant = 0;
-    else pl.variant = 1;
-    pl.tiles = (int)tiles(pl.variant);
-    set_raster(pl, M, N);
+    // LDS-tiled kernel, optionally with K cut in two (second launch: about 4 us plus the traffic of the partial sums).
+    // A tile costs `shared` us per K step when workgroups share a compute unit and `alone` when it has one to itself.
+    struct { int variant; double shared, alone; } lds[3] = {{0, 0.326, 17.9}, {1, 0.212, 5.16}, {3, 0.96, 0.96}};
+    for (const auto &c : lds) {
+        int bm, bn, bk;
+        conv_gemm_tile(c.variant, &bm, &bn, &bk);
+        const long KT = cdiv(K, bk);
+        for (long sp = 1; sp <= (c.variant == 3 ? 1 : 2); ++sp) {
+            if (sp > 1 && (KT < 8 || (size_t)(sp * M * N) > ws_floats)) continue;
+            const long wgs = tiles(c.variant) * sp, per_cu = cdiv(wgs, n_cu);
+            double cost = 0.756 + (double)cdiv(KT, sp) * (per_cu == 1 ? c.alone : (double)per_cu * c.shared);
+            if (sp > 1) cost += 4.0 + (double)M * N * (4.0 * sp + 2.0) / 5.0e6;
+            if (cost < best) {
+                best = cost;
+                pl = GemmPlan{0, c.variant, 1, (int)tiles(c.variant), 4, 0};
+                const long kt_per = cdiv(KT, sp);
+                pl.splits = (int)cdiv(KT, kt_per);
+            }
+        }
+    }
+    if (pl.kind == 0) set_raster(pl, M, N);
     return pl;
 }
 
@@ -418,7 +513,7 @@ hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream
     d.stride = a.stride; d.pad = a.pad; d.act = a.act;
     d.M = a.B * a.Ho * a.Wo; d.N = a.Cout; d.K = a.KH * a.KW * a.Cin;
     d.x_bytes = (unsigned)((size_t)a.B * a.H * a.W * a.Cin * 2);
-    d.w_bytes = (unsigned)((size_t)d.N * d.K * 2);
+    d.w_bytes = (unsigned)((size_t)((d.N + 15) / 16) * ((d.K + 31) / 32) * 1024);   // blocked layout, see ConvGemmArgs::w
     int bm, bn, bk;
     conv_gemm_tile(pl.variant, &bm, &bn, &bk);
     d.KT = (d.K + bk - 1) / bk;

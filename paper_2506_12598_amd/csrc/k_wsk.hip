@@ -4,7 +4,7 @@
 // parallelism is taken from K *inside* the workgroup instead of from a second kernel:
 //   - a workgroup of NW wavefronts owns one (TM*16) x (TN*16) output tile;
 //   - wavefront w multiplies the whole tile over its own contiguous slice of K, reading its MFMA
-//     operands straight from global memory (each lane 16 bytes = 8 consecutive k of one row), three K
+//     operands straight from global memory (each lane 16 bytes = 8 consecutive k of one row), several K
 //     steps in flight, with no LDS staging and no barrier in the loop: every element of the A and W
 //     tiles is still read exactly once per workgroup, because the slices are disjoint;
 //   - the NW partial tiles meet in LDS (float, lane-contiguous so the writes are conflict-free), and
@@ -18,7 +18,7 @@ namespace eclip {
 
 namespace {
 
-template <typename T, int TM, int TN, int NW>
+template <typename T, int TM, int TN, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
 {
     extern __shared__ __attribute__((aligned(16))) float red[];    // [NW][TM*TN][64][4]
@@ -33,8 +33,8 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (int)p.w_bytes, 0x00020000);
     constexpr unsigned OOB = 0xffffffffu;
-    bool a_ok[TM];
-    unsigned a_base[TM];
+    int a_ok[TM];
+    unsigned a_off0[TM];                     // byte offset of pixel (ih0, iw0) of the row's image (modulo 2^32 when padded)
     int a_ih0[TM], a_iw0[TM];
     const int HoWo = p.Ho * p.Wo;
 #pragma unroll
@@ -44,17 +44,19 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
         const int mm = a_ok[i] ? m : 0;
         const int b = mm / HoWo, r = mm - b * HoWo;
         const int oh = r / p.Wo, ow = r - oh * p.Wo;
-        a_base[i] = (unsigned)b * (unsigned)(p.H * p.W * p.Cin) * 2u;
         a_ih0[i] = oh * p.stride - p.pad;
         a_iw0[i] = ow * p.stride - p.pad;
+        a_off0[i] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * (unsigned)p.Cin * 2u;
     }
-    bool b_ok[TN];
+    // weights: 1 KB blocks of 16 rows x 32 k in lane order, so a fragment is one contiguous load
+    const int KB = (p.K + 31) >> 5, NB = (p.N + 15) >> 4;
+    int b_ok[TN];
     unsigned b_base[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-        const int n = n_base + j * 16 + row;
-        b_ok[j] = n < p.N;
-        b_base[j] = (unsigned)(b_ok[j] ? n : 0) * (unsigned)p.K * 2u;
+        const int nb = (n_base >> 4) + j;
+        b_ok[j] = nb < NB;
+        b_base[j] = ((unsigned)(b_ok[j] ? nb : 0) * (unsigned)KB * 64u + (unsigned)lane) * 16u;
     }
 
     // this wavefront's K steps (32 k each)
@@ -62,9 +64,10 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
     const int per_wave = (ksteps + NW - 1) / NW;
     const int ks0 = min(ksteps, wave * per_wave), ks1 = min(ksteps, ks0 + per_wave);
     const int n_steps = ks1 - ks0;
+    const int k_lim = min(p.K, ks1 * 32);
 
     // running position of this lane's next 8 k: k = (kh, kw, ci), advanced by 32 per step without dividing
-    int k = ks0 * 32 + g * 8;
+    int k = ks0 * 32 + g * 8, kb = ks0;
     int kh = 0, kw = 0, ci = k;
     if (p.KH * p.KW != 1) {
         const int tap = k / p.Cin;
@@ -73,27 +76,33 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
         kw = tap - kh * p.KW;
     }
     struct Frag { uint4 a[TM]; uint4 b[TN]; };
+    // branch-free: a lane whose chunk is padding, beyond M / N or beyond the wavefront's K slice loads zeros
     auto load = [&](Frag &f) {
-        const bool k_ok = k < p.K;
+        const int k_ok = k < k_lim, kb_ok = kb < ks1;
+        const unsigned tap_off = (unsigned)((kh * p.W + kw) * p.Cin + ci) * 2u;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int ih = a_ih0[i] + kh, iw = a_iw0[i] + kw;
-            const bool ok = a_ok[i] && k_ok && (unsigned)ih < (unsigned)p.H && (unsigned)iw < (unsigned)p.W;
-            const unsigned off = ok ? a_base[i] + (unsigned)((ih * p.W + iw) * p.Cin + ci) * 2u : OOB;
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0);
+            const int ok = a_ok[i] & k_ok & (int)((unsigned)(a_ih0[i] + kh) < (unsigned)p.H) & (int)((unsigned)(a_iw0[i] + kw) < (unsigned)p.W);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? a_off0[i] + tap_off : OOB, 0, 0);
             f.a[i] = make_uint4(v.x, v.y, v.z, v.w);
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            const unsigned off = (b_ok[j] && k_ok) ? b_base[j] + (unsigned)k * 2u : OOB;
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, off, 0, 0);
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, (b_ok[j] & kb_ok) ? b_base[j] + (unsigned)kb * 1024u : OOB, 0, 0);
             f.b[j] = make_uint4(v.x, v.y, v.z, v.w);
         }
         k += 32;
+        ++kb;
         ci += 32;
-        while (ci >= p.Cin) {         // at most 4 turns: Cin >= 8
-            ci -= p.Cin;
-            if (++kw == p.KW) { kw = 0; ++kh; }
+        // Cin >= 8, so 4 turns always suffice; for a 1x1 window Cin == K and a wrap only happens beyond K
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int wrap = ci >= p.Cin;
+            ci -= wrap ? p.Cin : 0;
+            kw += wrap;
+            const int wrap2 = kw == p.KW;
+            kw = wrap2 ? 0 : kw;
+            kh += wrap2;
         }
     };
 
@@ -109,22 +118,17 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
             for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(f.b[j], f.a[i], acc[i][j]);
     };
 
-    // Branch-free pipeline, three steps of loads in flight; steps beyond the slice load zeros (k >= K).
-    Frag f0, f1, f2;
-    if (n_steps <= 0) k = p.K;
-    load(f0);
-    if (n_steps <= 1) k = p.K;
-    load(f1);
-    for (int s = 0; s < n_steps; s += 3) {
-        if (s + 2 >= n_steps) k = p.K;
-        load(f2);
-        compute(f0);
-        if (s + 3 >= n_steps) k = p.K;
-        load(f0);
-        compute(f1);
-        if (s + 4 >= n_steps) k = p.K;
-        load(f1);
-        compute(f2);
+    // D steps of loads in flight per wavefront (the fewer registers a step takes, the deeper); a short slice is
+    // loaded whole before the first matrix instruction.  Steps beyond the slice load zeros and add nothing.
+    Frag f[D];
+    static_for<D>([&](auto dc) { load(f[decltype(dc)::value]); });
+    for (int s = 0; s < n_steps; s += D) {
+        const bool more = s + D < n_steps;       // wavefront-uniform
+        static_for<D>([&](auto dc) {
+            constexpr int d = decltype(dc)::value;
+            compute(f[d]);
+            if (more) load(f[d]);
+        });
     }
 
     // ---- cross-wavefront sum through LDS
@@ -149,6 +153,12 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
     }
 }
 
+// prefetch depth per tile shape: about 24 / (TM + TN) steps of 16-byte loads per lane
+// (16 wavefronts leave 128 registers per lane, which holds only two steps of a 32x64 tile)
+template <int TM, int TN, int NW> struct Depth {
+    static constexpr int value = (TM + TN) <= 2 ? 8 : (TM + TN) <= 3 ? 6 : (TM + TN) <= 5 ? 4 : (TM + TN) <= 6 ? (NW == 16 ? 2 : 3) : 2;
+};
+
 template <typename T, int TM, int TN>
 hipError_t launch_nw(const GemmDev &d, int nw, int tiles, hipStream_t s)
 {
@@ -156,10 +166,10 @@ hipError_t launch_nw(const GemmDev &d, int nw, int tiles, hipStream_t s)
     if (lds > 128 * 1024) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles);
     switch (nw) {
-    case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4>), grid, dim3(256), lds, s, d); break;
-    case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8>), grid, dim3(512), lds, s, d); break;
+    case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4, Depth<TM, TN, 4>::value>), grid, dim3(256), lds, s, d); break;
+    case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8, Depth<TM, TN, 8>::value>), grid, dim3(512), lds, s, d); break;
     case 16:
-        if constexpr (TM * TN <= 8) hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16>), grid, dim3(1024), lds, s, d);
+        if constexpr (TM * TN <= 8) hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16, Depth<TM, TN, 16>::value>), grid, dim3(1024), lds, s, d);
         else return hipErrorInvalidValue;        // 16 partial 64x64 tiles would not fit in LDS
         break;
     default: return hipErrorInvalidValue;
@@ -174,6 +184,9 @@ hipError_t launch_tile(const GemmDev &d, int variant, int nw, int tiles, hipStre
     case 0: return launch_nw<T, 1, 4>(d, nw, tiles, s);
     case 1: return launch_nw<T, 2, 4>(d, nw, tiles, s);
     case 2: return launch_nw<T, 4, 4>(d, nw, tiles, s);
+    case 3: return launch_nw<T, 1, 1>(d, nw, tiles, s);
+    case 4: return launch_nw<T, 1, 2>(d, nw, tiles, s);
+    case 5: return launch_nw<T, 2, 2>(d, nw, tiles, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -183,10 +196,10 @@ hipError_t set_attr_tile()
 {
     hipError_t e;
     const int lim = 144 * 1024;
-    if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 8>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 4, Depth<TM, TN, 4>::value>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+    if ((e = hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 8, Depth<TM, TN, 8>::value>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
     if constexpr (TM * TN <= 8)
-        return hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 16>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+        return hipFuncSetAttribute((const void *)conv_wsk_kernel<T, TM, TN, 16, Depth<TM, TN, 16>::value>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
     return hipSuccess;
 }
 
@@ -194,8 +207,8 @@ hipError_t set_attr_tile()
 
 void conv_wsk_tile(int variant, int *bm, int *bn)
 {
-    static const int t[3][2] = {{16, 64}, {32, 64}, {64, 64}};
-    const int v = variant < 0 ? 0 : (variant > 2 ? 2 : variant);
+    static const int t[CONV_WSK_VARIANTS][2] = {{16, 64}, {32, 64}, {64, 64}, {16, 16}, {16, 32}, {32, 32}};
+    const int v = variant < 0 ? 0 : (variant >= CONV_WSK_VARIANTS ? CONV_WSK_VARIANTS - 1 : variant);
     *bm = t[v][0];
     *bn = t[v][1];
 }
@@ -213,7 +226,10 @@ hipError_t conv_wsk_init()
 #define SET(T)                                                     \
     if ((e = set_attr_tile<T, 1, 4>()) != hipSuccess) return e;    \
     if ((e = set_attr_tile<T, 2, 4>()) != hipSuccess) return e;    \
-    if ((e = set_attr_tile<T, 4, 4>()) != hipSuccess) return e;
+    if ((e = set_attr_tile<T, 4, 4>()) != hipSuccess) return e;    \
+    if ((e = set_attr_tile<T, 1, 1>()) != hipSuccess) return e;    \
+    if ((e = set_attr_tile<T, 1, 2>()) != hipSuccess) return e;    \
+    if ((e = set_attr_tile<T, 2, 2>()) != hipSuccess) return e;
     SET(bf16_t)
     SET(f16_t)
 #undef SET

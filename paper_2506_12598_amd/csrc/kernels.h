@@ -13,7 +13,9 @@ enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
 // y[m][n] = act(sum_k A[m][k] * w[n][k] + bias[n] + res[m][n]),  m = (b,oh,ow), k = (kh,kw,ci).
 struct ConvGemmArgs {
     const void *x;       // [B][H][W][Cin]           Cin % 8 == 0
-    const void *w;       // [Cout][KH][KW][Cin]
+    const void *w;       // W[n][k], n = cout, k = (kh, kw, ci), in 1 KB blocks of 16 n x 32 k: block (nb, kb) at
+                         // (nb * ceil(K/32) + kb) * 1 KB, lane l of a block = W[16 nb + (l & 15)][32 kb + 8 (l >> 4) .. +7];
+                         // rows beyond Cout and k beyond K are zero
     const void *bias;    // [Cout] or null
     const void *res;     // [M][Cout] or null
     void *y;             // [M][Cout] in the model dtype, or null when y32 is used
@@ -30,6 +32,7 @@ struct GemmPlan {
     int raster;    // kind 0: workgroups walk the tiles in 8 x 4 blocks per XCD (tiles then counts whole blocks)
 };
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
+enum { CONV_WSK_VARIANTS = 6 };          // 16x64, 32x64, 64x64, 16x16, 16x32, 32x32
 void conv_wsk_tile(int variant, int *bm, int *bn);
 size_t conv_wsk_lds_bytes(int variant, int nw);
 hipError_t conv_gemm_init();   // raises the dynamic LDS limit of the 256x256 tile once per process
