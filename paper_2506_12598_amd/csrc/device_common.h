@@ -34,11 +34,22 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+// float -> bfloat16, round to nearest even: gfx950 has the conversion in hardware (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;          // NaN stays NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;               // round to nearest even
+    return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f);
+}
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// two floats -> two 16-bit values in one word (a in the low half)
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float a, float b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, bf16x2));
+}
+__device__ __forceinline__ uint32_t f32x2_to_f16x2_bits(float a, float b)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, f16x2));
 }
 __device__ __forceinline__ float f16_bits_to_f32(uint32_t b)
 {
@@ -61,6 +72,7 @@ template <> struct Cvt<bf16_t> {
     __device__ static __forceinline__ void store(bf16_t *p, float v) { p->bits = (uint16_t)f32_to_bf16_bits(v); }
     __device__ static __forceinline__ float from_bits(uint32_t b) { return bf16_bits_to_f32(b); }
     __device__ static __forceinline__ uint32_t to_bits(float v) { return f32_to_bf16_bits(v); }
+    __device__ static __forceinline__ uint32_t pack2(float a, float b) { return f32x2_to_bf16x2_bits(a, b); }
 };
 template <> struct Cvt<f16_t> {
     static constexpr int VEC = 8;
@@ -68,6 +80,7 @@ template <> struct Cvt<f16_t> {
     __device__ static __forceinline__ void store(f16_t *p, float v) { p->bits = (uint16_t)f32_to_f16_bits(v); }
     __device__ static __forceinline__ float from_bits(uint32_t b) { return f16_bits_to_f32(b); }
     __device__ static __forceinline__ uint32_t to_bits(float v) { return f32_to_f16_bits(v); }
+    __device__ static __forceinline__ uint32_t pack2(float a, float b) { return f32x2_to_f16x2_bits(a, b); }
 };
 
 // V consecutive elements <-> V floats.  V == Cvt<T>::VEC uses one 16-byte access, V == 1 a scalar one.
@@ -98,18 +111,35 @@ template <typename T, int V> struct Pack {
         } else {
             uint32_t w[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) w[i] = Cvt<T>::to_bits(v[2 * i]) | (Cvt<T>::to_bits(v[2 * i + 1]) << 16);
+            for (int i = 0; i < 4; ++i) w[i] = Cvt<T>::pack2(v[2 * i], v[2 * i + 1]);
             *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
 };
+
+// erf(x) to about 2e-7 absolute: the rational form 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p |x|)
+// (Abramowitz & Stegun 7.1.26, error below 1.5e-7 in exact arithmetic), with the hardware reciprocal and exp2.
+// About a third of the instructions of the library erff, which made an element-wise GELU ALU-bound; the absolute
+// error is what matters for GELU, which multiplies erf by x / 2.
+__device__ __forceinline__ float fast_erf(float x)
+{
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);
+    const float r = fmaf(-p * t, e, 1.0f);
+    return copysignf(r, x);
+}
 
 __device__ __forceinline__ float apply_act(int act, float v)
 {
     switch (act) {
     case ACT_RELU:  return fmaxf(v, 0.0f);
     case ACT_RELU6: return fminf(fmaxf(v, 0.0f), 6.0f);
-    case ACT_GELU:  return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f));
+    case ACT_GELU:  return 0.5f * v * (1.0f + fast_erf(v * 0.70710678118654752440f));
     default:        return v;
     }
 }

@@ -800,7 +800,10 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
             out->workgroups = (uint32_t)pl.tiles * (uint32_t)pl.splits;
             out->launches = pl.splits > 1 ? 2 : 1;
         } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1) {
-            name = "dwconv_kernel";
+            DwConvArgs da{};
+            da.B = (int)batch; da.C = P.L.c; da.Ho = P.L.h; da.Wo = P.L.w; da.KH = P.L.kh; da.KW = P.L.kw; da.stride = P.L.stride;
+            da.dtype = model->dtype == ECLIP_F32 ? DT_F32 : (model->dtype == ECLIP_BF16 ? DT_BF16 : DT_F16);
+            name = dwconv_pixels_per_thread(da, (int)model->pool->streams[mask_id].n_cu) == 4 ? "dwconv3_row_kernel" : "dwconv_kernel";
             out->workgroups = (uint32_t)((rows * (P.L.c / ((P.L.c % 8 || model->dtype == ECLIP_F32) ? (model->dtype == ECLIP_F32 && P.L.c % 4 == 0 ? 4 : 1) : 8)) + 255) / 256);
         } else {
             name = "conv_f32_kernel";

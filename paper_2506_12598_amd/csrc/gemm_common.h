@@ -56,8 +56,8 @@ __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint1
             *reinterpret_cast<float4 *>(y32 + off) = make_float4(o[0], o[1], o[2], o[3]);
         } else {
             uint2 q;
-            q.x = Cvt<T>::to_bits(o[0]) | (Cvt<T>::to_bits(o[1]) << 16);
-            q.y = Cvt<T>::to_bits(o[2]) | (Cvt<T>::to_bits(o[3]) << 16);
+            q.x = Cvt<T>::pack2(o[0], o[1]);
+            q.y = Cvt<T>::pack2(o[2], o[3]);
             *reinterpret_cast<uint2 *>(y + off) = q;
         }
     } else {

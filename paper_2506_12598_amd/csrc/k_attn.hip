@@ -137,10 +137,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
         if (2 * kp2 < nkb) {
             // contraction slot e of lane group g  <->  key (2*kp2 + e/4)*16 + 4*g + e%4
             uint4 pf;
-            pf.x = Cvt<T>::to_bits(sc[2 * kp2][0] * inv) | (Cvt<T>::to_bits(sc[2 * kp2][1] * inv) << 16);
-            pf.y = Cvt<T>::to_bits(sc[2 * kp2][2] * inv) | (Cvt<T>::to_bits(sc[2 * kp2][3] * inv) << 16);
-            pf.z = Cvt<T>::to_bits(sc[2 * kp2 + 1][0] * inv) | (Cvt<T>::to_bits(sc[2 * kp2 + 1][1] * inv) << 16);
-            pf.w = Cvt<T>::to_bits(sc[2 * kp2 + 1][2] * inv) | (Cvt<T>::to_bits(sc[2 * kp2 + 1][3] * inv) << 16);
+            pf.x = Cvt<T>::pack2(sc[2 * kp2][0] * inv, sc[2 * kp2][1] * inv);
+            pf.y = Cvt<T>::pack2(sc[2 * kp2][2] * inv, sc[2 * kp2][3] * inv);
+            pf.z = Cvt<T>::pack2(sc[2 * kp2 + 1][0] * inv, sc[2 * kp2 + 1][1] * inv);
+            pf.w = Cvt<T>::pack2(sc[2 * kp2 + 1][2] * inv, sc[2 * kp2 + 1][3] * inv);
 #pragma unroll
             for (int jb = 0; jb < D / 16; ++jb) {
                 const uint16_t *vr = vt + (jb * 16 + (lane & 15)) * p.ldv + 4 * g;
@@ -160,8 +160,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
                 *reinterpret_cast<float4 *>(p.y32 + off + jb * 16) = make_float4(o[jb][0], o[jb][1], o[jb][2], o[jb][3]);
             } else {
                 uint2 q;
-                q.x = Cvt<T>::to_bits(o[jb][0]) | (Cvt<T>::to_bits(o[jb][1]) << 16);
-                q.y = Cvt<T>::to_bits(o[jb][2]) | (Cvt<T>::to_bits(o[jb][3]) << 16);
+                q.x = Cvt<T>::pack2(o[jb][0], o[jb][1]);
+                q.y = Cvt<T>::pack2(o[jb][2], o[jb][3]);
                 *reinterpret_cast<uint2 *>(p.y + off + jb * 16) = q;
             }
         }

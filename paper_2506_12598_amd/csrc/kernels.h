@@ -58,6 +58,7 @@ struct DwConvArgs {
     void *y;
     int B, H, W, C, Ho, Wo, KH, KW, stride, pad, act, dtype;
 };
+int dwconv_pixels_per_thread(const DwConvArgs &a, int n_cu);   // 4 (large 3x3 layers, 16-bit types) or 1
 hipError_t launch_dwconv(const DwConvArgs &a, int n_cu, hipStream_t s);
 
 struct PoolArgs {

@@ -94,6 +94,25 @@ def test_depthwise_conv(c, h, s, dt):
     check(m, batch=2, tol=1e-5 if dt == wl.DT_F32 else 4e-3)
 
 
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("c,h,s,res", [(64, 75, 1, False), (64, 151, 2, False), (32, 110, 1, True)])
+def test_depthwise_conv_four_pixels_per_thread(c, h, s, res, dt):
+    """Large 3x3 depthwise layers run four output pixels per thread; the switch depends on the CU count of the
+    stream, so the layer runs on the 32-CU mask, with an output width that is not a multiple of four."""
+    m = wl.single_layer("conv", dt, seed=c + h, cin=c, cout=c, h=h, w=h, k=3, stride=s, pad=1, groups=c,
+                        act=wl.ACT_RELU6, bias_std=0.5, residual=res)
+    x = wl.make_input(m, 3)
+    exp = orc.run_model(m, x)
+    g = GpuModel(m, max_batch=3)
+    try:
+        assert g.h.kernel_info(0, 1, 3)["kernel"] == "dwconv3_row_kernel"
+        got = g.run(x, table=[1])
+    finally:
+        g.free()
+    # the residual case is two layers (convolution, then add + ReLU6): two roundings to the 16-bit type
+    assert rel_to_range(got, exp) <= (8e-3 if res else 4e-3)
+
+
 # ---------------- linear -------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dt", DTS)
 @pytest.mark.parametrize("rows,k,n,act,res", [(128, 768, 2304, wl.ACT_NONE, False), (48, 512, 128, wl.ACT_GELU, False),
