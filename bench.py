@@ -331,6 +331,137 @@ def characterize_mode():
 
 
 # ---------------------------------------------------------------------------------------------------
+# the paper's partitioning scenarios side by side (Sec. IV "Spatial Partitioning Scenarios", Table I) and the
+# per-kernel optimizer with a sweep of the switch budget (Sec. III-B)
+# ---------------------------------------------------------------------------------------------------
+def policies_mode(args):
+    import dataclasses
+    import torch
+    import workloads as wl
+    import paper_2506_12598_amd as ec
+
+    cfg = args.config
+    steps = args.steps if args.steps is not None else {1: 1000, 2: 500, 3: 200, 4: 20}[cfg]
+    warmup = args.warmup if args.warmup is not None else {1: 100, 2: 50, 3: 20, 4: 2}[cfg]
+    configs = [32, 64, 128, 192, 256]
+    full = len(configs) - 1
+    stage_models = wl.config_models(cfg)
+    n_w = len(stage_models)
+    # one kernel group per kernel: the unit of the paper's model
+    models = [dataclasses.replace(m, group_of_layer=list(range(len(m.layers))), n_groups=len(m.layers)) for m in stage_models]
+    batches = [[4]] * 3 + [[8]] if cfg == 4 else [[1]] * n_w
+    pb = [b[0] for b in batches]
+
+    masks, prof_id = [], {}
+    for w in range(n_w):
+        for ci, c in enumerate(configs):
+            prof_id[(w, ci)] = len(masks)
+            masks.append((ec.eclip_mask_layout(256, 32, n_w, w, c // 32), w))
+    prof_pool = ec.Pool(masks)
+    workers = [Worker(ec, torch, prof_pool, m, i, args.depth, batches[i]) for i, m in enumerate(models)]
+    # beta[w][k][c]: latency of kernel k of worker w on configuration c, in ns (Sec. III-B, factor (i))
+    beta = [[[int(wk.h.profile_group(k, prof_id[(w, ci)], batch=pb[w], iters=10 if cfg < 4 else 3)[0]) for ci in range(len(configs))]
+             for k in range(len(wk.model.layers))] for w, wk in enumerate(workers)]
+    same_ns, pooled_ns, _ = prof_pool.bench_switch(0, 1, 2000, with_create=False)
+    switch_cost_ns = max(0, int(pooled_ns - same_ns))
+    log(f"config {cfg}: {[len(m.layers) for m in models]} kernels per worker profiled on {configs} CUs; switch cost {switch_cost_ns} ns")
+
+    def predicted_us(assign):
+        """The model's objective for an assignment: sum over workers of solo latency x (1 + alpha), alpha from the
+        CUs by which the workers' kernel-weighted average allocations exceed the GPU (Sec. III-B), in us."""
+        tot_b, s_avg = 0.0, 0.0
+        for w, a in enumerate(assign):
+            tot_b += sum(beta[w][k][c] for k, c in enumerate(a))
+            s_avg += sum(configs[c] for c in a) / len(a)
+        return tot_b * (1.0 + max(0.0, s_avg - 256.0) / 256.0) / 1e3
+
+    ones = [[1] * len(m.layers) for m in models]
+    policies = []                                       # (name, per-kernel configuration index per worker or None = unmasked)
+    policies.append(("Baseline: one shared unmasked stream", "shared"))
+    policies.append(("Unpartitioned: one unmasked stream per worker", None))
+    # Model-Wise: the fewest CUs whose whole-model latency stays within slo x the latency on all CUs
+    mw = []
+    for w in range(n_w):
+        solo = sum(b[full] for b in beta[w])
+        c_w = next(ci for ci in range(len(configs)) if sum(b[ci] for b in beta[w]) <= args.slo * solo)
+        mw.append([c_w] * len(beta[w]))
+    policies.append((f"Model-Wise (fewest CUs within {args.slo:g}x solo latency)", mw))
+    # Kernel-Wise on pooled streams: every kernel at the fewest CUs that keep it within 5 % of its latency on all CUs
+    kw = [[next(ci for ci in range(len(configs)) if b[ci] <= 1.05 * b[full]) for b in beta[w]] for w in range(n_w)]
+    policies.append(("KW-Prealloc (every kernel at its own CU knee, pooled streams)", kw))
+    # ECLIP on the stage groups bench.py uses by default
+    g_beta = [[[sum(beta[w][k][ci] for k in range(len(m.layers)) if m.group_of_layer[k] == g) for ci in range(len(configs))]
+               for g in range(m.n_groups)] for w, m in enumerate(stage_models)]
+    g_nk = [[sum(1 for k in m.group_of_layer if k == g) for g in range(m.n_groups)] for m in stage_models]
+    mc = max(1, 4 // n_w)
+    a_g, _, _ = ec.eclip_alloc_solve(256, configs, g_nk, g_beta, args.switch_max, max_configs=mc, switch_cost_ns=switch_cost_ns)
+    policies.append((f"ECLIP, stage groups, switchMax {args.switch_max}, <= {mc} configs/worker, switch cost",
+                     [[a_g[w][m.group_of_layer[k]] for k in range(len(m.layers))] for w, m in enumerate(stage_models)]))
+    # ECLIP on single kernels: the optimizer derives the groups; sweep of the switch budget
+    a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, args.switch_max, max_configs=mc, switch_cost_ns=switch_cost_ns)
+    policies.append((f"ECLIP, per kernel, switchMax {args.switch_max}, <= {mc} configs/worker, switch cost", a))
+    # the budget alone (no price on a switch), as in the paper: how much do the switches it allows cost here?
+    for sm in (0, 2, 4, 8, 14, 28):
+        a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, sm, max_configs=mc)
+        policies.append((f"ECLIP, per kernel, switchMax {sm}, <= {mc} configs/worker, no switch cost", a))
+    a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, args.switch_max)
+    policies.append((f"ECLIP, per kernel, switchMax {args.switch_max}, model as printed (no stream limit, no switch cost)", a))
+
+    rows = []
+    pool = prof_pool
+    for name, assign in policies:
+        masks = [(None, -1)] + [(None, w) for w in range(n_w)]
+        mask_id = {}
+        if assign not in (None, "shared"):
+            for w in range(n_w):
+                for c in sorted(set(assign[w])):
+                    mask_id[(w, c)] = len(masks)
+                    masks.append((ec.eclip_mask_layout(256, 32, n_w, w, configs[c] // 32), w))
+        new_pool = ec.Pool(masks)
+        for wk in workers:
+            wk.h.rebind(new_pool)
+        pool.destroy()
+        pool = new_pool
+        for w, wk in enumerate(workers):
+            if assign == "shared": wk.h.alloc_set([0] * len(wk.model.layers))
+            elif assign is None: wk.h.alloc_set([1 + w] * len(wk.model.layers))
+            else: wk.h.alloc_set([mask_id[(w, c)] for c in assign[w]])
+        sw = [wk.h.switches() for wk in workers]
+        run_closed(workers, warmup)
+        torch.cuda.synchronize()
+        dt, served = run_closed(workers, steps)
+        torch.cuda.synchronize()
+        cus = "-" if assign in (None, "shared") else " | ".join(
+            ",".join(f"{configs[c]}x{n}" for c, n in _runs(a)) for a in assign)
+        rows.append({"policy": name, "inferences_per_s": served / dt, "ms_per_step": 1e3 * dt / steps, "switches_per_request": sw,
+                     "streams_in_use": len(masks) - 1 - n_w if assign not in (None, "shared") else 1 if assign == "shared" else n_w,
+                     "predicted_us": None if assign in (None, "shared") else predicted_us(assign), "allocation": cus})
+        log(f"{name}: {rows[-1]['inferences_per_s']:.0f} inf/s, switches {sw}")
+    for wk in workers:
+        wk.h.free()
+    pool.destroy()
+    note = " (every request at batch 1 in this mode)" if cfg == 3 else ""
+    print(f"# {WORKLOADS[cfg]}{note}; closed loop, {args.depth} requests in flight per worker, {steps} steps; CU configurations {configs}")
+    print(f"{'policy':98s} {'inf/s':>9s} {'ms/step':>8s} {'switches/request':>18s} {'streams':>7s} {'model us':>9s}")
+    for r in rows:
+        pu = "-" if r["predicted_us"] is None else f"{r['predicted_us']:.1f}"
+        print(f"{r['policy']:98s} {r['inferences_per_s']:9.0f} {r['ms_per_step']:8.3f} {str(r['switches_per_request']):>18s} "
+              f"{r['streams_in_use']:7d} {pu:>9s}")
+    print("# allocations (CUs x consecutive kernels, per worker):")
+    for r in rows:
+        if r["allocation"] != "-":
+            print(f"#   {r['policy'][:60]:60s} {r['allocation']}")
+
+
+def _runs(a):
+    out = []
+    for c in a:
+        if out and out[-1][0] == c: out[-1][1] += 1
+        else: out.append([c, 1])
+    return out
+
+
+# ---------------------------------------------------------------------------------------------------
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -347,6 +478,8 @@ def main():
     ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
     ap.add_argument("--only", default=None, help="with --kernels: comma-separated case keys (layernorm, softmax, maxpool, dwconv, "
                     "gap, gelu, copy, fc, gemm8192, gemm4096, ffn1, ffn2, proj, base_ffn1)")
+    ap.add_argument("--policies", action="store_true", help="compare the paper's partitioning scenarios and sweep the switch budget")
+    ap.add_argument("--slo", type=float, default=3.0, help="with --policies: Model-Wise latency target as a multiple of solo latency")
     ap.add_argument("--characterize", action="store_true", help="CU-mask geometry, switch cost and stream-count sweep")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -364,6 +497,9 @@ def main():
         return
     if args.characterize:
         characterize_mode()
+        return
+    if args.policies:
+        policies_mode(args)
         return
     time.sleep(0.5)
     idle_w = PowerSampler().read()          # board power before any kernel of this process has run
