@@ -199,6 +199,80 @@ def run_closed(workers, steps):
 
 
 # ---------------------------------------------------------------------------------------------------
+# HBM traffic from hardware counters (two rocprofv3 --pmc runs of this file, reduced by --traffic-from)
+# ---------------------------------------------------------------------------------------------------
+CSRC = os.path.join(ROOT, "paper_2506_12598_amd", "csrc")
+COPY_ROWS, COPY_WIDTH = 480000, 1024          # calibration copy: 2 x 983 MB read, 983 MB + 1966 MB written
+
+
+def source_hash():
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(CSRC)):
+        if f.endswith((".hip", ".h", ".cpp")):
+            h.update(open(os.path.join(CSRC, f), "rb").read())
+    return h.hexdigest()
+
+
+def traffic_path(cfg):
+    return os.path.join(ROOT, "profiles", f"traffic_config{cfg}.json")
+
+
+def pmc_copy(ec, torch):
+    """One request of a two-layer element-wise model (plain copies of a known size): the calibration kernel for the
+    FETCH_SIZE / WRITE_SIZE counters."""
+    import workloads as wl
+    import workloads.graphs as G
+    bb = G._Builder("cp", wl.DT_BF16, 0, G.IN_SEQ, COPY_WIDTH, 1, COPY_ROWS)
+    x = bb.eltwise(-1)
+    bb.eltwise(x)
+    m = bb.finish()
+    pool = ec.Pool([(None, -1)])
+    h = ec.Model(pool, m, wl.to_storage(m.weights, m.dtype), max_batch=1)
+    h.alloc_set([0])
+    d_in = torch.zeros((1, COPY_ROWS, COPY_WIDTH), dtype=torch.int16, device="cuda")
+    d_out = torch.zeros((1, COPY_ROWS, COPY_WIDTH), dtype=torch.float32, device="cuda")
+    h.submit(d_in.data_ptr(), d_out.data_ptr(), 1).wait()
+    torch.cuda.synchronize()
+    h.free(); pool.destroy()
+
+
+def traffic_from(cfg, fetch_csv, write_csv, command):
+    """Reduces the counter_collection CSVs of two `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE; both of
+    `bench.py --pmc-copy ...`) to HBM bytes per launch for every kernel function, scaled by what the same counter
+    reads for the calibration copy, and stores them with a hash of the kernel sources."""
+    import csv
+    import re
+
+    def reduce(path, counter):
+        acc = {}
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] != counter:
+                continue
+            m = re.search(r"(\w+)(<|\(|$)", r["Kernel_Name"].replace("void ", "").replace("eclip::(anonymous namespace)::", ""))
+            name = m.group(1) if m else r["Kernel_Name"]
+            a = acc.setdefault(name, [0.0, 0])
+            a[0] += float(r["Counter_Value"]); a[1] += 1
+        return acc
+
+    n = COPY_ROWS * COPY_WIDTH * 2
+    f, w = reduce(fetch_csv, "FETCH_SIZE"), reduce(write_csv, "WRITE_SIZE")
+    assert f["eltwise_kernel"][1] == 2 and w["eltwise_kernel"][1] == 2, "expected the two calibration copies"
+    scale_f = (2 * n) / (f["eltwise_kernel"][0] * 1024.0)          # counters are in KiB
+    scale_w = (3 * n) / (w["eltwise_kernel"][0] * 1024.0)
+    kernels = {}
+    for k in f:
+        if k in w and k != "eltwise_kernel":
+            kernels[k] = {"dispatches": f[k][1], "fetch_bytes_per_launch": scale_f * 1024.0 * f[k][0] / f[k][1],
+                          "write_bytes_per_launch": scale_w * 1024.0 * w[k][0] / w[k][1]}
+    out = {"command": command, "counter_unit": "KiB", "copy_bytes_read": 2 * n, "copy_bytes_written": 3 * n,
+           "copy_scale_fetch": scale_f, "copy_scale_write": scale_w, "kernels": kernels, "source_sha256": source_hash()}
+    with open(traffic_path(cfg), "w") as fh:
+        json.dump(out, fh, indent=1)
+    print(json.dumps(out, indent=1))
+
+
+# ---------------------------------------------------------------------------------------------------
 # single kernels at roofline shapes
 # ---------------------------------------------------------------------------------------------------
 def kernels_mode(only=None):
@@ -480,6 +554,9 @@ def main():
                     "gap, gelu, copy, fc, gemm8192, gemm4096, ffn1, ffn2, proj, base_ffn1)")
     ap.add_argument("--policies", action="store_true", help="compare the paper's partitioning scenarios and sweep the switch budget")
     ap.add_argument("--slo", type=float, default=3.0, help="with --policies: Model-Wise latency target as a multiple of solo latency")
+    ap.add_argument("--pmc-copy", action="store_true", help="also run the calibration copy (for rocprofv3 --pmc runs)")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
+                    help="reduce two rocprofv3 --pmc counter_collection CSVs to profiles/traffic_config<N>.json and exit")
     ap.add_argument("--characterize", action="store_true", help="CU-mask geometry, switch cost and stream-count sweep")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -487,6 +564,11 @@ def main():
               "placed on different GPUs without any exchange step. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    if args.traffic_from:
+        traffic_from(args.config, args.traffic_from[0], args.traffic_from[1],
+                     "rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) --output-format csv -- python3 bench.py --pmc-copy "
+                     f"--config {args.config} --steps 200 --warmup 20 --window 0 --no-cpu-baseline")
+        return
     import torch
     import workloads as wl
     import paper_2506_12598_amd as ec
@@ -501,6 +583,8 @@ def main():
     if args.policies:
         policies_mode(args)
         return
+    if args.pmc_copy:
+        pmc_copy(ec, torch)
     time.sleep(0.5)
     idle_w = PowerSampler().read()          # board power before any kernel of this process has run
 
@@ -656,7 +740,14 @@ def main():
         ach, peak, unit, bound = d["flops"] / d["ns"] / 1e3, MFMA_PEAK_TFLOPS, "TFLOP/s", "mfma"
     else:
         ach, peak, unit, bound = d["bytes"] / d["ns"], HBM_PEAK_GBS, "GB/s", "hbm"
-    roofline = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak, "traffic": None,
+    # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counters of an earlier profiled run of this workload;
+    # null when there is none or when a kernel source has changed since
+    traffic = None
+    if os.path.exists(traffic_path(cfg)):
+        t = json.load(open(traffic_path(cfg)))
+        if t.get("source_sha256") == source_hash() and dom in t["kernels"]:
+            traffic = t["kernels"][dom]["fetch_bytes_per_launch"] + t["kernels"][dom]["write_bytes_per_launch"]
+    roofline = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak, "traffic": traffic,
                 "kernel": dom, "flop_per_byte": ai, "layers_per_step": d["layers"], "launches_per_step": d["launches"],
                 "avg_layer_us": d["ns"] / d["layers"] / 1e3, "avg_bytes_per_layer": d["bytes"] / d["layers"],
                 "achieved_tflops": d["flops"] / d["ns"] / 1e3, "achieved_gbs": d["bytes"] / d["ns"],

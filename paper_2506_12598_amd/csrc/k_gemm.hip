@@ -423,6 +423,28 @@ static void set_raster(GemmPlan &pl, long M, long N)
     pl.tiles = (int)(cdiv(blocks, 8) * 8 * 32);
 }
 
+// Wave-split-K tiles are dealt to the 8 XCDs along one dimension when that dimension has enough tiles to keep the
+// XCDs evenly loaded (a multiple of 8 tiles): along N when N >= M (the weights,
+// N x K, are then the larger operand; the im2col operand is at most M x K), else along M; the other dimension is the
+// second choice.
+static void set_xcd_split(GemmPlan &pl, long M, long N)
+{
+    int bm, bn;
+    conv_wsk_tile(pl.variant, &bm, &bn);
+    const long tm = cdiv(M, bm), tn = cdiv(N, bn);
+    auto fits = [](long t) { return t >= 8 && t % 8 == 0; };
+    const bool n_first = N >= M;                      // W is N x K, the im2col operand at most M x K
+    const int order[2] = {n_first ? 2 : 3, n_first ? 3 : 2};
+    for (int r : order) {
+        const long t = r == 2 ? tn : tm, other = r == 2 ? tm : tn;
+        if (fits(t)) {
+            pl.raster = r;
+            pl.tiles = (int)(8 * cdiv(t, 8) * other);
+            return;
+        }
+    }
+}
+
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
 {
     auto tiles = [&](int v) { int bm, bn, bk; conv_gemm_tile(v, &bm, &bn, &bk); return cdiv(M, bm) * cdiv(N, bn); };
@@ -436,6 +458,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     if (f_kind == 1 && f_variant >= 0 && f_variant < CONV_WSK_VARIANTS && (f_n == 4 || f_n == 8 || f_n == 16) &&
         conv_wsk_lds_bytes(f_variant, f_n) <= 128 * 1024) {
         pl.kind = 1; pl.variant = f_variant; pl.nw = f_n; pl.tiles = (int)wsk_tiles(f_variant);
+        set_xcd_split(pl, M, N);
         return pl;
     }
     if (f_kind == 0 && f_variant >= 0 && f_variant <= 3) {
@@ -501,6 +524,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         }
     }
     if (pl.kind == 0) set_raster(pl, M, N);
+    else set_xcd_split(pl, M, N);
     return pl;
 }
 
@@ -526,6 +550,7 @@ hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream
     if (pl.kind == 1) {
         conv_wsk_tile(pl.variant, &bm, &bn);
         d.tiles_m = (d.M + bm - 1) / bm;
+        d.tiles_n = (d.N + bn - 1) / bn;
         return launch_conv_wsk(d, a.dtype, pl.variant, pl.nw, pl.tiles, s);
     }
     if (a.dtype == DT_BF16) return launch_t<bf16_t>(d, pl, s);

@@ -24,7 +24,24 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
     extern __shared__ __attribute__((aligned(16))) float red[];    // [NW][TM*TN][64][4]
     constexpr int BM = TM * 16, BN = TN * 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tile_m = blockIdx.x % p.tiles_m, tile_n = blockIdx.x / p.tiles_m;
+    // Workgroup b runs on XCD b % 8, and each XCD has its own L2.  With raster 2 (3) the tiles are dealt so that an
+    // XCD owns a contiguous range of tile columns (rows): the larger operand, the weights (the activations), is then
+    // fetched from memory by one XCD only instead of by all eight.
+    int tile_m, tile_n;
+    if (p.raster == 2) {
+        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_n + 7) >> 3, r = q / p.tiles_m;
+        tile_m = q - r * p.tiles_m;
+        tile_n = xcd * per + r;
+        if (r >= per || tile_n >= p.tiles_n) return;
+    } else if (p.raster == 3) {
+        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_m + 7) >> 3, r = q / p.tiles_n;
+        tile_n = q - r * p.tiles_n;
+        tile_m = xcd * per + r;
+        if (r >= per || tile_m >= p.tiles_m) return;
+    } else {
+        tile_m = blockIdx.x % p.tiles_m;
+        tile_n = blockIdx.x / p.tiles_m;
+    }
     const int m_base = tile_m * BM, n_base = tile_n * BN;
     const int row = lane & 15, g = lane >> 4;
 
