@@ -74,6 +74,35 @@ __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint1
     }
 }
 
+// The same for 8 consecutive channels n..n+7 of row m, with 16-byte accesses: requires N % 8 == 0, n % 8 == 0,
+// m < M and n < N (checked by the caller).  `o` holds the sums without bias.
+template <typename T>
+__device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N, int act,
+                                                int m, int n, float (&o)[8])
+{
+    const long off = (long)m * N + n;
+    if (bias) {
+        float bv[8];
+        Pack<T, 8>::load(reinterpret_cast<const T *>(bias) + n, bv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += bv[e];
+    }
+    if (res) {
+        float rv[8];
+        Pack<T, 8>::load(reinterpret_cast<const T *>(res) + off, rv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += rv[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = apply_act(act, o[e]);
+    if (y32) {
+        *reinterpret_cast<float4 *>(y32 + off) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4 *>(y32 + off + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    } else {
+        Pack<T, 8>::store(reinterpret_cast<T *>(y) + off, o);
+    }
+}
+
 // wave-split-K kernel (k_wsk.hip)
 hipError_t launch_conv_wsk(const GemmDev &d, int dtype, int variant, int nw, int tiles, hipStream_t s);
 

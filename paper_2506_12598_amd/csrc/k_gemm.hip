@@ -59,7 +59,17 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
     // (large problems) those 32 workgroups form an 8 x 4 block of tiles, so that one K step pulls 8 + 4
     // operand tiles into the L2 instead of up to 32 + 1; blocks are dealt to the XCDs in row-major order.
     int tile_m, tile_n;
-    if (p.raster) {
+    if (p.raster == 2) {                      // an XCD owns a contiguous range of tile columns (mid-size problems)
+        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_n + 7) >> 3, r = q / p.tiles_m;
+        tile_m = q - r * p.tiles_m;
+        tile_n = xcd * per + r;
+        if (r >= per || tile_n >= p.tiles_n) return;
+    } else if (p.raster == 3) {               // ... or of tile rows
+        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_m + 7) >> 3, r = q / p.tiles_n;
+        tile_n = q - r * p.tiles_n;
+        tile_m = xcd * per + r;
+        if (r >= per || tile_m >= p.tiles_m) return;
+    } else if (p.raster) {
         const int b = blockIdx.x, l = b >> 3, w = l & 31;
         const int sb = (l >> 5) * 8 + (b & 7);
         const int sbm = (p.tiles_m + 7) >> 3;
@@ -223,23 +233,27 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
         // Two groups of wavefronts, half a step apart.  Wavefronts w and w + 4 share a SIMD, and WN == 4 puts
         // them in different groups (group = wave / 4 = wm).  Time is cut into phases by workgroup barriers; in
         // every phase one group runs its memory half-step (fragments of step t from LDS into registers, tile
-        // t+1 from registers into LDS) while the other issues the global loads of tile t+3 and runs the 32 MFMAs of its
+        // t+1 from registers into LDS) while the other issues the global loads of tile t+3 and runs the MFMAs of its
         // previous half-step, so the matrix pipe and the LDS pipe of each SIMD are busy at the same time
         // instead of taking turns.  Group 1 starts one phase late and group 0 ends one phase late: both pass
         //   1 + (1 or 0) + 2 * steps + (0 or 1)
         // barriers, and the trip count is the same for every wavefront of a workgroup.
         // LDS hazards: slot s = (t+1)%2 is written in the memory half-steps of step t (phases 2t, 2t+1); its
         // previous content (tile t-1) was last read in phase 2t-1, and it is first read in phase 2t+2.
-        static_assert(LOOP != LOOP_PINGPONG || (RS == 2 && WM == 2 && WN == 4 && BK == 32), "ping-pong schedule: 8 wavefronts, two register sets");
+        static_assert(LOOP != LOOP_PINGPONG || (RS == 2 && WM == 2 && WN == 4), "ping-pong schedule: 8 wavefronts, two register sets");
+        constexpr int TK = BK / 32;              // matrix instructions along K per step and 16x16 block
         const bool late = wm != 0;
-        uint4 fa[TM], fb[TN];
+        uint4 fa[TK][TM], fb[TK][TN];
         auto read_frags = [&](int slot) {
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const uint4 *>(&sB0[slot * BN * LDK + (wn * (BN / WN) + j * 16 + frag_row) * LDK + frag_k]);
+            for (int ks = 0; ks < TK; ++ks) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const uint4 *>(&sA0[slot * BM * LDK + (wm * (BM / WM) + i * 16 + frag_row) * LDK + frag_k]);
+                for (int j = 0; j < TN; ++j)
+                    fb[ks][j] = *reinterpret_cast<const uint4 *>(&sB0[slot * BN * LDK + (wn * (BN / WN) + j * 16 + frag_row) * LDK + ks * 32 + frag_k]);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    fa[ks][i] = *reinterpret_cast<const uint4 *>(&sA0[slot * BM * LDK + (wm * (BM / WM) + i * 16 + frag_row) * LDK + ks * 32 + frag_k]);
+            }
         };
         // the loads of a later tile are issued from inside the MFMA half-step (their address arithmetic fills
         // issue slots between matrix instructions), which keeps the memory half-step down to LDS traffic
@@ -247,9 +261,11 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
             __builtin_amdgcn_s_setprio(1);
             load_next(na, nb);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int ks = 0; ks < TK; ++ks)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[j], fa[i], acc[i][j]);
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[ks][j], fa[ks][i], acc[i][j]);
             __builtin_amdgcn_s_setprio(0);
         };
         store_tile(0, ra[0], rb[0]);
@@ -302,6 +318,48 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
     const int m_l = m_base + wm * (BM / WM) + (lane & 15);
     const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
 
+    if (p.splits == 1 && (p.N & 7) == 0 && TM % 2 == 0) {
+        // Row-contiguous stores.  Straight out of the accumulators a store instruction would write 8 bytes to each
+        // of 64 different rows (measured: 6.4 us for the 12.6 MB output of a 1536 x 4096 layer, 2 TB/s).  Instead
+        // each wavefront passes its sub-tile through a private LDS buffer, 32 rows at a time, and writes 16 bytes
+        // (8 channels) per lane along the rows: whole 128-byte lines, and the bias and residual reads get the same
+        // shape.  The buffer is private to the wavefront, so after the one barrier that ends the K loop's use of
+        // LDS only the wavefront's own LDS counter is waited on.
+        constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
+        constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass
+        static_assert(32 % RPP == 0 || RPP > 32, "whole passes per 32 rows");
+        __syncthreads();
+        float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
+        const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
+        const int n = n_base + wn * (BN / WN) + col8;
+        static_for<TM / 2>([&](auto hc) {
+            constexpr int h = decltype(hc)::value;
+            static_for<2>([&](auto ic) {
+                constexpr int i2 = decltype(ic)::value;
+                static_for<TN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    const f32x4 a4 = acc[2 * h + i2][j];
+                    *reinterpret_cast<float4 *>(&stage[(i2 * 16 + (lane & 15)) * SP + j * 16 + (lane >> 4) * 4]) = make_float4(a4[0], a4[1], a4[2], a4[3]);
+                });
+            });
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): this wavefront's LDS writes have landed
+#pragma unroll
+            for (int ps = 0; ps < (32 + RPP - 1) / RPP; ++ps) {
+                const int rr = ps * RPP + rr0;
+                const int m = m_base + wm * (BM / WM) + h * 32 + rr;
+                if (rr < 32 && m < p.M && n < p.N) {
+                    const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
+                    const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
+                    float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+                    epilogue_store8<T>(p.bias, p.res, p.y, p.y32, p.N, p.act, m, n, o);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0xc07f);              // reads done before the next 32 rows overwrite the buffer
+        });
+        return;
+    }
     if (p.splits == 1) {
         static_for<TM>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
@@ -368,7 +426,7 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
 }
 
 struct Variant { int bm, bn, bk; };
-constexpr Variant kVariants[4] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}};
+constexpr Variant kVariants[CONV_GEMM_VARIANTS] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}, {128, 256, 64}};
 
 constexpr size_t lds_bytes(int bm, int bn, int bk, int pad = 8) { return (size_t)2 * (bm + bn) * (bk + pad) * 2; }
 
@@ -380,7 +438,8 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
     case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, dim3(256), lds_bytes(128, 128, 32), s, d); break;
     case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, dim3(256), lds_bytes(64, 64, 64), s, d); break;
     case 2: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, dim3(256), lds_bytes(32, 64, 64), s, d); break;
-    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(256, 256, 32, 16), s, d); break;
+    case 3: hipLaunchKernelGGL((conv_gemm_kernel<T, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(256, 256, 32, 16), s, d); break;
+    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 256, 64, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(128, 256, 64, 16), s, d); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
@@ -394,16 +453,19 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
 
 hipError_t conv_gemm_init()
 {
-    hipError_t e = hipFuncSetAttribute((const void *)conv_gemm_kernel<bf16_t, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(256, 256, 32, 16));
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)conv_gemm_kernel<f16_t, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(256, 256, 32, 16));
+    hipError_t e;
+#define SET(T, BM, BN, BK)                                                                                                   \
+    if ((e = hipFuncSetAttribute((const void *)conv_gemm_kernel<T, BM, BN, BK, 2, 4, 2, LOOP_PINGPONG>,                      \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(BM, BN, BK, 16))) != hipSuccess) \
+        return e;
+    SET(bf16_t, 256, 256, 32) SET(f16_t, 256, 256, 32) SET(bf16_t, 128, 256, 64) SET(f16_t, 128, 256, 64)
+#undef SET
+    return hipSuccess;
 }
 
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk)
 {
-    const int v = variant < 0 ? 0 : (variant > 3 ? 3 : variant);
+    const int v = variant < 0 ? 0 : (variant >= CONV_GEMM_VARIANTS ? CONV_GEMM_VARIANTS - 1 : variant);
     *bm = kVariants[v].bm;
     *bn = kVariants[v].bn;
     *bk = kVariants[v].bk;
@@ -417,7 +479,14 @@ static void set_raster(GemmPlan &pl, long M, long N)
     int bm, bn, bk;
     conv_gemm_tile(pl.variant, &bm, &bn, &bk);
     const long tm = cdiv(M, bm), tn = cdiv(N, bn);
-    if (pl.kind != 0 || pl.splits != 1 || tm * tn < 256) return;
+    if (pl.kind != 0) return;
+    if (tm * tn < 256 || pl.splits != 1) {
+        // fewer tiles than CUs (or K slices in grid.y): deal whole tile columns or rows to the XCDs when they divide
+        // evenly, so that each L2 holds 1/8 of one operand instead of all of both
+        if (tn >= 8 && tn % 8 == 0) { pl.raster = 2; pl.tiles = (int)(tn * tm); }
+        else if (tm >= 8 && tm % 8 == 0) { pl.raster = 3; pl.tiles = (int)(tn * tm); }
+        return;
+    }
     const long blocks = cdiv(tm, 8) * cdiv(tn, 4);
     pl.raster = 1;
     pl.tiles = (int)(cdiv(blocks, 8) * 8 * 32);
@@ -461,7 +530,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         set_xcd_split(pl, M, N);
         return pl;
     }
-    if (f_kind == 0 && f_variant >= 0 && f_variant <= 3) {
+    if (f_kind == 0 && f_variant >= 0 && f_variant < CONV_GEMM_VARIANTS) {
         pl.variant = f_variant;
         pl.tiles = (int)tiles(pl.variant);
         int bm, bn, bk;

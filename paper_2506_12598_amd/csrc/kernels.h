@@ -31,6 +31,7 @@ struct GemmPlan {
     int nw;        // kind 1: wavefronts per workgroup, each taking 1/nw of K
     int raster;    // kind 0: workgroups walk the tiles in 8 x 4 blocks per XCD (tiles then counts whole blocks)
 };
+enum { CONV_GEMM_VARIANTS = 5 };         // 128x128x32, 64x64x64, 32x64x64, 256x256x32, 128x256x64
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
 enum { CONV_WSK_VARIANTS = 6 };          // 16x64, 32x64, 64x64, 16x16, 16x32, 32x32
 void conv_wsk_tile(int variant, int *bm, int *bn);

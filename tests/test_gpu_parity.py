@@ -243,7 +243,7 @@ def test_bert_base_layer_shapes_full_width():
 
 
 # ---------------- every GEMM kernel variant, forced, on ragged shapes ----------------------------------------------
-GEMM_FORCE = ["0,0,1", "0,0,3", "0,1,1", "0,1,2", "0,2,1", "0,2,5", "0,3,1", "0,3,2", "1,0,4", "1,0,8", "1,0,16", "1,1,4", "1,1,8",
+GEMM_FORCE = ["0,0,1", "0,0,3", "0,1,1", "0,1,2", "0,2,1", "0,2,5", "0,3,1", "0,3,2", "0,4,1", "0,4,3", "1,0,4", "1,0,8", "1,0,16", "1,1,4", "1,1,8",
               "1,1,16", "1,2,4", "1,2,8", "1,3,4", "1,3,8", "1,3,16", "1,4,4", "1,4,16", "1,5,8", "1,5,16"]
 
 
