@@ -545,7 +545,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         return pl;
     }
     // Every candidate is priced with a small cost model fitted to per-layer timings of all GEMM layers of the
-    // ResNet-18/50, VGG-16, MobileNetV2 and BERT-base/large graphs at batch 1 to 8, on 256 and on 128 CUs (picks
+    // ResNet-18/50/152, VGG-16, MobileNetV2 and BERT-base/large graphs at batch 1 to 8, on 256 and on 128 CUs (picks
     // within 3 % of the per-layer best of an exhaustive sweep, in total).  Times in microseconds, without the
     // launch cost that all single-launch candidates share.
     //
@@ -553,8 +553,8 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     // (16 rows per instruction: slow) and the weights as contiguous 1 KB blocks (fast); its workgroups run one
     // after another; each wavefront needs ceil(steps / depth) round trips to memory; the partial tiles of the nw
     // wavefronts are summed through LDS.
-    const double ra = 4.347e4, rw = 4.235e5;         // bytes per us per CU: activation rows, weight blocks
-    const double lat = 0.017, c_out = 4.5e-6, c_red = 9.0e-6, l2 = 3.794e8, c_wg = 0.030;
+    const double ra = 3.312e4, rw = 6.383e5;         // bytes per us per CU: activation rows, weight blocks
+    const double lat = 0.0186, c_out = 3.23e-6, c_red = 6.78e-6, l2 = 4.362e8, c_wg = 0.0288;
     double best = 1e30;
     for (int v = 0; v < CONV_WSK_VARIANTS; ++v) {
         int bm, bn;
@@ -572,18 +572,19 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
             if (cost < best) { best = cost; pl = GemmPlan{1, v, 1, (int)t, nw, 0}; }
         }
     }
-    // LDS-tiled kernel, optionally with K cut in two (second launch: about 4 us plus the traffic of the partial sums).
+    // LDS-tiled kernel, optionally with K cut in two (second launch: its cost plus the traffic of the partial sums).
     // A tile costs `shared` us per K step when workgroups share a compute unit and `alone` when it has one to itself.
-    struct { int variant; double shared, alone; } lds[3] = {{0, 0.326, 17.9}, {1, 0.212, 5.16}, {3, 0.96, 0.96}};
+    struct { int variant; double shared, alone, fixed; } lds[4] = {{0, 0.357, 5.31, 0.664}, {1, 0.268, 4.73, 0.664}, {3, 0.746, 0.746, 0.664},
+                                                                   {4, 1.0, 1.0, 2.40}};
     for (const auto &c : lds) {
         int bm, bn, bk;
         conv_gemm_tile(c.variant, &bm, &bn, &bk);
         const long KT = cdiv(K, bk);
         for (long sp = 1; sp <= (c.variant == 3 ? 1 : 2); ++sp) {
-            if (sp > 1 && (KT < 8 || (size_t)(sp * M * N) > ws_floats)) continue;
+            if (sp > 1 && (K < 512 || (size_t)(sp * M * N) > ws_floats)) continue;
             const long wgs = tiles(c.variant) * sp, per_cu = cdiv(wgs, n_cu);
-            double cost = 0.756 + (double)cdiv(KT, sp) * (per_cu == 1 ? c.alone : (double)per_cu * c.shared);
-            if (sp > 1) cost += 4.0 + (double)M * N * (4.0 * sp + 2.0) / 5.0e6;
+            double cost = c.fixed + (double)cdiv(KT, sp) * (per_cu == 1 ? c.alone : (double)per_cu * c.shared);
+            if (sp > 1) cost += 1.68 + (double)M * N * (4.0 * sp + 2.0) / 5.36e6;
             if (cost < best) {
                 best = cost;
                 pl = GemmPlan{0, c.variant, 1, (int)tiles(c.variant), 4, 0};
