@@ -31,8 +31,102 @@ namespace eclip {
 
 namespace {
 
+// Epilogue of one workgroup tile: acc[i][j] is the 16x16 block (i, j) of the wavefront's sub-tile, lane l holding
+// output pixel (l & 15) and channels 4 (l >> 4) .. +3 of the block.  `smem` is the workgroup's LDS (the K loop is
+// done with it); z is the K slice.
+template <typename T, int BM, int BN, int WM, int WN, int TM, int TN>
+__device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc)[TM][TN], uint16_t *smem, int m_base, int n_base, int z)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    // lane owns output pixel m0 + (lane & 15) and channels n0 + 4*(lane >> 4) .. +3 of each 16x16 block
+    const int m_l = m_base + wm * (BM / WM) + (lane & 15);
+    const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
+
+    if (p.splits == 1 && (p.N & 7) == 0 && TM % 2 == 0) {
+        // Row-contiguous stores.  Straight out of the accumulators a store instruction would write 8 bytes to each
+        // of 64 different rows (measured: 6.4 us for the 12.6 MB output of a 1536 x 4096 layer, 2 TB/s).  Instead
+        // each wavefront passes its sub-tile through a private LDS buffer, 32 rows at a time, and writes 16 bytes
+        // (8 channels) per lane along the rows: whole 128-byte lines, and the bias and residual reads get the same
+        // shape.  The buffer is private to the wavefront, so after the one barrier that ends the K loop's use of
+        // LDS only the wavefront's own LDS counter is waited on.
+        constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
+        constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass
+        static_assert(32 % RPP == 0 || RPP > 32, "whole passes per 32 rows");
+        __syncthreads();
+        float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
+        const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
+        const int n = n_base + wn * (BN / WN) + col8;
+        static_for<TM / 2>([&](auto hc) {
+            constexpr int h = decltype(hc)::value;
+            static_for<2>([&](auto ic) {
+                constexpr int i2 = decltype(ic)::value;
+                static_for<TN>([&](auto jc) {
+                    constexpr int j = decltype(jc)::value;
+                    const f32x4 a4 = acc[2 * h + i2][j];
+                    *reinterpret_cast<float4 *>(&stage[(i2 * 16 + (lane & 15)) * SP + j * 16 + (lane >> 4) * 4]) = make_float4(a4[0], a4[1], a4[2], a4[3]);
+                });
+            });
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): this wavefront's LDS writes have landed
+#pragma unroll
+            for (int ps = 0; ps < (32 + RPP - 1) / RPP; ++ps) {
+                const int rr = ps * RPP + rr0;
+                const int m = m_base + wm * (BM / WM) + h * 32 + rr;
+                if (rr < 32 && m < p.M && n < p.N) {
+                    const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
+                    const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
+                    float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+                    epilogue_store8<T>(p.bias, p.res, p.y, p.y32, p.N, p.act, m, n, o);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_s_waitcnt(0xc07f);              // reads done before the next 32 rows overwrite the buffer
+        });
+        return;
+    }
+    if (p.splits == 1) {
+        static_for<TM>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            static_for<TN>([&](auto jc) {
+                constexpr int j = decltype(jc)::value;
+                epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_l + i * 16, n_l + j * 16, acc[i][j]);
+            });
+        });
+        return;
+    }
+    // split-K: this slice's partial sums go to ws[z][m][n]; a second kernel adds the slices.  (A single-kernel
+    // form, in which the last slice to arrive at a per-tile counter does the sum, was measured and dropped:
+    // across XCDs it needs either a device-scope fence, i.e. a write-back of the issuing XCD's whole L2 per
+    // workgroup, or write-through stores and cache-bypassing loads for every partial sum; both cost several
+    // times the second launch.)
+    const bool vec = ((p.N & 3) == 0);
+    static_for<TM>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        static_for<TN>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            const int m = m_l + i * 16, n = n_l + j * 16;
+            if (m < p.M && n < p.N) {
+                float *dst = p.ws + ((long)z * p.M + m) * p.N + n;
+                if (vec) {
+                    *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (n + r < p.N) dst[r] = acc[i][j][r];
+                }
+            }
+        });
+    });
+}
+template <typename T, int BM, int BN, int WM, int WN, int TM, int TN>
+__device__ __forceinline__ void tile_epilogue(const GemmDev &p, f32x4 (&acc)[TM][TN], uint16_t *smem, int m_base, int n_base, int z)
+{
+    tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN>(p, acc, smem, m_base, n_base, z);
+}
+
 // K-loop schedules
-enum { LOOP_PLAIN = 0, LOOP_OVERLAP = 1, LOOP_PINGPONG = 2 };
+enum { LOOP_PLAIN = 0, LOOP_PINGPONG = 2 };
 
 template <typename T, int BM, int BN, int BK, int WM, int WN, int RS, int LOOP = LOOP_PLAIN>
 __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
@@ -80,7 +174,6 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
         tile_m = blockIdx.x % p.tiles_m;
         tile_n = blockIdx.x / p.tiles_m;
     }
-    const int z = blockIdx.y;
     const int m_base = tile_m * BM, n_base = tile_n * BN;
 
     // ---- per-thread, per-chunk addressing that does not change along K
@@ -285,7 +378,7 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
             __syncthreads();
         }
         if (!late) __syncthreads();
-    } else if constexpr (LOOP == LOOP_PLAIN) {
+    } else {
         for (int kt = kt_begin; kt < kt_end; kt += RS) {
 #pragma unroll
             for (int r = 0; r < RS; ++r) {
@@ -295,104 +388,9 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
                 compute(r & 1);
             }
         }
-    } else {
-        // Large tiles (RS == 2): the LDS stores of step t+1 share a basic block with the MFMAs of step t, so
-        // the scheduler can hide them behind the matrix pipe.  Safe with two slots: slot (t+1)%2 was last read
-        // at step t-1, and every wavefront has passed the barrier that ended that step.
-        static_assert(LOOP != LOOP_OVERLAP || RS == 2, "the overlapped loop alternates two register sets");
-        store_tile(0, ra[0], rb[0]);
-        __syncthreads();
-        for (int kt = kt_begin; kt < kt_end; kt += 2) {
-            load_next(ra[0], rb[0]);
-            compute(0);
-            store_tile(1, ra[1], rb[1]);
-            __syncthreads();
-            load_next(ra[1], rb[1]);
-            compute(1);
-            store_tile(0, ra[0], rb[0]);
-            __syncthreads();
-        }
     }
 
-    // lane owns output pixel m0 + (lane & 15) and channels n0 + 4*(lane >> 4) .. +3 of each 16x16 block
-    const int m_l = m_base + wm * (BM / WM) + (lane & 15);
-    const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
-
-    if (p.splits == 1 && (p.N & 7) == 0 && TM % 2 == 0) {
-        // Row-contiguous stores.  Straight out of the accumulators a store instruction would write 8 bytes to each
-        // of 64 different rows (measured: 6.4 us for the 12.6 MB output of a 1536 x 4096 layer, 2 TB/s).  Instead
-        // each wavefront passes its sub-tile through a private LDS buffer, 32 rows at a time, and writes 16 bytes
-        // (8 channels) per lane along the rows: whole 128-byte lines, and the bias and residual reads get the same
-        // shape.  The buffer is private to the wavefront, so after the one barrier that ends the K loop's use of
-        // LDS only the wavefront's own LDS counter is waited on.
-        constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
-        constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass
-        static_assert(32 % RPP == 0 || RPP > 32, "whole passes per 32 rows");
-        __syncthreads();
-        float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
-        const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
-        const int n = n_base + wn * (BN / WN) + col8;
-        static_for<TM / 2>([&](auto hc) {
-            constexpr int h = decltype(hc)::value;
-            static_for<2>([&](auto ic) {
-                constexpr int i2 = decltype(ic)::value;
-                static_for<TN>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
-                    const f32x4 a4 = acc[2 * h + i2][j];
-                    *reinterpret_cast<float4 *>(&stage[(i2 * 16 + (lane & 15)) * SP + j * 16 + (lane >> 4) * 4]) = make_float4(a4[0], a4[1], a4[2], a4[3]);
-                });
-            });
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): this wavefront's LDS writes have landed
-#pragma unroll
-            for (int ps = 0; ps < (32 + RPP - 1) / RPP; ++ps) {
-                const int rr = ps * RPP + rr0;
-                const int m = m_base + wm * (BM / WM) + h * 32 + rr;
-                if (rr < 32 && m < p.M && n < p.N) {
-                    const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
-                    const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
-                    float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                    epilogue_store8<T>(p.bias, p.res, p.y, p.y32, p.N, p.act, m, n, o);
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_s_waitcnt(0xc07f);              // reads done before the next 32 rows overwrite the buffer
-        });
-        return;
-    }
-    if (p.splits == 1) {
-        static_for<TM>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            static_for<TN>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_l + i * 16, n_l + j * 16, acc[i][j]);
-            });
-        });
-        return;
-    }
-    // split-K: this slice's partial sums go to ws[z][m][n]; a second kernel adds the slices.  (A single-kernel
-    // form, in which the last slice to arrive at a per-tile counter does the sum, was measured and dropped:
-    // across XCDs it needs either a device-scope fence, i.e. a write-back of the issuing XCD's whole L2 per
-    // workgroup, or write-through stores and cache-bypassing loads for every partial sum; both cost several
-    // times the second launch.)
-    const bool vec = ((p.N & 3) == 0);
-    static_for<TM>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        static_for<TN>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            const int m = m_l + i * 16, n = n_l + j * 16;
-            if (m < p.M && n < p.N) {
-                float *dst = p.ws + ((long)z * p.M + m) * p.N + n;
-                if (vec) {
-                    *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (n + r < p.N) dst[r] = acc[i][j][r];
-                }
-            }
-        });
-    });
+    tile_epilogue<T, BM, BN, WM, WN, TM, TN>(p, acc, smem, m_base, n_base, blockIdx.y);
 }
 
 // y = act(sum_z ws[z] + bias + res): one thread per 4 consecutive channels (one channel when N % 4 != 0).
