@@ -45,6 +45,8 @@ WORKLOADS = {
     2: "ResNet-50-style bf16 batch 1 + BERT-base-style fp16 seq 128 batch 1, 4 kernel groups each",
     3: "ResNet-50 bf16 + VGG-16 bf16 + MobileNetV2 fp16 + BERT-base fp16, batch 1-8 uniform per request",
     4: "3x BERT-large-style bf16 seq 384 batch 4 + ResNet-152-style bf16 batch 8 (stress)",
+    6: "second family: ALBERT-base-style fp16 seq 128 + DenseNet-121-style bf16, batch 1",
+    7: "second family: ResNeXt-50-32x4d-style bf16 + ShuffleNet-g8-style bf16, batch 1",
 }
 
 
@@ -415,11 +417,11 @@ def policies_mode(args):
     import paper_2506_12598_amd as ec
 
     cfg = args.config
-    steps = args.steps if args.steps is not None else {1: 1000, 2: 500, 3: 200, 4: 20}[cfg]
-    warmup = args.warmup if args.warmup is not None else {1: 100, 2: 50, 3: 20, 4: 2}[cfg]
+    steps = args.steps if args.steps is not None else {1: 1000, 2: 500, 3: 200, 4: 20, 6: 300, 7: 300}[cfg]
+    warmup = args.warmup if args.warmup is not None else {1: 100, 2: 50, 3: 20, 4: 2, 6: 30, 7: 30}[cfg]
     configs = [32, 64, 128, 192, 256]
     full = len(configs) - 1
-    stage_models = wl.config_models(cfg)
+    stage_models = wl.config_models(cfg if cfg <= 4 else cfg - 1)
     n_w = len(stage_models)
     # one kernel group per kernel: the unit of the paper's model
     models = [dataclasses.replace(m, group_of_layer=list(range(len(m.layers))), n_groups=len(m.layers)) for m in stage_models]
@@ -541,7 +543,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=1, choices=[1, 2, 3, 4], help="co-location mix (1 = headline workload)")
+    ap.add_argument("--config", type=int, default=1, choices=[1, 2, 3, 4, 6, 7],
+                    help="co-location mix (1 = headline workload; 6, 7 = mixes of the second workload family)")
     ap.add_argument("--depth", type=int, default=2, help="requests each worker keeps in flight")
     ap.add_argument("--window", type=float, default=10.0, help="seconds of open-loop Poisson load per policy (0 = skip)")
     ap.add_argument("--rate", type=float, default=None, help="Poisson arrivals/s per model (default: 200 for config 1, "
@@ -589,10 +592,10 @@ def main():
     idle_w = PowerSampler().read()          # board power before any kernel of this process has run
 
     cfg = args.config
-    steps = args.steps if args.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 30}[cfg]
-    warmup = args.warmup if args.warmup is not None else {1: 200, 2: 100, 3: 30, 4: 3}[cfg]
+    steps = args.steps if args.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 30, 6: 500, 7: 500}[cfg]
+    warmup = args.warmup if args.warmup is not None else {1: 200, 2: 100, 3: 30, 4: 3, 6: 50, 7: 50}[cfg]
     configs = [32, 64, 128, 192, 256] if cfg != 4 else [32, 64, 96, 128, 160, 192, 224, 256]
-    models = wl.config_models(cfg)
+    models = wl.config_models(cfg if cfg <= 4 else cfg - 1)
     n_w = len(models)
     if cfg == 3:
         rng = np.random.default_rng(77)

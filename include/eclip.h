@@ -136,7 +136,8 @@ eclip_status eclip_pool_probe(eclip_pool *pool, uint32_t mask_id, uint32_t n_blo
  * ---------------------------------------------------------------------------------------- */
 
 enum { ECLIP_OP_CONV = 1, ECLIP_OP_LINEAR, ECLIP_OP_MAXPOOL, ECLIP_OP_GAP, ECLIP_OP_LAYERNORM,
-       ECLIP_OP_SOFTMAX, ECLIP_OP_ATTENTION, ECLIP_OP_EMBED, ECLIP_OP_ELTWISE };
+       ECLIP_OP_SOFTMAX, ECLIP_OP_ATTENTION, ECLIP_OP_EMBED, ECLIP_OP_ELTWISE, ECLIP_OP_CONCAT,
+       ECLIP_OP_SHUFFLE };
 enum { ECLIP_ACT_NONE = 0, ECLIP_ACT_RELU, ECLIP_ACT_RELU6, ECLIP_ACT_GELU };
 enum { ECLIP_F32 = 0, ECLIP_BF16 = 1, ECLIP_F16 = 2 };
 enum { ECLIP_KIND_IMAGE = 0, ECLIP_KIND_SEQ = 1, ECLIP_KIND_VEC = 2 };
@@ -145,7 +146,8 @@ enum { ECLIP_IN_IMAGE = 0, ECLIP_IN_TOKENS = 1, ECLIP_IN_SEQ = 2, ECLIP_IN_VEC =
 /* One layer = one kernel of the model, in execution order.  Logical tensor layouts:
  * IMAGE [B][C][H][W]; SEQ [B][S][Hd] described as c = Hd, h = 1, w = S; VEC [B][n] as c = n.
  *   CONV       y = act(conv2d(x, W[c][cin/groups][kh][kw], stride, pad) + b + in1); zero padding;
- *              groups must be 1 or cin == c (depthwise)
+ *              groups = 1 (matrix cores), cin == c == groups (depthwise kernel) or any common
+ *              divisor of cin and c (grouped convolution, direct kernel; 16-bit models)
  *   LINEAR     y = act(x W[c][k]^T + b + in1); an IMAGE input is flattened in (C,H,W) order,
  *              a SEQ input is transformed per token
  *   MAXPOOL    kh x kw window, stride, pad (padding never wins the max)
@@ -157,6 +159,8 @@ enum { ECLIP_IN_IMAGE = 0, ECLIP_IN_TOKENS = 1, ECLIP_IN_SEQ = 2, ECLIP_IN_VEC =
  *   EMBED      input = int32 token ids [B][S]; y = tok[id] + pos[s] + typ[0]; tables at w_off
  *              (aux0 rows), g_off (aux1 rows), be_off (2 rows)
  *   ELTWISE    y = act(x + b + in1)
+ *   CONCAT     y = [x | in1] along the channel axis (second workload family: dense blocks)
+ *   SHUFFLE    channel shuffle with `groups` groups: y[.., j] = x[.., (j % groups) * (c / groups) + j / groups]
  * in0/in1 index earlier layers; -1 = the model input; in1 = -2 = absent.  Offsets are element
  * offsets into the weight blob, -1 = absent (treated as zero bias / gamma 1 / beta 0). */
 typedef struct {

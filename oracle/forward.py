@@ -23,7 +23,8 @@ _SRC = os.path.join(_HERE, "fwd_oracle.c")
 _LIB = os.path.join(_HERE, "libfwd_oracle.so")
 
 # operator / tensor-kind codes of the layer descriptor (values fixed by the descriptor format)
-OP_CONV, OP_LINEAR, OP_MAXPOOL, OP_GAP, OP_LAYERNORM, OP_SOFTMAX, OP_ATTENTION, OP_EMBED, OP_ELTWISE = range(1, 10)
+OP_CONV, OP_LINEAR, OP_MAXPOOL, OP_GAP, OP_LAYERNORM, OP_SOFTMAX, OP_ATTENTION, OP_EMBED, OP_ELTWISE, OP_CONCAT, OP_SHUFFLE = \
+    range(1, 12)
 KIND_IMAGE, KIND_SEQ, KIND_VEC = range(3)
 IN_IMAGE, IN_TOKENS, IN_SEQ, IN_VEC = range(4)
 
@@ -235,6 +236,16 @@ def run_model(model, x_in: np.ndarray, keep_all: bool = False, storage_dtype: in
         elif L.op == OP_ELTWISE:
             bias = W[L.b_off:L.b_off + L.c] if L.b_off >= 0 else None
             y = eltwise(x, bias, res, L.act, 1 if L.kind == KIND_IMAGE else np.ndim(x) - 1)
+        elif L.op == OP_CONCAT:
+            # channels are axis 1 of an image [B,C,H,W] and the last axis of a sequence / vector
+            y = np.concatenate([_f64(x), _f64(res)], axis=1 if L.kind == KIND_IMAGE else -1)
+        elif L.op == OP_SHUFFLE:
+            # channel shuffle: view the C channels as (groups, C/groups), transpose, flatten
+            ax = 1 if L.kind == KIND_IMAGE else np.ndim(x) - 1
+            xs = np.moveaxis(_f64(x), ax, -1)
+            n = L.c // L.groups
+            ys = xs.reshape(xs.shape[:-1] + (L.groups, n)).swapaxes(-1, -2).reshape(xs.shape)
+            y = np.moveaxis(ys, -1, ax)
         else:
             raise ValueError(f"unknown op {L.op}")
         if storage_dtype and L is not model.layers[-1]:

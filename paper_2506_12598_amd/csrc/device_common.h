@@ -83,7 +83,8 @@ template <> struct Cvt<f16_t> {
     __device__ static __forceinline__ uint32_t pack2(float a, float b) { return f32x2_to_f16x2_bits(a, b); }
 };
 
-// V consecutive elements <-> V floats.  V == Cvt<T>::VEC uses one 16-byte access, V == 1 a scalar one.
+// V consecutive elements <-> V floats.  V == Cvt<T>::VEC uses one 16-byte access, V == 4 of a 16-bit type an 8-byte
+// one, V == 1 a scalar one.
 template <typename T, int V> struct Pack {
     __device__ static __forceinline__ void load(const T *p, float (&v)[V])
     {
@@ -92,6 +93,10 @@ template <typename T, int V> struct Pack {
         } else if constexpr (sizeof(T) == 4) {
             const float4 q = *reinterpret_cast<const float4 *>(p);
             v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else if constexpr (V == 4) {               // four 16-bit elements: one 8-byte access
+            const uint2 q = *reinterpret_cast<const uint2 *>(p);
+            v[0] = Cvt<T>::from_bits(q.x & 0xffffu); v[1] = Cvt<T>::from_bits(q.x >> 16);
+            v[2] = Cvt<T>::from_bits(q.y & 0xffffu); v[3] = Cvt<T>::from_bits(q.y >> 16);
         } else {
             const uint4 q = *reinterpret_cast<const uint4 *>(p);
             const uint32_t w[4] = {q.x, q.y, q.z, q.w};
@@ -108,6 +113,8 @@ template <typename T, int V> struct Pack {
             Cvt<T>::store(p, v[0]);
         } else if constexpr (sizeof(T) == 4) {
             *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        } else if constexpr (V == 4) {
+            *reinterpret_cast<uint2 *>(p) = make_uint2(Cvt<T>::pack2(v[0], v[1]), Cvt<T>::pack2(v[2], v[3]));
         } else {
             uint32_t w[4];
 #pragma unroll

@@ -426,14 +426,16 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
             if (in.h + 2 * L.pad < L.kh || in.w + 2 * L.pad < L.kw) return fail(ECLIP_EINVAL, "layer %u: kernel larger than padded input", i);
             const int ho = (in.h + 2 * L.pad - L.kh) / L.stride + 1, wo = (in.w + 2 * L.pad - L.kw) / L.stride + 1;
             if (L.h != ho || L.w != wo) return fail(ECLIP_EINVAL, "layer %u: CONV output %dx%d declared, %dx%d expected", i, L.h, L.w, ho, wo);
-            const bool dw = L.groups > 1;
-            if (dw && in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: depthwise CONV directly on a channel-padded network input is not supported", i);
-            if (L.groups != 1 && !(L.groups == P.in_c_logical && L.c == L.groups))
-                return fail(ECLIP_EINVAL, "layer %u: groups must be 1 or equal to both channel counts (depthwise)", i);
+            if (L.groups < 1 || P.in_c_logical % L.groups || L.c % L.groups)
+                return fail(ECLIP_EINVAL, "layer %u: groups must divide both channel counts", i);
+            const bool dw = L.groups > 1 && L.groups == P.in_c_logical && L.c == L.groups;     // depthwise kernel
+            const bool grouped = L.groups > 1 && !dw;                                            // direct grouped kernel
+            if (L.groups > 1 && in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: grouped CONV directly on a channel-padded network input is not supported", i);
+            if (grouped && f32) return fail(ECLIP_EINVAL, "layer %u: grouped CONV (1 < groups < channels) needs a 16-bit model", i);
             if ((st = check_off(L.w_off, (size_t)L.c * (P.in_c_logical / L.groups) * L.kh * L.kw, "weight", i))) return st;
             if (L.b_off >= 0 && (st = check_off(L.b_off, L.c, "bias", i))) return st;
-            if (!f32 && !dw && in.c % 8) return fail(ECLIP_EINVAL, "layer %u: 16-bit CONV needs an input channel count that is a multiple of 8 (got %d)", i, in.c);
-            P.gemm = !f32 && !dw;
+            if (!f32 && L.groups == 1 && in.c % 8) return fail(ECLIP_EINVAL, "layer %u: 16-bit CONV needs an input channel count that is a multiple of 8 (got %d)", i, in.c);
+            P.gemm = !f32 && L.groups == 1;
             break;
         }
         case ECLIP_OP_LINEAR: {
@@ -499,11 +501,26 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
             if (in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: ELTWISE directly on a channel-padded network input is not supported", i);
             if (L.b_off >= 0 && (st = check_off(L.b_off, L.c, "bias", i))) return st;
             break;
+        case ECLIP_OP_CONCAT: {
+            if (L.in1 == -2) return fail(ECLIP_EINVAL, "layer %u: CONCAT needs two inputs", i);
+            if (L.in1 == -1 && d->in_kind == ECLIP_IN_TOKENS) return fail(ECLIP_EINVAL, "layer %u: token ids cannot be concatenated", i);
+            const Dims r = L.in1 == -1 ? in_dims : m->layers[L.in1].out;
+            if (r.kind != in.kind || r.h != in.h || r.w != in.w) return fail(ECLIP_EINVAL, "layer %u: CONCAT inputs differ in shape", i);
+            if (L.kind != in.kind || L.h != in.h || L.w != in.w || L.c != in.c + r.c) return fail(ECLIP_EINVAL, "layer %u: CONCAT output must have the summed channel count", i);
+            if (in.c != P.in_c_logical || (L.in1 == -1 && d->in_kind == ECLIP_IN_IMAGE && in_dims.c != (int)d->in_c))
+                return fail(ECLIP_EINVAL, "layer %u: CONCAT directly on a channel-padded network input is not supported", i);
+            break;
+        }
+        case ECLIP_OP_SHUFFLE:
+            if (L.kind != in.kind || L.c != in.c || L.h != in.h || L.w != in.w) return fail(ECLIP_EINVAL, "layer %u: SHUFFLE changes shape", i);
+            if (L.groups < 1 || L.c % L.groups) return fail(ECLIP_EINVAL, "layer %u: SHUFFLE groups must divide the channel count", i);
+            if (in.c != P.in_c_logical) return fail(ECLIP_EINVAL, "layer %u: SHUFFLE directly on a channel-padded network input is not supported", i);
+            break;
         default:
             return fail(ECLIP_EINVAL, "layer %u: unknown op %d", i, L.op);
         }
-        if (L.in1 != -2) {
-            if (L.op == ECLIP_OP_MAXPOOL || L.op == ECLIP_OP_GAP || L.op == ECLIP_OP_SOFTMAX || L.op == ECLIP_OP_ATTENTION || L.op == ECLIP_OP_EMBED)
+        if (L.in1 != -2 && L.op != ECLIP_OP_CONCAT) {
+            if (L.op == ECLIP_OP_SHUFFLE || L.op == ECLIP_OP_MAXPOOL || L.op == ECLIP_OP_GAP || L.op == ECLIP_OP_SOFTMAX || L.op == ECLIP_OP_ATTENTION || L.op == ECLIP_OP_EMBED)
                 return fail(ECLIP_EINVAL, "layer %u: this op takes no second input", i);
             if (L.in1 == -1 && d->in_kind == ECLIP_IN_TOKENS) return fail(ECLIP_EINVAL, "layer %u: token ids cannot be a residual", i);
             const Dims r = L.in1 == -1 ? in_dims : m->layers[L.in1].out;
@@ -538,8 +555,18 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
             int kh = L.kh, kw = L.kw;
             const int cin_l = P.in_c_logical, cin_s = P.in.c;
             if (L.op == ECLIP_OP_LINEAR) { kh = (P.in.kind == ECLIP_KIND_IMAGE) ? P.in.h : 1; kw = (P.in.kind == ECLIP_KIND_IMAGE) ? P.in.w : 1; }
-            const bool dw = L.op == ECLIP_OP_CONV && L.groups > 1;
+            const bool dw = L.op == ECLIP_OP_CONV && L.groups > 1 && L.groups == cin_l && L.c == L.groups;
+            const bool grouped = L.op == ECLIP_OP_CONV && L.groups > 1 && !dw;
             const E *src = w + L.w_off;
+            if (grouped) {                              // [cout][cig][kh][kw] -> [cout][kh][kw][cig]
+                const int cig = cin_l / L.groups;
+                std::vector<E> t((size_t)L.c * kh * kw * cig);
+                for (int co = 0; co < L.c; ++co)
+                    for (int ci = 0; ci < cig; ++ci)
+                        for (int i = 0; i < kh * kw; ++i)
+                            t[((size_t)co * kh * kw + i) * cig + ci] = src[((size_t)co * cig + ci) * kh * kw + i];
+                put(arena, cursor, t.data(), t.size() * es, &P.w_dev);
+            } else
             if (dw) {                                   // -> [kh][kw][c]
                 std::vector<E> t((size_t)kh * kw * L.c);
                 for (int c = 0; c < L.c; ++c)
@@ -799,6 +826,9 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
             out->k_splits = (uint32_t)pl.splits;
             out->workgroups = (uint32_t)pl.tiles * (uint32_t)pl.splits;
             out->launches = pl.splits > 1 ? 2 : 1;
+        } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1 && !(P.L.groups == P.in.c && P.L.c == P.L.groups)) {
+            name = "gconv_kernel";
+            out->workgroups = (uint32_t)((rows * P.L.c + 255) / 256);
         } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1) {
             DwConvArgs da{};
             da.B = (int)batch; da.C = P.L.c; da.Ho = P.L.h; da.Wo = P.L.w; da.KH = P.L.kh; da.KW = P.L.kw; da.stride = P.L.stride;
@@ -818,6 +848,8 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
     case ECLIP_OP_ATTENTION: name = "attention_kernel"; break;
     case ECLIP_OP_EMBED: name = "embed_kernel"; break;
     case ECLIP_OP_ELTWISE: name = "eltwise_kernel"; break;
+    case ECLIP_OP_CONCAT: name = "concat_kernel"; break;
+    case ECLIP_OP_SHUFFLE: name = "shuffle_kernel"; break;
     default: break;
     }
     snprintf(out->kernel, sizeof out->kernel, "%s", name);
@@ -860,6 +892,10 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
             const GemmPlan pl = conv_gemm_plan((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats);
             *n_launched -= 1;
             e = launch_conv_gemm(a, pl, s, n_launched);
+        } else if (L.op == ECLIP_OP_CONV && L.groups > 1 && !(L.groups == g.Cin && L.c == L.groups)) {
+            GConvArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y, g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout,
+                        g.KH, g.KW, g.stride, g.pad, L.groups, L.act, dt};
+            e = launch_gconv(a, n_cu, s);
         } else if (L.op == ECLIP_OP_CONV && L.groups > 1) {
             DwConvArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y, g.B, g.H, g.W, L.c, g.Ho, g.Wo, g.KH, g.KW, g.stride, g.pad, L.act, dt};
             e = launch_dwconv(a, n_cu, s);
@@ -906,6 +942,12 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
         e = launch_eltwise(a, n_cu, s);
         break;
     }
+    case ECLIP_OP_CONCAT:
+        e = launch_concat(src(L.in0), src(L.in1), y, rows, P.in.c, L.c - P.in.c, dt, s);
+        break;
+    case ECLIP_OP_SHUFFLE:
+        e = launch_shuffle(src(L.in0), y, rows, L.c, L.groups, dt, s);
+        break;
     default:
         e = hipErrorInvalidValue;
     }

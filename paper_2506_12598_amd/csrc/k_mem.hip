@@ -212,6 +212,69 @@ __global__ __launch_bounds__(256) void dwconv3_row_kernel(DwConvArgs a, unsigned
     }
 }
 
+// ---------------- grouped convolution, channel concatenation, channel shuffle ------------------------------
+// (the operators of the second workload family: ResNeXt-, DenseNet- and ShuffleNet-style blocks)
+// One thread per output element; the Cin/groups input channels of a tap are contiguous in x and in w, read V at a time.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void gconv_kernel(GConvArgs a, unsigned total)
+{
+    const unsigned ui = blockIdx.x * blockDim.x + threadIdx.x;
+    if (ui >= total) return;
+    const int co = (int)(ui % (unsigned)a.Cout);
+    const unsigned m = ui / (unsigned)a.Cout;
+    const int ow = (int)(m % (unsigned)a.Wo);
+    const unsigned mh = m / (unsigned)a.Wo;
+    const int oh = (int)(mh % (unsigned)a.Ho), b = (int)(mh / (unsigned)a.Ho);
+    const int cig = a.Cin / a.groups, g = co / (a.Cout / a.groups);
+    const T *x = (const T *)a.x, *w = (const T *)a.w + (long)co * a.KH * a.KW * cig;
+    float acc = a.bias ? Cvt<T>::load((const T *)a.bias + co) : 0.0f;
+    for (int kh = 0; kh < a.KH; ++kh) {
+        const int ih = oh * a.stride - a.pad + kh;
+        if ((unsigned)ih >= (unsigned)a.H) continue;
+        for (int kw = 0; kw < a.KW; ++kw) {
+            const int iw = ow * a.stride - a.pad + kw;
+            if ((unsigned)iw >= (unsigned)a.W) continue;
+            const T *xp = x + (((long)b * a.H + ih) * a.W + iw) * a.Cin + g * cig;
+            const T *wp = w + (kh * a.KW + kw) * cig;
+            for (int ci = 0; ci < cig; ci += V) {
+                float xv[V], wv[V];
+                Pack<T, V>::load(xp + ci, xv);
+                Pack<T, V>::load(wp + ci, wv);
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc = fmaf(xv[i], wv[i], acc);
+            }
+        }
+    }
+    const long off = (long)m * a.Cout + co;
+    if (a.res) acc += Cvt<T>::load((const T *)a.res + off);
+    Cvt<T>::store((T *)a.y + off, apply_act(a.act, acc));
+}
+
+// one thread per V consecutive output channels; c0 and c1 are multiples of V
+template <typename T, int V>
+__global__ __launch_bounds__(256) void concat_kernel(const T *a, const T *b, T *y, int c0, int c1, long total)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const unsigned cv = (unsigned)(c0 + c1) / V, ui = (unsigned)idx;
+    const int c = (int)(ui % cv) * V;
+    const long m = ui / cv;
+    float v[V];
+    if (c < c0) Pack<T, V>::load(a + m * c0 + c, v);
+    else Pack<T, V>::load(b + m * c1 + (c - c0), v);
+    Pack<T, V>::store(y + m * (c0 + c1) + c, v);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void shuffle_kernel(const T *x, T *y, int c, int groups, long total)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const unsigned ui = (unsigned)idx, j = ui % (unsigned)c;
+    const long m = ui / (unsigned)c;
+    y[idx] = x[m * c + (j % (unsigned)groups) * (unsigned)(c / groups) + j / (unsigned)groups];
+}
+
 // ---------------- max pooling ---------------------------------------------------------------------------
 // Window coordinates are clamped into the image instead of skipped: a clamped tap re-reads a pixel that is
 // already inside the window (2*pad <= window is checked at load), so the maximum is unchanged and the loads
@@ -577,6 +640,48 @@ hipError_t launch_maxpool(const PoolArgs &a, int, hipStream_t s)
     }
     ECLIP_DISPATCH(a.dtype, a.C, CALL);
 #undef CALL
+    return hipGetLastError();
+}
+
+hipError_t launch_gconv(const GConvArgs &a, int, hipStream_t s)
+{
+    const long total = (long)a.B * a.Ho * a.Wo * a.Cout;
+    if (total >= (1L << 31)) return hipErrorInvalidValue;
+    const int cig = a.Cin / a.groups;
+    const dim3 grid(blocks_for(total, 256));
+#define G(T)                                                                                               \
+    if (cig % 8 == 0) hipLaunchKernelGGL((gconv_kernel<T, 8>), grid, dim3(256), 0, s, a, (unsigned)total);      \
+    else if (cig % 4 == 0) hipLaunchKernelGGL((gconv_kernel<T, 4>), grid, dim3(256), 0, s, a, (unsigned)total); \
+    else hipLaunchKernelGGL((gconv_kernel<T, 1>), grid, dim3(256), 0, s, a, (unsigned)total);
+    if (a.dtype == DT_BF16) { G(bf16_t) } else if (a.dtype == DT_F16) { G(f16_t) } else return hipErrorInvalidValue;
+#undef G
+    return hipGetLastError();
+}
+
+hipError_t launch_concat(const void *a, const void *b, void *y, long rows, int c0, int c1, int dtype, hipStream_t s)
+{
+    if (rows * (c0 + c1) >= (1L << 31)) return hipErrorInvalidValue;
+    const int unit = dtype == DT_F32 ? 4 : 8;
+    const bool vec = c0 % unit == 0 && c1 % unit == 0;
+#define CC(T, V)                                                                                                       \
+    {                                                                                                                  \
+        const long total = rows * ((c0 + c1) / V);                                                                     \
+        hipLaunchKernelGGL((concat_kernel<T, V>), dim3(blocks_for(total, 256)), dim3(256), 0, s, (const T *)a, (const T *)b, (T *)y, c0, c1, total); \
+    }
+    if (dtype == DT_F32) { if (vec) CC(float, 4) else CC(float, 1) }
+    else if (dtype == DT_BF16) { if (vec) CC(bf16_t, 8) else CC(bf16_t, 1) }
+    else { if (vec) CC(f16_t, 8) else CC(f16_t, 1) }
+#undef CC
+    return hipGetLastError();
+}
+
+hipError_t launch_shuffle(const void *x, void *y, long rows, int c, int groups, int dtype, hipStream_t s)
+{
+    const long total = rows * c;
+    if (total >= (1L << 31)) return hipErrorInvalidValue;
+    const dim3 grid(blocks_for(total, 256));
+    if (dtype == DT_F32) hipLaunchKernelGGL((shuffle_kernel<uint32_t>), grid, dim3(256), 0, s, (const uint32_t *)x, (uint32_t *)y, c, groups, total);
+    else hipLaunchKernelGGL((shuffle_kernel<uint16_t>), grid, dim3(256), 0, s, (const uint16_t *)x, (uint16_t *)y, c, groups, total);
     return hipGetLastError();
 }
 

@@ -62,6 +62,18 @@ struct DwConvArgs {
 int dwconv_pixels_per_thread(const DwConvArgs &a, int n_cu);   // 4 (large 3x3 layers, 16-bit types) or 1
 hipError_t launch_dwconv(const DwConvArgs &a, int n_cu, hipStream_t s);
 
+// grouped convolution, 1 < groups < C: one thread per output element, weights [Cout][KH][KW][Cin/groups]
+struct GConvArgs {
+    const void *x, *w, *bias, *res;
+    void *y;
+    int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, groups, act, dtype;
+};
+hipError_t launch_gconv(const GConvArgs &a, int n_cu, hipStream_t s);
+// y[m][0 .. c0) = a[m][:], y[m][c0 .. c0 + c1) = b[m][:]
+hipError_t launch_concat(const void *a, const void *b, void *y, long rows, int c0, int c1, int dtype, hipStream_t s);
+// y[m][j] = x[m][(j % groups) * (c / groups) + j / groups]
+hipError_t launch_shuffle(const void *x, void *y, long rows, int c, int groups, int dtype, hipStream_t s);
+
 struct PoolArgs {
     const void *x; void *y;
     int B, H, W, C, Ho, Wo, KH, KW, stride, pad, dtype;

@@ -56,3 +56,18 @@ def test_config5_bert_large_seq384_batch4_bf16_six_layers():
     # every kernel runs at its full shape (M = 1536) and the oracle needs a quarter of the 16 s of the full stack
     m = wl.bert(6, 1024, 16, 4096, 384, seed=9, dtype=wl.DT_BF16)
     full_check(m, 4, [3, 5])
+
+
+def test_second_family_resnext50_and_shufflenet_full_size():
+    rx, sh = wl.config_models(6)
+    assert sum(1 for L in rx.layers if L.op == wl.OP_CONV and 1 < L.groups < L.c) == 16       # grouped 3x3 convolutions
+    assert sum(1 for L in sh.layers if L.op == wl.OP_SHUFFLE) == 16
+    full_check(rx, 1, [3, 2, 4, 1])
+    full_check(sh, 1, [1, 3, 5])
+
+
+def test_second_family_albert_base_and_densenet121_full_size():
+    al, dn = wl.config_models(5)
+    assert sum(1 for L in dn.layers if L.op == wl.OP_CONCAT) == 58 and dn.n_groups == 4
+    full_check(al, 1, [2, 5, 3, 0])
+    full_check(dn, 1, [4, 2, 5, 3])

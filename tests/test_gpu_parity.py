@@ -264,3 +264,49 @@ def test_every_gemm_variant_forced(force):
         check(m, batch=1, tol=2e-4)
     finally:
         os.environ.pop("ECLIP_GEMM_FORCE", None)
+
+
+# ---------------- second workload family (ResNeXt-, DenseNet-, ShuffleNet-, ALBERT-style) -------------------------
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("cin,cout,groups,k,s,res", [(32, 32, 8, 3, 1, True), (64, 128, 8, 3, 2, False), (128, 128, 32, 3, 1, False),
+                                                     (48, 96, 3, 1, 1, False), (64, 64, 2, 3, 1, True)])
+def test_grouped_conv(cin, cout, groups, k, s, res, dt):
+    m = wl.single_layer("conv", dt, seed=cin + groups, cin=cin, cout=cout, h=13, w=11, k=k, stride=s, pad=k // 2, groups=groups,
+                        act=wl.ACT_RELU, bias_std=0.5, residual=res)
+    check(m, batch=2, tol=4e-3 if not res else 8e-3)
+
+
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+@pytest.mark.parametrize("c0,c1", [(64, 64), (24, 40), (24, 18)])
+def test_concat(c0, c1, dt):
+    m = wl.single_layer("concat", dt, seed=c0, rows=37, c0=c0, c1=c1)
+    x = wl.make_input(m, 2)
+    outs = orc.run_model(m, x, keep_all=True)
+    got = run_gpu(m, x)
+    # the first operand is copied bit for bit; the second went through one more layer
+    assert np.array_equal(got[..., :c0], x.astype(np.float64))
+    assert np.abs(got[..., c0:] - outs[0]).max() <= (1e-5 if dt == wl.DT_F32 else 2e-2)
+
+
+@pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
+@pytest.mark.parametrize("c,groups", [(24, 3), (64, 8), (30, 5)])
+def test_channel_shuffle_is_exact(c, groups, dt):
+    m = wl.single_layer("shuffle", dt, seed=c, c=c, h=5, w=7, groups=groups)
+    x = wl.make_input(m, 3)
+    assert np.array_equal(run_gpu(m, x), orc.run_model(m, x))
+
+
+def test_resnext_style_small():
+    check(wl.resnext(reps=(2, 1, 1), groups=8, width_per_group=4, hw=64, n_classes=100, res_scale=0.5), batch=2)
+
+
+def test_densenet_style_small():
+    check(wl.densenet(blocks=(2, 4, 2), growth=16, hw=64, n_classes=100), batch=2)
+
+
+def test_shufflenet_style_small():
+    check(wl.shufflenet(groups=4, reps=(2, 2), base=128, hw=64, n_classes=100), batch=2)
+
+
+def test_albert_style_small():
+    check(wl.albert(n_layers=4, hidden=256, heads=4, ffn=512, seq=64, vocab=1000, embed=64), batch=2)

@@ -320,3 +320,55 @@ def test_storage_rounded_mode_only_adds_rounding():
     assert np.array_equal(stored[0], wl.round_to_dtype(exact[0].astype(np.float32), wl.DT_BF16))
     assert np.abs(stored[-1] - exact[-1]).max() <= 2e-2 * (exact[-1].max() - exact[-1].min())
     assert not np.array_equal(stored[-1], exact[-1])
+
+
+# ---------------- second workload family: grouped convolution, concatenation, channel shuffle ----------------
+def test_grouped_conv_equals_block_diagonal_dense_conv():
+    """A grouped convolution is a dense one whose weight is zero outside the diagonal blocks: pins the group
+    indexing of the routine against its own dense path."""
+    rng = np.random.default_rng(5)
+    g, cig, cog = 4, 3, 2
+    x = rng.standard_normal((2, g * cig, 6, 7))
+    w = rng.standard_normal((g * cog, cig, 3, 3))
+    dense = np.zeros((g * cog, g * cig, 3, 3))
+    for k in range(g):
+        dense[k * cog:(k + 1) * cog, k * cig:(k + 1) * cig] = w[k * cog:(k + 1) * cog]
+    a = orc.conv2d(x, w, None, 2, 1, g)
+    b = orc.conv2d(x, dense, None, 2, 1, 1)
+    assert np.allclose(a, b, rtol=0, atol=1e-12)
+
+
+def test_shuffle_is_the_index_permutation_and_inverts():
+    m = wl.single_layer("shuffle", wl.DT_F32, c=12, h=2, w=3, groups=3)
+    x = wl.make_input(m, 2)
+    y = orc.run_model(m, x)
+    n = 12 // 3
+    for j in range(12):                       # written out from the definition: out j <- in (j % g) * n + j // g
+        assert np.array_equal(y[:, j], x[:, (j % 3) * n + j // 3])
+    # shuffling with g and then with c / g is the identity
+    m2 = wl.single_layer("shuffle", wl.DT_F32, c=12, h=2, w=3, groups=4)
+    assert np.array_equal(orc.run_model(m2, y.astype(np.float32)), x)
+    # one group, or one channel per group, moves nothing
+    for g in (1, 12):
+        mi = wl.single_layer("shuffle", wl.DT_F32, c=12, h=2, w=3, groups=g)
+        assert np.array_equal(orc.run_model(mi, x), x)
+
+
+def test_concat_keeps_both_operands_in_order():
+    m = wl.single_layer("concat", wl.DT_F32, rows=5, c0=8, c1=8)
+    x = wl.make_input(m, 2)
+    outs = orc.run_model(m, x, keep_all=True)
+    assert outs[-1].shape == (2, 5, 16)
+    assert np.array_equal(outs[-1][..., :8], x) and np.array_equal(outs[-1][..., 8:], outs[0])
+
+
+def test_albert_layers_share_one_set_of_weights():
+    m = wl.albert(n_layers=3, hidden=64, heads=2, ffn=128, seq=8, vocab=50, embed=32)
+    lin = [L for L in m.layers if L.op == wl.OP_LINEAR][1:]              # skip the embedding projection
+    per_layer = [lin[i:i + 4] for i in range(0, len(lin), 4)]
+    assert len(per_layer) == 3
+    for layer in per_layer[1:]:
+        assert [L.w_off for L in layer] == [L.w_off for L in per_layer[0]]
+    # and the blob holds one encoder layer, not three
+    one = wl.albert(n_layers=1, hidden=64, heads=2, ffn=128, seq=8, vocab=50, embed=32)
+    assert m.weights.size == one.weights.size

@@ -21,6 +21,8 @@ Layer semantics (what a consumer has to compute), logical layouts:
              softmax(q k^T / sqrt(d)) v  -> [B,S,Hd]
   EMBED      x = int32 token ids [B,S]; y = tok[id] + pos[s] + typ[0]
   ELTWISE    y = act(x + b + in1)
+  CONCAT     y = [x | in1] along the channel axis
+  SHUFFLE    channel shuffle: channels viewed as (groups, c/groups), transposed, flattened
 
 The co-location configurations these stand in for are the paper's workload
 mixes (Sec. IV-A): a CNN classifier family and a transformer-encoder family,
@@ -35,7 +37,8 @@ from typing import List, Optional, Tuple
 import numpy as np
 
 # ---- enums shared (by value) with the C ABI ---------------------------------
-OP_CONV, OP_LINEAR, OP_MAXPOOL, OP_GAP, OP_LAYERNORM, OP_SOFTMAX, OP_ATTENTION, OP_EMBED, OP_ELTWISE = range(1, 10)
+OP_CONV, OP_LINEAR, OP_MAXPOOL, OP_GAP, OP_LAYERNORM, OP_SOFTMAX, OP_ATTENTION, OP_EMBED, OP_ELTWISE, OP_CONCAT, OP_SHUFFLE = \
+    range(1, 12)
 ACT_NONE, ACT_RELU, ACT_RELU6, ACT_GELU = range(4)
 DT_F32, DT_BF16, DT_F16 = range(3)
 KIND_IMAGE, KIND_SEQ, KIND_VEC = range(3)
@@ -43,7 +46,7 @@ IN_IMAGE, IN_TOKENS, IN_SEQ, IN_VEC = range(4)
 
 OP_NAMES = {OP_CONV: "conv", OP_LINEAR: "linear", OP_MAXPOOL: "maxpool", OP_GAP: "gap",
             OP_LAYERNORM: "layernorm", OP_SOFTMAX: "softmax", OP_ATTENTION: "attention",
-            OP_EMBED: "embed", OP_ELTWISE: "eltwise"}
+            OP_EMBED: "embed", OP_ELTWISE: "eltwise", OP_CONCAT: "concat", OP_SHUFFLE: "shuffle"}
 DT_NAMES = {DT_F32: "f32", DT_BF16: "bf16", DT_F16: "f16"}
 
 
@@ -241,6 +244,24 @@ class _Builder:
         b_off = self.normal((c,), bias_std) if bias_std > 0 else -1
         return self.add(Layer(OP_ELTWISE, x, res, kind, c, h, w, act=act, b_off=b_off))
 
+    def concat(self, x, x2):
+        kind, c, h, w = self.dims(x)
+        kind2, c2, h2, w2 = self.dims(x2)
+        assert (kind, h, w) == (kind2, h2, w2)
+        return self.add(Layer(OP_CONCAT, x, x2, kind, c + c2, h, w))
+
+    def shuffle(self, x, groups):
+        kind, c, h, w = self.dims(x)
+        assert c % groups == 0
+        return self.add(Layer(OP_SHUFFLE, x, -2, kind, c, h, w, groups=groups))
+
+    def linear_shared(self, x, n, w_off, b_off, act=ACT_NONE, res=-2):
+        """A linear layer on a sequence that reuses weights already in the blob (cross-layer sharing)."""
+        kind, c, h, w = self.dims(x)
+        assert kind == KIND_SEQ
+        self.flops += 2.0 * w * n * c
+        return self.add(Layer(OP_LINEAR, x, res, KIND_SEQ, n, 1, w, act=act, w_off=w_off, b_off=b_off))
+
     def next_group(self):
         self.cur_group += 1
 
@@ -358,6 +379,122 @@ def bert(n_layers=12, hidden=768, heads=12, ffn=3072, seq=128, vocab=30522, seed
     return b.finish()
 
 
+# ---- second workload family: analogues of the paper's remaining models (Sec. IV: albert, densenet201, resnext101,
+# ---- shufflenet), same conventions as above (normalisation folded, He-normal weights, zero bias) -----------------
+def albert(n_layers=12, hidden=768, heads=12, ffn=3072, seq=128, vocab=30000, embed=128, seed=21, dtype=DT_F16,
+           layers_per_group=3, std=0.02) -> Model:
+    """ALBERT-style encoder: factorised embedding (vocab x embed, then embed -> hidden) and ONE set of encoder
+    weights shared by all layers (every layer's descriptor points at the same offsets of the blob)."""
+    b = _Builder(f"albert_L{n_layers}_H{hidden}", dtype, seed, IN_TOKENS, embed, 1, seq)
+    x = b.embed(embed, vocab, max(seq, 512), std)
+    x = b.layernorm(x)
+    x = b.linear(x, hidden, std=std)
+    shared = None
+    for li in range(n_layers):
+        if li and li % layers_per_group == 0:
+            b.next_group()
+        if shared is None:
+            qkv = b.linear(x, 3 * hidden, std=std)
+            a = b.attention(qkv, heads)
+            o = b.linear(a, hidden, std=std)
+            h = b.layernorm(o, res=x)
+            f1 = b.linear(h, ffn, ACT_GELU, std=std)
+            f2 = b.linear(f1, hidden, std=std)
+            x = b.layernorm(f2, res=h)
+            shared = [(b.layers[i].w_off, b.layers[i].b_off) for i in (qkv, o, f1, f2)] + \
+                     [(b.layers[i].g_off, b.layers[i].be_off) for i in (h, x)]
+        else:
+            (wq, bq), (wo, bo), (w1, b1), (w2, b2), (g1, e1), (g2, e2) = shared
+            qkv = b.linear_shared(x, 3 * hidden, wq, bq)
+            a = b.attention(qkv, heads)
+            o = b.linear_shared(a, hidden, wo, bo)
+            h = b.add(Layer(OP_LAYERNORM, o, x, KIND_SEQ, hidden, 1, seq, g_off=g1, be_off=e1, eps=1e-12))
+            f1 = b.linear_shared(h, ffn, w1, b1, ACT_GELU)
+            f2 = b.linear_shared(f1, hidden, w2, b2)
+            x = b.add(Layer(OP_LAYERNORM, f2, h, KIND_SEQ, hidden, 1, seq, g_off=g2, be_off=e2, eps=1e-12))
+    return b.finish()
+
+
+def densenet(blocks=(6, 12, 24, 16), growth=32, seed=22, dtype=DT_BF16, hw=224, n_classes=1000, bottleneck=4) -> Model:
+    """DenseNet-style classifier: every dense layer is conv1x1 (bottleneck x growth) + conv3x3 (growth) whose output
+    is concatenated to its input; transitions halve channels (conv1x1) and resolution (2x2 max-pool standing in for
+    the average pool).  Kernel groups = the dense blocks."""
+    b = _Builder(f"densenet_{'_'.join(map(str, blocks))}", dtype, seed, IN_IMAGE, 3, hw, hw)
+    x = b.conv(-1, 2 * growth, 7, 2, 3, ACT_RELU)
+    x = b.maxpool(x, 3, 2, 1)
+    c = 2 * growth
+    for bi, n in enumerate(blocks):
+        if bi:
+            b.next_group()
+        for _ in range(n):
+            y = b.conv(x, bottleneck * growth, 1, 1, 0, ACT_RELU)
+            y = b.conv(y, growth, 3, 1, 1, ACT_RELU)
+            x = b.concat(x, y)
+            c += growth
+        if bi + 1 < len(blocks):
+            c //= 2
+            x = b.conv(x, c, 1, 1, 0, ACT_RELU)
+            x = b.maxpool(x, 2, 2, 0)
+    x = b.gap(x)
+    b.linear(x, n_classes)
+    return b.finish()
+
+
+def resnext(reps=(3, 4, 6, 3), groups=32, width_per_group=4, seed=23, dtype=DT_BF16, hw=224, n_classes=1000,
+            res_scale=1.0) -> Model:
+    """ResNeXt-style classifier: ResNet bottlenecks whose 3x3 convolution is grouped (`groups` groups of
+    `width_per_group` x 2^stage channels).  Kernel groups = the four stages."""
+    b = _Builder(f"resnext_{groups}x{width_per_group}d", dtype, seed, IN_IMAGE, 3, hw, hw)
+    x = b.conv(-1, 64, 7, 2, 3, ACT_RELU)
+    x = b.maxpool(x, 3, 2, 1)
+    cin = 64
+    for stage, n in enumerate(reps):
+        if stage:
+            b.next_group()
+        inner = groups * width_per_group << stage
+        cout = 256 << stage
+        for i in range(n):
+            s = 2 if (stage > 0 and i == 0) else 1
+            sc = x
+            if s != 1 or cin != cout:
+                sc = b.conv(x, cout, 1, s, 0, ACT_NONE)
+            y = b.conv(x, inner, 1, 1, 0, ACT_RELU)
+            y = b.conv(y, inner, 3, s, 1, ACT_RELU, groups=groups)
+            x = b.conv(y, cout, 1, 1, 0, ACT_RELU, res=sc, w_scale=res_scale)
+            cin = cout
+    x = b.gap(x)
+    b.linear(x, n_classes)
+    return b.finish()
+
+
+def shufflenet(groups=8, reps=(4, 8, 4), base=384, seed=24, dtype=DT_BF16, hw=224, n_classes=1000, res_scale=0.5) -> Model:
+    """ShuffleNet-style classifier (v1 units): grouped 1x1 -> channel shuffle -> depthwise 3x3 -> grouped 1x1,
+    added to the input (stride 1) or to a strided 1x1 projection of it (stride 2, standing in for the pooled
+    concatenation); the last convolution of every unit is scaled by `res_scale` to keep the un-normalised residual
+    stream bounded.  Channel counts are multiples of 8 x groups.  Kernel groups = the three stages."""
+    b = _Builder(f"shufflenet_g{groups}", dtype, seed, IN_IMAGE, 3, hw, hw)
+    x = b.conv(-1, 24, 3, 2, 1, ACT_RELU)
+    x = b.maxpool(x, 3, 2, 1)
+    cin = 24
+    for stage, n in enumerate(reps):
+        if stage:
+            b.next_group()
+        cout = base << stage
+        mid = cout // 4
+        for i in range(n):
+            s = 2 if i == 0 else 1
+            g1 = 1 if cin % groups else groups          # the 24-channel stem output is not divisible: dense 1x1 there
+            sc = x if (s == 1 and cin == cout) else b.conv(x, cout, 1, s, 0, ACT_NONE)
+            y = b.conv(x, mid, 1, 1, 0, ACT_RELU, groups=g1)
+            y = b.shuffle(y, groups)
+            y = b.conv(y, mid, 3, s, 1, ACT_NONE, groups=mid)
+            x = b.conv(y, cout, 1, 1, 0, ACT_RELU, res=sc, groups=groups, w_scale=res_scale)
+            cin = cout
+    x = b.gap(x)
+    b.linear(x, n_classes)
+    return b.finish()
+
+
 def single_layer(op: str, dtype=DT_BF16, seed=0, **kw) -> Model:
     """A one- or two-layer model used to test each kernel through the same entry points."""
     if op == "conv":
@@ -399,6 +536,17 @@ def single_layer(op: str, dtype=DT_BF16, seed=0, **kw) -> Model:
         b = _Builder("eltwise", dtype, seed, IN_SEQ, kw["width"], 1, kw["rows"])
         res = -1 if kw.get("residual") else -2
         b.eltwise(-1, kw.get("act", ACT_NONE), res=res, bias_std=kw.get("bias_std", 0.0))
+    elif op == "concat":
+        # a sequence input concatenated with an element-wise copy of itself plus a bias (two distinct operands)
+        b = _Builder("concat", dtype, seed, IN_SEQ, kw["c0"], 1, kw["rows"])
+        if kw["c1"] == kw["c0"]:
+            other = b.eltwise(-1, ACT_NONE, bias_std=1.0)
+        else:
+            other = b.linear(-1, kw["c1"], std=0.1, bias_std=0.5)
+        b.concat(-1, other)
+    elif op == "shuffle":
+        b = _Builder("shuffle", dtype, seed, IN_IMAGE, kw["c"], kw["h"], kw["w"])
+        b.shuffle(-1, kw["groups"])
     else:
         raise ValueError(op)
     return b.finish()
@@ -453,4 +601,14 @@ def config_models(cfg: int, small: bool = False) -> List[Model]:
                    [resnet(152, seed=12, hw=64, res_scale=0.25)]
         return [bert(24, 1024, 16, 4096, 384, seed=9 + i, dtype=DT_BF16) for i in range(3)] + \
                [resnet(152, seed=12, res_scale=0.25)]
+    # second workload family: analogues of two of the paper's mixes (Sec. IV: Mix 2 = albert + densenet201,
+    # Mix 5 = resnext101 + shufflenet), at the public depths of the smaller members of each family
+    if cfg == 5:
+        if small:
+            return [albert(2, 128, 4, 512, 48, vocab=1000, embed=64, seed=21), densenet((2, 4, 2), 16, seed=22, hw=64)]
+        return [albert(seed=21), densenet(seed=22)]
+    if cfg == 6:
+        if small:
+            return [resnext((2, 1, 1), 8, 4, seed=23, hw=64, res_scale=0.5), shufflenet(4, (2, 2), 128, seed=24, hw=64)]
+        return [resnext(seed=23, res_scale=0.5), shufflenet(seed=24)]
     raise ValueError(cfg)
