@@ -164,8 +164,29 @@ def load_expect(model, status, text=None, **kw):
 
 def test_valid_descriptors_pass_validation_and_stop_at_the_null_pool():
     for m in [wl.tiny_cnn(), wl.resnet(18, hw=64), wl.resnet(50, hw=64), wl.vgg16(hw=32, width=16, fc=64),
-              wl.mobilenetv2(hw=64), wl.bert(2, 128, 4, 512, 48, vocab=1000)]:
+              wl.mobilenetv2(hw=64), wl.bert(2, 128, 4, 512, 48, vocab=1000)] + wl.config_models(5, small=True) + \
+            wl.config_models(6, small=True):
         load_expect(m, ec.EINVAL, "pool is null")
+
+
+def test_descriptor_errors_of_the_second_workload_family():
+    m = wl.config_models(5, small=True)[1]                       # DenseNet-style
+    i = next(k for k, L in enumerate(m.layers) if L.op == wl.OP_CONCAT)
+    m.layers[i].c += 8
+    load_expect(m, ec.EINVAL, "summed channel count")
+    m = wl.config_models(5, small=True)[1]
+    m.layers[i].in1 = -2
+    load_expect(m, ec.EINVAL, "two inputs")
+    m = wl.config_models(6, small=True)[1]                       # ShuffleNet-style
+    i = next(k for k, L in enumerate(m.layers) if L.op == wl.OP_SHUFFLE)
+    m.layers[i].groups = 7
+    load_expect(m, ec.EINVAL, "SHUFFLE groups")
+    m = wl.config_models(6, small=True)[0]                       # ResNeXt-style
+    i = next(k for k, L in enumerate(m.layers) if L.op == wl.OP_CONV and 1 < L.groups < L.c)
+    m.layers[i].groups = 5
+    load_expect(m, ec.EINVAL, "groups must divide")
+    m = wl.single_layer("conv", wl.DT_F32, cin=16, cout=16, h=8, w=8, k=3, pad=1, groups=4)
+    load_expect(m, ec.EINVAL, "16-bit model")
 
 
 def test_descriptor_errors():
