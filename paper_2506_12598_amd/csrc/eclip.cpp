@@ -290,6 +290,7 @@ struct LayerPlan {
     size_t out_off = 0;        // byte offset of this layer's output in the activation arena
     size_t w_dev = NONE, b_dev = NONE, g_dev = NONE, be_dev = NONE;   // byte offsets in the device weight arena
     bool gemm = false;         // runs on the matrix-core GEMM kernel
+    bool pair_next = false;    // this layer and the next are independent GEMM layers of one group: one launch may carry both
 };
 
 struct eclip_req {
@@ -529,6 +530,14 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
         }
         if ((size_t)out.c * out.h * out.w * d->max_batch >= ((size_t)1 << 30)) return fail(ECLIP_ELIMIT, "layer %u: tensor of 2^30 elements or more", i);
         P.out = out;
+    }
+    // Horizontal fusion candidates: consecutive matrix-core layers of one kernel group, the second not reading the
+    // first (e.g. the projection shortcut and the first convolution of a residual block), neither being the last
+    // layer (whose output goes to the caller).
+    for (uint32_t i = 0; i + 2 < d->n_layers; ++i) {
+        LayerPlan &A = m->layers[i];
+        const LayerPlan &B = m->layers[i + 1];
+        A.pair_next = A.gemm && B.gemm && d->group_of_layer[i] == d->group_of_layer[i + 1] && B.L.in0 != (int)i && B.L.in1 != (int)i;
     }
     return ECLIP_OK;
 }
@@ -958,6 +967,33 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
     return launch_to_f32(y, d_out32, rows * P.out.c, dt, s);
 }
 
+// Launches layers i and i + 1 (pair_next) in one kernel when the planner finds a common plan; *done tells whether it did.
+static hipError_t launch_pair(eclip_model *m, uint32_t i, int batch, hipStream_t s, int n_cu, const void *d_in, uint32_t *n_launched, bool *done)
+{
+    *done = false;
+    ConvGemmArgs a[2];
+    GemmPlan own[2], pl[2];
+    long mnk[2][3];
+    for (int k = 0; k < 2; ++k) {
+        const LayerPlan &P = m->layers[i + k];
+        const eclip_layer &L = P.L;
+        auto src = [&](int idx) -> const void * {
+            if (idx == -2) return nullptr;
+            if (idx == -1) return m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in;
+            return (const void *)(m->d_act + m->layers[idx].out_off);
+        };
+        const GemmShape g = gemm_shape(P, batch);
+        a[k] = ConvGemmArgs{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), m->d_act + P.out_off, nullptr, m->d_ws,
+                            g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, m->dtype};
+        mnk[k][0] = (long)g.B * g.Ho * g.Wo; mnk[k][1] = g.Cout; mnk[k][2] = (long)g.KH * g.KW * g.Cin;
+        own[k] = conv_gemm_plan(mnk[k][0], mnk[k][1], mnk[k][2], n_cu, m->ws_floats);
+    }
+    if (!conv_gemm_plan_pair(own[0], mnk[0][0], mnk[0][1], mnk[0][2], own[1], mnk[1][0], mnk[1][1], mnk[1][2], n_cu, &pl[0], &pl[1]))
+        return hipSuccess;
+    *done = true;
+    return launch_conv_gemm_pair(a[0], pl[0], a[1], pl[1], s, n_launched);
+}
+
 static hipError_t launch_input_stage(eclip_model *m, int batch, const void *d_in, hipStream_t s, uint32_t *n_launched)
 {
     if (m->in_kind != ECLIP_IN_IMAGE) return hipSuccess;
@@ -1001,6 +1037,11 @@ extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void 
             r->n_switches++;
         }
         prev_group = g;
+        if (model->layers[i].pair_next) {
+            bool paired = false;
+            HIP_TRY(launch_pair(model, i, (int)batch, cur, (int)ps.n_cu, d_in, &r->n_kernels, &paired));
+            if (paired) { ++i; continue; }
+        }
         HIP_TRY(launch_layer(model, i, (int)batch, cur, (int)ps.n_cu, d_in, i + 1 == n_layers ? (float *)d_out : nullptr, &r->n_kernels));
     }
     HIP_TRY(hipEventRecord(r->done, cur));

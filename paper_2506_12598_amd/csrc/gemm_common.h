@@ -105,5 +105,7 @@ __device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint
 
 // wave-split-K kernel (k_wsk.hip)
 hipError_t launch_conv_wsk(const GemmDev &d, int dtype, int variant, int nw, int tiles, hipStream_t s);
+// two independent layers of the same tile shape and wavefront count in one launch
+hipError_t launch_conv_wsk_pair(const GemmDev &d0, int tiles0, const GemmDev &d1, int tiles1, int dtype, int variant, int nw, hipStream_t s);
 
 }  // namespace eclip

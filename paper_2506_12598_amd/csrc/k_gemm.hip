@@ -512,6 +512,26 @@ static void set_xcd_split(GemmPlan &pl, long M, long N)
     }
 }
 
+// Cost of the wave-split-K kernel (us, without the launch), 1e30 when the combination does not exist.  A compute
+// unit pulls the im2col rows in MFMA fragment order (16 rows per instruction: slow) and the weights as contiguous
+// 1 KB blocks (fast); its workgroups run one after another; each wavefront needs ceil(steps / depth) round trips to
+// memory; the partial tiles of the nw wavefronts are summed through LDS.
+static double wsk_cost(long M, long N, long K, int n_cu, int v, int nw)
+{
+    const double ra = 3.312e4, rw = 6.383e5;         // bytes per us per CU: activation rows, weight blocks
+    const double lat = 0.0186, c_out = 3.23e-6, c_red = 6.78e-6, l2 = 4.362e8, c_wg = 0.0288;
+    if (conv_wsk_lds_bytes(v, nw) > 128 * 1024) return 1e30;
+    int bm, bn;
+    conv_wsk_tile(v, &bm, &bn);
+    const int depth = (bm + bn) <= 32 ? 8 : (bm + bn) <= 48 ? 6 : (bm + bn) <= 80 ? 4 : (bm + bn) <= 96 ? (nw == 16 ? 2 : 3) : 2;
+    const double t = (double)(cdiv(M, bm) * cdiv(N, bn));
+    const double per_cu = (double)cdiv((long)t, n_cu), frac = t / n_cu > 1.0 ? t / n_cu : 1.0;
+    const double a_b = (double)(M < bm ? M : bm) * K * 2.0, w_b = (double)(N < bn ? N : bn) * K * 2.0;
+    const double cu = per_cu * (a_b / ra + w_b / rw) + frac * c_wg + frac * bm * bn * (c_out + c_red * nw);
+    const double all = t * (a_b + w_b) / l2;
+    return (cu > all ? cu : all) + lat * (double)cdiv(cdiv(cdiv(K, 32), nw), depth);
+}
+
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
 {
     auto tiles = [&](int v) { int bm, bn, bk; conv_gemm_tile(v, &bm, &bn, &bk); return cdiv(M, bm) * cdiv(N, bn); };
@@ -546,30 +566,12 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     // ResNet-18/50/152, VGG-16, MobileNetV2 and BERT-base/large graphs at batch 1 to 8, on 256 and on 128 CUs (picks
     // within 3 % of the per-layer best of an exhaustive sweep, in total).  Times in microseconds, without the
     // launch cost that all single-launch candidates share.
-    //
-    // Wave-split-K, tile bm x bn, nw wavefronts.  A compute unit pulls the im2col rows in MFMA fragment order
-    // (16 rows per instruction: slow) and the weights as contiguous 1 KB blocks (fast); its workgroups run one
-    // after another; each wavefront needs ceil(steps / depth) round trips to memory; the partial tiles of the nw
-    // wavefronts are summed through LDS.
-    const double ra = 3.312e4, rw = 6.383e5;         // bytes per us per CU: activation rows, weight blocks
-    const double lat = 0.0186, c_out = 3.23e-6, c_red = 6.78e-6, l2 = 4.362e8, c_wg = 0.0288;
     double best = 1e30;
-    for (int v = 0; v < CONV_WSK_VARIANTS; ++v) {
-        int bm, bn;
-        conv_wsk_tile(v, &bm, &bn);
-        const int depth = (bm + bn) <= 32 ? 8 : (bm + bn) <= 48 ? 6 : (bm + bn) <= 80 ? 4 : (bm + bn) <= 96 ? 3 : 2;
+    for (int v = 0; v < CONV_WSK_VARIANTS; ++v)
         for (int nw = 4; nw <= 16; nw *= 2) {
-            if (conv_wsk_lds_bytes(v, nw) > 128 * 1024) continue;
-            const double t = (double)wsk_tiles(v);
-            const double per_cu = (double)cdiv((long)t, n_cu), frac = t / n_cu > 1.0 ? t / n_cu : 1.0;
-            const double a_b = (double)(M < bm ? M : bm) * K * 2.0, w_b = (double)(N < bn ? N : bn) * K * 2.0;
-            const double cu = per_cu * (a_b / ra + w_b / rw) + frac * c_wg + frac * bm * bn * (c_out + c_red * nw);
-            const double all = t * (a_b + w_b) / l2;
-            const int d = (bm + bn == 96 && nw == 16) ? 2 : depth;
-            const double cost = (cu > all ? cu : all) + lat * (double)cdiv(cdiv(cdiv(K, 32), nw), d);
-            if (cost < best) { best = cost; pl = GemmPlan{1, v, 1, (int)t, nw, 0}; }
+            const double cost = wsk_cost(M, N, K, n_cu, v, nw);
+            if (cost < best) { best = cost; pl = GemmPlan{1, v, 1, (int)wsk_tiles(v), nw, 0}; }
         }
-    }
     // LDS-tiled kernel, optionally with K cut in two (second launch: its cost plus the traffic of the partial sums).
     // A tile costs `shared` us per K step when workgroups share a compute unit and `alone` when it has one to itself.
     struct { int variant; double shared, alone, fixed; } lds[4] = {{0, 0.357, 5.31, 0.664}, {1, 0.268, 4.73, 0.664}, {3, 0.746, 0.746, 0.664},
@@ -596,7 +598,32 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     return pl;
 }
 
-hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream_t s, uint32_t *n_launched)
+// Two independent layers in one launch of the wave-split-K kernel: possible when both are planned on that kernel and
+// one (tile, wavefront count) serves both at a modelled extra cost below what the second launch would cost.
+bool conv_gemm_plan_pair(const GemmPlan &s0, long M0, long N0, long K0, const GemmPlan &s1, long M1, long N1, long K1, int n_cu,
+                         GemmPlan *p0, GemmPlan *p1)
+{
+    if (s0.kind != 1 || s1.kind != 1 || getenv("ECLIP_GEMM_FORCE") || getenv("ECLIP_NO_PAIRS")) return false;
+    const double separate = wsk_cost(M0, N0, K0, n_cu, s0.variant, s0.nw) + wsk_cost(M1, N1, K1, n_cu, s1.variant, s1.nw);
+    double best = 1e30;
+    int bv = -1, bnw = 0;
+    for (int v = 0; v < CONV_WSK_VARIANTS; ++v)
+        for (int nw = 4; nw <= 16; nw *= 2) {
+            const double c = wsk_cost(M0, N0, K0, n_cu, v, nw) + wsk_cost(M1, N1, K1, n_cu, v, nw);
+            if (c < best) { best = c; bv = v; bnw = nw; }
+        }
+    const double launch_us = 2.5;                    // what a kernel costs as one more link of an in-order chain
+    if (bv < 0 || best > separate + launch_us) return false;
+    int bm, bn;
+    conv_wsk_tile(bv, &bm, &bn);
+    *p0 = GemmPlan{1, bv, 1, (int)(cdiv(M0, bm) * cdiv(N0, bn)), bnw, 0};
+    *p1 = GemmPlan{1, bv, 1, (int)(cdiv(M1, bm) * cdiv(N1, bn)), bnw, 0};
+    set_xcd_split(*p0, M0, N0);
+    if (p0->tiles % 8 == 0) set_xcd_split(*p1, M1, N1);     // the second layer's workgroup b runs on XCD (tiles0 + b) % 8
+    return true;
+}
+
+static GemmDev make_dev(const ConvGemmArgs &a, const GemmPlan &pl)
 {
     GemmDev d;
     d.x = (const uint16_t *)a.x; d.w = (const uint16_t *)a.w; d.bias = (const uint16_t *)a.bias;
@@ -614,15 +641,29 @@ hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream
     d.tiles_m = (d.M + bm - 1) / bm;
     d.tiles_n = (d.N + bn - 1) / bn;
     d.raster = pl.raster;
-    if (n_launched) *n_launched += pl.splits > 1 ? 2 : 1;
     if (pl.kind == 1) {
         conv_wsk_tile(pl.variant, &bm, &bn);
         d.tiles_m = (d.M + bm - 1) / bm;
         d.tiles_n = (d.N + bn - 1) / bn;
-        return launch_conv_wsk(d, a.dtype, pl.variant, pl.nw, pl.tiles, s);
     }
+    return d;
+}
+
+hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream_t s, uint32_t *n_launched)
+{
+    const GemmDev d = make_dev(a, pl);
+    if (n_launched) *n_launched += pl.splits > 1 ? 2 : 1;
+    if (pl.kind == 1) return launch_conv_wsk(d, a.dtype, pl.variant, pl.nw, pl.tiles, s);
     if (a.dtype == DT_BF16) return launch_t<bf16_t>(d, pl, s);
     return launch_t<f16_t>(d, pl, s);
+}
+
+hipError_t launch_conv_gemm_pair(const ConvGemmArgs &a0, const GemmPlan &p0, const ConvGemmArgs &a1, const GemmPlan &p1, hipStream_t s,
+                                 uint32_t *n_launched)
+{
+    if (p0.kind != 1 || p1.kind != 1 || p0.variant != p1.variant || p0.nw != p1.nw || a0.dtype != a1.dtype) return hipErrorInvalidValue;
+    if (n_launched) *n_launched += 1;
+    return launch_conv_wsk_pair(make_dev(a0, p0), p0.tiles, make_dev(a1, p1), p1.tiles, a0.dtype, p0.variant, p0.nw, s);
 }
 
 }  // namespace eclip

@@ -19,8 +19,13 @@ namespace eclip {
 namespace {
 
 template <typename T, int TM, int TN, int NW, int D>
-__global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
+__global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p1, int n0)
 {
+    // One launch can carry two independent layers ("horizontal" fusion, e.g. the two convolutions that read a
+    // residual block's input): workgroups 0 .. n0-1 work on p0, the rest on p1.  A single layer passes n0 = grid.
+    const bool second = (int)blockIdx.x >= n0;
+    const GemmDev &p = second ? p1 : p0;
+    const int bid = (int)blockIdx.x - (second ? n0 : 0);
     extern __shared__ __attribute__((aligned(16))) float red[];    // [NW][TM*TN][64][4]
     constexpr int BM = TM * 16, BN = TN * 16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -29,18 +34,18 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p)
     // fetched from memory by one XCD only instead of by all eight.
     int tile_m, tile_n;
     if (p.raster == 2) {
-        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_n + 7) >> 3, r = q / p.tiles_m;
+        const int xcd = bid & 7, q = bid >> 3, per = (p.tiles_n + 7) >> 3, r = q / p.tiles_m;
         tile_m = q - r * p.tiles_m;
         tile_n = xcd * per + r;
         if (r >= per || tile_n >= p.tiles_n) return;
     } else if (p.raster == 3) {
-        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_m + 7) >> 3, r = q / p.tiles_n;
+        const int xcd = bid & 7, q = bid >> 3, per = (p.tiles_m + 7) >> 3, r = q / p.tiles_n;
         tile_n = q - r * p.tiles_n;
         tile_m = xcd * per + r;
         if (r >= per || tile_m >= p.tiles_m) return;
     } else {
-        tile_m = blockIdx.x % p.tiles_m;
-        tile_n = blockIdx.x / p.tiles_m;
+        tile_m = bid % p.tiles_m;
+        tile_n = bid / p.tiles_m;
     }
     const int m_base = tile_m * BM, n_base = tile_n * BN;
     const int row = lane & 15, g = lane >> 4;
@@ -200,16 +205,16 @@ template <int TM, int TN, int NW> struct Depth {
 };
 
 template <typename T, int TM, int TN>
-hipError_t launch_nw(const GemmDev &d, int nw, int tiles, hipStream_t s)
+hipError_t launch_nw(const GemmDev &d, const GemmDev &d1, int n0, int nw, int tiles, hipStream_t s)
 {
     const size_t lds = (size_t)nw * TM * TN * 64 * 16;
     if (lds > 128 * 1024) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles);
     switch (nw) {
-    case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4, Depth<TM, TN, 4>::value>), grid, dim3(256), lds, s, d); break;
-    case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8, Depth<TM, TN, 8>::value>), grid, dim3(512), lds, s, d); break;
+    case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4, Depth<TM, TN, 4>::value>), grid, dim3(256), lds, s, d, d1, n0); break;
+    case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8, Depth<TM, TN, 8>::value>), grid, dim3(512), lds, s, d, d1, n0); break;
     case 16:
-        if constexpr (TM * TN <= 8) hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16, Depth<TM, TN, 16>::value>), grid, dim3(1024), lds, s, d);
+        if constexpr (TM * TN <= 8) hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 16, Depth<TM, TN, 16>::value>), grid, dim3(1024), lds, s, d, d1, n0);
         else return hipErrorInvalidValue;        // 16 partial 64x64 tiles would not fit in LDS
         break;
     default: return hipErrorInvalidValue;
@@ -218,15 +223,15 @@ hipError_t launch_nw(const GemmDev &d, int nw, int tiles, hipStream_t s)
 }
 
 template <typename T>
-hipError_t launch_tile(const GemmDev &d, int variant, int nw, int tiles, hipStream_t s)
+hipError_t launch_tile(const GemmDev &d, const GemmDev &d1, int n0, int variant, int nw, int tiles, hipStream_t s)
 {
     switch (variant) {
-    case 0: return launch_nw<T, 1, 4>(d, nw, tiles, s);
-    case 1: return launch_nw<T, 2, 4>(d, nw, tiles, s);
-    case 2: return launch_nw<T, 4, 4>(d, nw, tiles, s);
-    case 3: return launch_nw<T, 1, 1>(d, nw, tiles, s);
-    case 4: return launch_nw<T, 1, 2>(d, nw, tiles, s);
-    case 5: return launch_nw<T, 2, 2>(d, nw, tiles, s);
+    case 0: return launch_nw<T, 1, 4>(d, d1, n0, nw, tiles, s);
+    case 1: return launch_nw<T, 2, 4>(d, d1, n0, nw, tiles, s);
+    case 2: return launch_nw<T, 4, 4>(d, d1, n0, nw, tiles, s);
+    case 3: return launch_nw<T, 1, 1>(d, d1, n0, nw, tiles, s);
+    case 4: return launch_nw<T, 1, 2>(d, d1, n0, nw, tiles, s);
+    case 5: return launch_nw<T, 2, 2>(d, d1, n0, nw, tiles, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -278,8 +283,14 @@ hipError_t conv_wsk_init()
 
 hipError_t launch_conv_wsk(const GemmDev &d, int dtype, int variant, int nw, int tiles, hipStream_t s)
 {
-    if (dtype == DT_BF16) return launch_tile<bf16_t>(d, variant, nw, tiles, s);
-    return launch_tile<f16_t>(d, variant, nw, tiles, s);
+    if (dtype == DT_BF16) return launch_tile<bf16_t>(d, d, tiles, variant, nw, tiles, s);
+    return launch_tile<f16_t>(d, d, tiles, variant, nw, tiles, s);
+}
+
+hipError_t launch_conv_wsk_pair(const GemmDev &d0, int tiles0, const GemmDev &d1, int tiles1, int dtype, int variant, int nw, hipStream_t s)
+{
+    if (dtype == DT_BF16) return launch_tile<bf16_t>(d0, d1, tiles0, variant, nw, tiles0 + tiles1, s);
+    return launch_tile<f16_t>(d0, d1, tiles0, variant, nw, tiles0 + tiles1, s);
 }
 
 }  // namespace eclip

@@ -42,6 +42,12 @@ hipError_t conv_wsk_init();    // raises the dynamic LDS limit of the wave-split
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats);
 // *n_launched (optional) is increased by the number of kernels launched (2 when K is split).
 hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &p, hipStream_t s, uint32_t *n_launched);
+// Two layers that do not depend on each other in one launch (wave-split-K kernel only).  conv_gemm_plan_pair takes
+// the layers' own plans and returns true, with a common plan for each, when sharing a launch is modelled to pay.
+bool conv_gemm_plan_pair(const GemmPlan &s0, long M0, long N0, long K0, const GemmPlan &s1, long M1, long N1, long K1, int n_cu,
+                         GemmPlan *p0, GemmPlan *p1);
+hipError_t launch_conv_gemm_pair(const ConvGemmArgs &a0, const GemmPlan &p0, const ConvGemmArgs &a1, const GemmPlan &p1, hipStream_t s,
+                                 uint32_t *n_launched);
 
 // ---- float32 direct convolution / linear (plain FMA) -------------------------------------------
 struct ConvF32Args {
