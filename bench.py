@@ -563,7 +563,7 @@ def main():
     ap.add_argument("--characterize", action="store_true", help="CU-mask geometry, switch cost and stream-count sweep")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; co-located models are independent workers and would be "
+        print("bench.py: this library runs on one GPU; co-located models are independent workers and would be "
               "placed on different GPUs without any exchange step. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 

@@ -1,6 +1,6 @@
 """GPU parity at the configurations' full sizes, through the same entry points and launch configuration the
 benchmark uses (batch, dtype, kernel groups on masked streams).  The oracle's whole forward pass is affordable at
-these sizes on the GPU machine's host cores (0.3 - 20 s each), so every output element is compared."""
+these sizes on the host cores (0.3 - 20 s each), so every output element is compared."""
 import numpy as np
 import pytest
 

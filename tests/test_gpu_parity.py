@@ -1,6 +1,6 @@
 """GPU parity: every kernel and every model, through the C ABI, element by element against the CPU oracle.
 
-Tolerances (stated by the build target): float32 configuration max-abs error <= 1e-4; bf16 / fp16
+Tolerances: float32 configuration max-abs error <= 1e-4; bf16 / fp16
 configurations max-abs error <= 2e-2 x (max - min of the oracle output).  Single kernels whose only
 rounding is float32 accumulation are held to a much tighter bound so that a dropped K-slice, a wrong tap
 or a transposed operand cannot hide inside the model-level tolerance.
