@@ -57,20 +57,6 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
     const uint16_t *kp = p.qkv + p.Hd + h * D;
     const uint16_t *vp = p.qkv + 2 * p.Hd + h * D;
 
-    // ---- V^T into LDS: thread loads 8 consecutive head dims of one key, scatters them to 8 rows
-    for (int c = tid; c < p.Sp * (D / 8); c += NW * 64) {
-        const int key = c / (D / 8), j0 = (c % (D / 8)) * 8;
-        uint4 q = make_uint4(0, 0, 0, 0);
-        if (key < p.S) q = *reinterpret_cast<const uint4 *>(vp + (row0 + key) * ld + j0);
-        const uint32_t w[4] = {q.x, q.y, q.z, q.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            vt[(j0 + 2 * i) * p.ldv + key] = (uint16_t)(w[i] & 0xffffu);
-            vt[(j0 + 2 * i + 1) * p.ldv + key] = (uint16_t)(w[i] >> 16);
-        }
-    }
-    __syncthreads();
-
     const int q_row = qb * NW * 16 + wave * 16 + (lane & 15);      // this lane's query
     const int g = lane >> 4;                                        // lane group: contraction chunk / key quad
     const bool q_ok = q_row < p.S;
@@ -83,6 +69,51 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
         if (q_ok) qf[ks] = *reinterpret_cast<const uint4 *>(qp + (row0 + q_row) * ld + ks * 32 + g * 8);
     }
 
+    // Short sequences: the K fragments too are fetched before the V^T fill, so that all global loads of the
+    // workgroup are in flight together (one memory round trip instead of three).
+    constexpr bool PREFETCH_K = KB <= 16;
+    uint4 kfr[PREFETCH_K ? KB : 1][D / 32];
+    if constexpr (PREFETCH_K) {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int ks = 0; ks < D / 32; ++ks) {
+                const int key = kb * 16 + (lane & 15);
+                kfr[kb][ks] = make_uint4(0, 0, 0, 0);
+                if (key < p.S) kfr[kb][ks] = *reinterpret_cast<const uint4 *>(kp + (row0 + key) * ld + ks * 32 + g * 8);
+            }
+    }
+
+    // ---- V^T into LDS.  A thread loads 8 consecutive head dims of 4 consecutive keys (four 16-byte loads), turns the
+    // 4 x 8 block in registers and writes, for each of the 8 head dims, its 4 keys as one 8-byte word; consecutive
+    // lanes take consecutive key quads, so every store instruction of a wavefront writes 512 contiguous bytes.
+    auto load_v = [&](int c, uint32_t (&w)[4][4]) {
+        const int kq = c % (p.Sp / 4), j0 = (c / (p.Sp / 4)) * 8, key0 = kq * 4;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            uint4 q = make_uint4(0, 0, 0, 0);
+            if (c < (p.Sp / 4) * (D / 8) && key0 + t < p.S) q = *reinterpret_cast<const uint4 *>(vp + (row0 + key0 + t) * ld + j0);
+            w[t][0] = q.x; w[t][1] = q.y; w[t][2] = q.z; w[t][3] = q.w;
+        }
+    };
+    auto store_vt = [&](int c, const uint32_t (&w)[4][4]) {
+        if (c >= (p.Sp / 4) * (D / 8)) return;
+        const int kq = c % (p.Sp / 4), j0 = (c / (p.Sp / 4)) * 8, key0 = kq * 4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint2 lo = make_uint2((w[0][i] & 0xffffu) | (w[1][i] << 16), (w[2][i] & 0xffffu) | (w[3][i] << 16));
+            const uint2 hi = make_uint2((w[0][i] >> 16) | (w[1][i] & 0xffff0000u), (w[2][i] >> 16) | (w[3][i] & 0xffff0000u));
+            *reinterpret_cast<uint2 *>(&vt[(j0 + 2 * i) * p.ldv + key0]) = lo;
+            *reinterpret_cast<uint2 *>(&vt[(j0 + 2 * i + 1) * p.ldv + key0]) = hi;
+        }
+    };
+    for (int c = tid; c < (p.Sp / 4) * (D / 8); c += NW * 64) {
+        uint32_t w[4][4];
+        load_v(c, w);
+        store_vt(c, w);
+    }
+    __syncthreads();
+
     // ---- scores
     f32x4 sc[KB];
     const int nkb = p.Sp / 16;
@@ -94,7 +125,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
 #pragma unroll
             for (int ks = 0; ks < D / 32; ++ks) {
                 uint4 kf = make_uint4(0, 0, 0, 0);
-                if (key < p.S) kf = *reinterpret_cast<const uint4 *>(kp + (row0 + key) * ld + ks * 32 + g * 8);
+                if constexpr (PREFETCH_K) kf = kfr[kb][ks];
+                else if (key < p.S) kf = *reinterpret_cast<const uint4 *>(kp + (row0 + key) * ld + ks * 32 + g * 8);
                 sc[kb] = MmaA<T>::run(kf, qf[ks], sc[kb]);
             }
         }
