@@ -32,9 +32,9 @@ template <> struct Mma<f16_t> {
 };
 
 // bias + residual + activation + store of 4 consecutive channels n..n+3 of output row m
-template <typename T>
+template <typename T, int ACT>
 __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32,
-                                               int M, int N, int act, int m, int n, f32x4 v, int nvalid = 4)
+                                               int M, int N, int m, int n, f32x4 v, int nvalid = 4)
 {
     if (m >= M || n >= N) return;
     const long off = (long)m * N + n;
@@ -51,7 +51,7 @@ __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint1
             o[2] += Cvt<T>::from_bits(q.y & 0xffffu); o[3] += Cvt<T>::from_bits(q.y >> 16);
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) o[r] = apply_act(act, o[r]);
+        for (int r = 0; r < 4; ++r) o[r] = apply_act_c<ACT>(o[r]);
         if (y32) {
             *reinterpret_cast<float4 *>(y32 + off) = make_float4(o[0], o[1], o[2], o[3]);
         } else {
@@ -67,7 +67,7 @@ __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint1
             float t = o[r];
             if (bias) t += Cvt<T>::from_bits(bias[n + r]);
             if (res) t += Cvt<T>::from_bits(res[off + r]);
-            t = apply_act(act, t);
+            t = apply_act_c<ACT>(t);
             if (y32) y32[off + r] = t;
             else y[off + r] = (uint16_t)Cvt<T>::to_bits(t);
         }
@@ -76,8 +76,8 @@ __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint1
 
 // The same for 8 consecutive channels n..n+7 of row m, with 16-byte accesses: requires N % 8 == 0, n % 8 == 0,
 // m < M and n < N (checked by the caller).  `o` holds the sums without bias.
-template <typename T>
-__device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N, int act,
+template <typename T, int ACT>
+__device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N,
                                                 int m, int n, float (&o)[8])
 {
     const long off = (long)m * N + n;
@@ -94,12 +94,30 @@ __device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint
         for (int e = 0; e < 8; ++e) o[e] += rv[e];
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = apply_act(act, o[e]);
+    for (int e = 0; e < 8; ++e) o[e] = apply_act_c<ACT>(o[e]);
     if (y32) {
         *reinterpret_cast<float4 *>(y32 + off) = make_float4(o[0], o[1], o[2], o[3]);
         *reinterpret_cast<float4 *>(y32 + off + 4) = make_float4(o[4], o[5], o[6], o[7]);
     } else {
         Pack<T, 8>::store(reinterpret_cast<T *>(y) + off, o);
+    }
+}
+
+// The same for any N: channels n..n+7 of row m that lie below N, one element at a time.
+template <typename T, int ACT>
+__device__ __forceinline__ void epilogue_store8_ragged(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N,
+                                                       int m, int n, const float (&o)[8])
+{
+    const long off = (long)m * N + n;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (n + e >= N) break;
+        float t = o[e];
+        if (bias) t += Cvt<T>::from_bits(bias[n + e]);
+        if (res) t += Cvt<T>::from_bits(res[off + e]);
+        t = apply_act_c<ACT>(t);
+        if (y32) y32[off + e] = t;
+        else y[off + e] = (uint16_t)Cvt<T>::to_bits(t);
     }
 }
 

@@ -34,25 +34,26 @@ namespace {
 // Epilogue of one workgroup tile: acc[i][j] is the 16x16 block (i, j) of the wavefront's sub-tile, lane l holding
 // output pixel (l & 15) and channels 4 (l >> 4) .. +3 of the block.  `smem` is the workgroup's LDS (the K loop is
 // done with it); z is the K slice.
-template <typename T, int BM, int BN, int WM, int WN, int TM, int TN>
+template <typename T, int BM, int BN, int WM, int WN, int TM, int TN, int ACT, bool N8>
 __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc)[TM][TN], uint16_t *smem, int m_base, int n_base, int z)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    // lane owns output pixel m0 + (lane & 15) and channels n0 + 4*(lane >> 4) .. +3 of each 16x16 block
-    const int m_l = m_base + wm * (BM / WM) + (lane & 15);
-    const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
 
-    if (p.splits == 1 && (p.N & 7) == 0 && TM % 2 == 0) {
+    if (p.splits == 1) {
         // Row-contiguous stores.  Straight out of the accumulators a store instruction would write 8 bytes to each
         // of 64 different rows (measured: 6.4 us for the 12.6 MB output of a 1536 x 4096 layer, 2 TB/s).  Instead
         // each wavefront passes its sub-tile through a private LDS buffer, 32 rows at a time, and writes 16 bytes
         // (8 channels) per lane along the rows: whole 128-byte lines, and the bias and residual reads get the same
         // shape.  The buffer is private to the wavefront, so after the one barrier that ends the K loop's use of
-        // LDS only the wavefront's own LDS counter is waited on.
+        // LDS only the wavefront's own LDS counter is waited on.  N8: N is a multiple of 8, so a lane's 8 channels
+        // are all inside the row and aligned; otherwise the (rare) ragged form stores them one by one from a loop
+        // that is not unrolled, to keep it out of the way.
+        static_assert(TM % 2 == 0, "32 rows per pass");
         constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
         constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass
         static_assert(32 % RPP == 0 || RPP > 32, "whole passes per 32 rows");
+        constexpr int PASSES = (32 + RPP - 1) / RPP;
         __syncthreads();
         float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
         const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
@@ -69,32 +70,32 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
             });
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): this wavefront's LDS writes have landed
-#pragma unroll
-            for (int ps = 0; ps < (32 + RPP - 1) / RPP; ++ps) {
+            auto pass = [&](int ps) {
                 const int rr = ps * RPP + rr0;
                 const int m = m_base + wm * (BM / WM) + h * 32 + rr;
                 if (rr < 32 && m < p.M && n < p.N) {
                     const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
                     const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
                     float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                    epilogue_store8<T>(p.bias, p.res, p.y, p.y32, p.N, p.act, m, n, o);
+                    if constexpr (N8) epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
+                    else epilogue_store8_ragged<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
                 }
+            };
+            if constexpr (N8) {
+#pragma unroll
+                for (int ps = 0; ps < PASSES; ++ps) pass(ps);
+            } else {
+#pragma unroll 1
+                for (int ps = 0; ps < PASSES; ++ps) pass(ps);
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_s_waitcnt(0xc07f);              // reads done before the next 32 rows overwrite the buffer
         });
         return;
     }
-    if (p.splits == 1) {
-        static_for<TM>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            static_for<TN>([&](auto jc) {
-                constexpr int j = decltype(jc)::value;
-                epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_l + i * 16, n_l + j * 16, acc[i][j]);
-            });
-        });
-        return;
-    }
+    // lane owns output pixel m0 + (lane & 15) and channels n0 + 4*(lane >> 4) .. +3 of each 16x16 block
+    const int m_l = m_base + wm * (BM / WM) + (lane & 15);
+    const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
     // split-K: this slice's partial sums go to ws[z][m][n]; a second kernel adds the slices.  (A single-kernel
     // form, in which the last slice to arrive at a per-tile counter does the sum, was measured and dropped:
     // across XCDs it needs either a device-scope fence, i.e. a write-back of the issuing XCD's whole L2 per
@@ -122,7 +123,17 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
 template <typename T, int BM, int BN, int WM, int WN, int TM, int TN>
 __device__ __forceinline__ void tile_epilogue(const GemmDev &p, f32x4 (&acc)[TM][TN], uint16_t *smem, int m_base, int n_base, int z)
 {
-    tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN>(p, acc, smem, m_base, n_base, z);
+    // the partial sums of a K slice take no activation
+    if (p.splits != 1) { tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN, ACT_NONE, true>(p, acc, smem, m_base, n_base, z); return; }
+    if ((p.N & 7) == 0) {
+#define EPI(A) tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN, A, true>(p, acc, smem, m_base, n_base, z)
+        ECLIP_ACT_SWITCH(p.act, EPI)
+#undef EPI
+    } else {
+#define EPI(A) tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN, A, false>(p, acc, smem, m_base, n_base, z)
+        ECLIP_ACT_SWITCH(p.act, EPI)
+#undef EPI
+    }
 }
 
 // K-loop schedules
@@ -420,7 +431,9 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
     } else {
         for (int z = 0; z < splits; ++z) s[0] += src[z * slice];
     }
-    epilogue_store<T>(bias, res, y, y32, M, N, act, m, n, s, vec ? 4 : 1);
+#define EPI(A) epilogue_store<T, A>(bias, res, y, y32, M, N, m, n, s, vec ? 4 : 1)
+    ECLIP_ACT_SWITCH(act, EPI)
+#undef EPI
 }
 
 struct Variant { int bm, bn, bk; };

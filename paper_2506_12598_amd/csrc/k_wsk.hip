@@ -18,6 +18,50 @@ namespace eclip {
 
 namespace {
 
+// Sum of the NW wavefronts' partial tiles (in LDS, block (i, j) of wavefront w at red4[(w * TM * TN + i * TN + j) * 64 + lane])
+// with bias, residual and the activation ACT, written to the output.
+template <typename T, int TM, int TN, int NW, int ACT>
+__device__ __forceinline__ void wsk_finish(const GemmDev &p, const float4 *red4, int m_base, int n_base)
+{
+    constexpr int BM = TM * 16, BN = TN * 16;
+    const int tid = threadIdx.x;
+    if ((p.N & 7) == 0 && p.M * p.N >= (1 << 20)) {
+        // large outputs: one thread per (row, 8 consecutive channels): its two float4 of every partial tile sit 16
+        // lanes apart; stores are 16 bytes per lane along the rows instead of 8 bytes to each of 16 rows.  (Small
+        // outputs keep the form below: twice the threads share the summation, which matters more there.)
+        constexpr int C8 = BN / 8;
+        for (int t = tid; t < BM * C8; t += NW * 64) {
+            const int r = t / C8, c8 = t - r * C8;
+            const int blk = (r >> 4) * TN + (c8 >> 1), l0 = (c8 & 1) * 32 + (r & 15);
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float4 q0 = red4[(w * (TM * TN) + blk) * 64 + l0], q1 = red4[(w * (TM * TN) + blk) * 64 + l0 + 16];
+                s0[0] += q0.x; s0[1] += q0.y; s0[2] += q0.z; s0[3] += q0.w;
+                s1[0] += q1.x; s1[1] += q1.y; s1[2] += q1.z; s1[3] += q1.w;
+            }
+            const int m = m_base + r, n = n_base + c8 * 8;
+            if (m < p.M && n < p.N) {
+                float o[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
+                epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
+            }
+        }
+        return;
+    }
+    for (int slot = tid; slot < TM * TN * 64; slot += NW * 64) {
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float4 q = red4[w * (TM * TN * 64) + slot];
+            s[0] += q.x; s[1] += q.y; s[2] += q.z; s[3] += q.w;
+        }
+        const int blk = slot >> 6, l = slot & 63;
+        const int i = blk / TN, j = blk - i * TN;
+        // lane l of block (i, j) holds output pixel 16*i + (l & 15), channels 16*j + 4*(l >> 4) .. +3
+        epilogue_store<T, ACT>(p.bias, p.res, p.y, p.y32, p.M, p.N, m_base + i * 16 + (l & 15), n_base + j * 16 + (l >> 4) * 4, s);
+    }
+}
+
 template <typename T, int TM, int TN, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p1, int n0)
 {
@@ -161,41 +205,9 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p
         for (int j = 0; j < TN; ++j)
             red4[(wave * (TM * TN) + i * TN + j) * 64 + lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
     __syncthreads();
-    if ((p.N & 7) == 0 && p.M * p.N >= (1 << 20)) {
-        // large outputs: one thread per (row, 8 consecutive channels): its two float4 of every partial tile sit 16
-        // lanes apart; stores are 16 bytes per lane along the rows instead of 8 bytes to each of 16 rows.  (Small
-        // outputs keep the form below: twice the threads share the summation, which matters more there.)
-        constexpr int C8 = BN / 8;
-        for (int t = tid; t < BM * C8; t += NW * 64) {
-            const int r = t / C8, c8 = t - r * C8;
-            const int blk = (r >> 4) * TN + (c8 >> 1), l0 = (c8 & 1) * 32 + (r & 15);
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const float4 q0 = red4[(w * (TM * TN) + blk) * 64 + l0], q1 = red4[(w * (TM * TN) + blk) * 64 + l0 + 16];
-                s0[0] += q0.x; s0[1] += q0.y; s0[2] += q0.z; s0[3] += q0.w;
-                s1[0] += q1.x; s1[1] += q1.y; s1[2] += q1.z; s1[3] += q1.w;
-            }
-            const int m = m_base + r, n = n_base + c8 * 8;
-            if (m < p.M && n < p.N) {
-                float o[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
-                epilogue_store8<T>(p.bias, p.res, p.y, p.y32, p.N, p.act, m, n, o);
-            }
-        }
-        return;
-    }
-    for (int slot = tid; slot < TM * TN * 64; slot += NW * 64) {
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float4 q = red4[w * (TM * TN * 64) + slot];
-            s[0] += q.x; s[1] += q.y; s[2] += q.z; s[3] += q.w;
-        }
-        const int blk = slot >> 6, l = slot & 63;
-        const int i = blk / TN, j = blk - i * TN;
-        // lane l of block (i, j) holds output pixel 16*i + (l & 15), channels 16*j + 4*(l >> 4) .. +3
-        epilogue_store<T>(p.bias, p.res, p.y, p.y32, p.M, p.N, p.act, m_base + i * 16 + (l & 15), n_base + j * 16 + (l >> 4) * 4, s);
-    }
+#define FIN(A) wsk_finish<T, TM, TN, NW, A>(p, red4, m_base, n_base)
+    ECLIP_ACT_SWITCH(p.act, FIN)
+#undef FIN
 }
 
 // prefetch depth per tile shape: about 24 / (TM + TN) steps of 16-byte loads per lane
