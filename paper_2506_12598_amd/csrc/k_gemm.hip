@@ -526,23 +526,32 @@ static void set_xcd_split(GemmPlan &pl, long M, long N)
 }
 
 // Cost of the wave-split-K kernel (us, without the launch), 1e30 when the combination does not exist.  A compute
-// unit pulls the im2col rows in MFMA fragment order (16 rows per instruction: slow) and the weights as contiguous
-// 1 KB blocks (fast); its workgroups run one after another; each wavefront needs ceil(steps / depth) round trips to
-// memory; the partial tiles of the nw wavefronts are summed through LDS.
+// unit pulls the im2col rows as 64-byte runs (slow) and the weights as contiguous 1 KB blocks (fast), or is bound by
+// its matrix instructions when the tile is large; its workgroups run one after another; each wavefront needs
+// ceil(steps / depth) round trips to memory; the partial tiles of the nw wavefronts are summed through LDS.
 static double wsk_cost(long M, long N, long K, int n_cu, int v, int nw)
 {
-    const double ra = 3.312e4, rw = 6.383e5;         // bytes per us per CU: activation rows, weight blocks
-    const double lat = 0.0186, c_out = 3.23e-6, c_red = 6.78e-6, l2 = 4.362e8, c_wg = 0.0288;
+    const double ra = 2.676e4, rw = 4.635e5;         // bytes per us per CU: activation rows, weight blocks
+    const double rm = 1.539e6;                       // multiply-adds per us per CU with 8 or more wavefronts
+    const double lat = 0.04896, c_out = 3.14e-6, c_red = 1.248e-5, l2 = 9.238e7, c_wg = 0.02628;
     if (conv_wsk_lds_bytes(v, nw) > 128 * 1024) return 1e30;
     int bm, bn;
     conv_wsk_tile(v, &bm, &bn);
-    const int depth = (bm + bn) <= 32 ? 8 : (bm + bn) <= 48 ? 6 : (bm + bn) <= 80 ? 4 : (bm + bn) <= 96 ? (nw == 16 ? 2 : 3) : 2;
+    const int depth = (bm + bn) <= 32 ? 8 : (bm + bn) <= 48 ? 6 : (bm + bn) <= 80 ? (nw == 16 ? 3 : 4) : (bm + bn) <= 96 ? (nw == 16 ? 2 : 3) : 2;
     const double t = (double)(cdiv(M, bm) * cdiv(N, bn));
     const double per_cu = (double)cdiv((long)t, n_cu), frac = t / n_cu > 1.0 ? t / n_cu : 1.0;
     const double a_b = (double)(M < bm ? M : bm) * K * 2.0, w_b = (double)(N < bn ? N : bn) * K * 2.0;
-    const double cu = per_cu * (a_b / ra + w_b / rw) + frac * c_wg + frac * bm * bn * (c_out + c_red * nw);
+    const double loads = a_b / ra + w_b / rw;
+    const double macs = (double)(M < bm ? M : bm) * bn * K / rm / (nw < 8 ? nw / 8.0 : 1.0);
+    const double cu = per_cu * (loads > macs ? loads : macs) + frac * c_wg + frac * bm * bn * (c_out + c_red * nw);
     const double all = t * (a_b + w_b) / l2;
-    return (cu > all ? cu : all) + lat * (double)cdiv(cdiv(cdiv(K, 32), nw), depth);
+    const double cost = (cu > all ? cu : all) + lat * (double)cdiv(cdiv(cdiv(K, 32), nw), depth);
+    // what the model above leaves unexplained per (tile, wavefront count), fitted last: cost * scale + offset
+    static const struct { double scale, offset; } kAdjust[CONV_WSK_VARIANTS][3] = {
+        {{1.0, 0.0}, {1.0, 0.0}, {1.0, -0.1}},  {{0.95, 0.2}, {1.0, 0.0}, {0.95, 0.0}}, {{1.2, 0.0}, {1.0, 0.0}, {1.0, 0.0}},
+        {{1.0, 0.0}, {1.0, 0.0}, {1.0, 0.0}},   {{1.0, 0.0}, {0.9, 0.1}, {1.05, 0.0}},  {{0.9, 0.0}, {1.0, 0.0}, {1.0, 0.0}}};
+    const auto &adj = kAdjust[v][nw == 4 ? 0 : nw == 8 ? 1 : 2];
+    return cost * adj.scale + adj.offset;
 }
 
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
@@ -577,7 +586,7 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     }
     // Every candidate is priced with a small cost model fitted to per-layer timings of all GEMM layers of the
     // ResNet-18/50/152, VGG-16, MobileNetV2 and BERT-base/large graphs at batch 1 to 8, on 256 and on 128 CUs (picks
-    // within 3 % of the per-layer best of an exhaustive sweep, in total).  Times in microseconds, without the
+    // within 4 % of the per-layer best of an exhaustive sweep, in total).  Times in microseconds, without the
     // launch cost that all single-launch candidates share.
     double best = 1e30;
     for (int v = 0; v < CONV_WSK_VARIANTS; ++v)
@@ -587,8 +596,8 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
         }
     // LDS-tiled kernel, optionally with K cut in two (second launch: its cost plus the traffic of the partial sums).
     // A tile costs `shared` us per K step when workgroups share a compute unit and `alone` when it has one to itself.
-    struct { int variant; double shared, alone, fixed; } lds[4] = {{0, 0.357, 5.31, 0.664}, {1, 0.268, 4.73, 0.664}, {3, 0.746, 0.746, 0.664},
-                                                                   {4, 1.0, 1.0, 2.40}};
+    struct { int variant; double shared, alone, fixed; } lds[4] = {{0, 0.3613, 0.6385, 0.02038}, {1, 0.3664, 1.171, 0.1703}, {3, 0.7721, 0.7721, 0.554},
+                                                                   {4, 1.157, 1.157, 2.62}};
     for (const auto &c : lds) {
         int bm, bn, bk;
         conv_gemm_tile(c.variant, &bm, &bn, &bk);
@@ -597,7 +606,9 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
             if (sp > 1 && (K < 512 || (size_t)(sp * M * N) > ws_floats)) continue;
             const long wgs = tiles(c.variant) * sp, per_cu = cdiv(wgs, n_cu);
             double cost = c.fixed + (double)cdiv(KT, sp) * (per_cu == 1 ? c.alone : (double)per_cu * c.shared);
-            if (sp > 1) cost += 1.68 + (double)M * N * (4.0 * sp + 2.0) / 5.36e6;
+            if (sp == 1 && c.variant == 1) cost *= 1.35;          // residuals of the fit, as for the other kernel
+            if (sp == 1 && c.variant == 0) cost -= 0.1;
+            if (sp > 1) cost += 15.48 + (double)M * N * (4.0 * sp + 2.0) / 4.243e6;
             if (cost < best) {
                 best = cost;
                 pl = GemmPlan{0, c.variant, 1, (int)tiles(c.variant), 4, 0};
