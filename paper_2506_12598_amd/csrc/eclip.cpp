@@ -842,7 +842,8 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
             DwConvArgs da{};
             da.B = (int)batch; da.C = P.L.c; da.Ho = P.L.h; da.Wo = P.L.w; da.KH = P.L.kh; da.KW = P.L.kw; da.stride = P.L.stride;
             da.dtype = model->dtype == ECLIP_F32 ? DT_F32 : (model->dtype == ECLIP_BF16 ? DT_BF16 : DT_F16);
-            name = dwconv_pixels_per_thread(da, (int)model->pool->streams[mask_id].n_cu) == 4 ? "dwconv3_row_kernel" : "dwconv_kernel";
+            const int dw_cu = (int)model->pool->streams[mask_id].n_cu;
+            name = dwconv_strip_rows(da, dw_cu) ? "dwconv3_strip_kernel" : dwconv_pixels_per_thread(da, dw_cu) == 4 ? "dwconv3_row_kernel" : "dwconv_kernel";
             out->workgroups = (uint32_t)((rows * (P.L.c / ((P.L.c % 8 || model->dtype == ECLIP_F32) ? (model->dtype == ECLIP_F32 && P.L.c % 4 == 0 ? 4 : 1) : 8)) + 255) / 256);
         } else {
             name = "conv_f32_kernel";

@@ -220,6 +220,111 @@ __global__ __launch_bounds__(256) void dwconv3_row_kernel(DwConvArgs a, unsigned
     }
 }
 
+// The same for stride-1 layers tall enough to give every compute unit several strips: a thread owns PW output
+// columns x `ph` output rows of 8 channels and walks down its strip.  An input row is then loaded once per strip
+// instead of once per output row it touches, the 9 weight vectors, the bias and the index arithmetic are paid once
+// per strip, and the input row of the next output row is in flight while the current one is multiplied.  The input
+// rows live in a ring of R register rows (R - 3 rows ahead of the arithmetic); the walk is unrolled by R so that ring
+// positions are constants.
+template <typename T, int PW, int R>
+__global__ __launch_bounds__(256, 2) void dwconv3_strip_kernel(DwConvArgs a, unsigned total, unsigned wq, unsigned hq, int ph)
+{
+    constexpr int COLS = PW + 2;
+    const unsigned ui = banded_block() * blockDim.x + threadIdx.x;
+    if (ui >= total) return;
+    const unsigned cv = (unsigned)a.C >> 3;
+    const int c = (int)(ui % cv) * 8;
+    const unsigned m = ui / cv;
+    const int ow0 = (int)(m % wq) * PW;
+    const unsigned mh = m / wq;
+    const int oh0 = (int)(mh % hq) * ph;
+    const int b = (int)(mh / hq);
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((unsigned)a.B * a.H * a.W * a.C * 2u), 0x00020000);
+    const T *w = (const T *)a.w;
+    uint4 wp[9];                             // the 9 taps x 8 channels, kept packed: 36 registers instead of 72
+    float bv[8];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) wp[t] = *reinterpret_cast<const uint4 *>(w + (long)t * a.C + c);
+    if (a.bias) Pack<T, 8>::load((const T *)a.bias + c, bv);
+    else
+#pragma unroll
+        for (int i = 0; i < 8; ++i) bv[i] = 0.0f;
+    const int iw0 = ow0 - a.pad, ih0 = oh0 - a.pad;
+    unsigned col_off[COLS];                  // byte offset of (column, channel) inside an input row, or out of range
+#pragma unroll
+    for (int j = 0; j < COLS; ++j) col_off[j] = (unsigned)(iw0 + j) < (unsigned)a.W ? (unsigned)((iw0 + j) * a.C + c) * 2u : 0xffffffffu;
+    const unsigned row_bytes = (unsigned)(a.W * a.C) * 2u;
+    u32x4 ring[R][COLS];
+    auto load_row = [&](int r, u32x4 (&q)[COLS]) {           // input row ih0 + r of the strip
+        const int ih = ih0 + r;
+        const bool row_ok = (unsigned)ih < (unsigned)a.H;
+        const unsigned base = (unsigned)(b * a.H + ih) * row_bytes;
+#pragma unroll
+        for (int j = 0; j < COLS; ++j)
+            q[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, (row_ok && col_off[j] != 0xffffffffu) ? base + col_off[j] : 0xffffffffu, 0, 0);
+    };
+#pragma unroll
+    for (int r = 0; r < R - 1; ++r) load_row(r, ring[r]);
+    for (int i0 = 0; i0 < ph; i0 += R) {
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+            const int i = i0 + u;                            // output row oh0 + i reads input rows i .. i + 2
+            load_row(i + R - 1, ring[(u + R - 1) % R]);      // R - 3 output rows ahead (beyond the image: zeros)
+            float acc[PW][8];
+#pragma unroll
+            for (int p = 0; p < PW; ++p)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[p][e] = bv[e];
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                float wv[3][8];
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    const uint32_t ws[4] = {wp[kh * 3 + kw].x, wp[kh * 3 + kw].y, wp[kh * 3 + kw].z, wp[kh * 3 + kw].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { wv[kw][2 * e] = Cvt<T>::from_bits(ws[e] & 0xffffu); wv[kw][2 * e + 1] = Cvt<T>::from_bits(ws[e] >> 16); }
+                }
+#pragma unroll
+                for (int j = 0; j < COLS; ++j) {
+                    const u32x4 q = ring[(u + kh) % R][j];
+                    const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
+                    float xv[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { xv[2 * e] = Cvt<T>::from_bits(xs[e] & 0xffffu); xv[2 * e + 1] = Cvt<T>::from_bits(xs[e] >> 16); }
+#pragma unroll
+                    for (int p = 0; p < PW; ++p) {
+                        const int kw = j - p;                // a constant once the loops are unrolled
+                        if (kw >= 0 && kw < 3) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[p][e] = fmaf(xv[e], wv[kw][e], acc[p][e]);
+                        }
+                    }
+                }
+            }
+            const int oh = oh0 + i;
+            if (i < ph && oh < a.Ho) {
+#pragma unroll
+                for (int p = 0; p < PW; ++p) {
+                    const int ow = ow0 + p;
+                    if (ow < a.Wo) {
+                        const long off = ((long)(b * a.Ho + oh) * a.Wo + ow) * a.C + c;
+                        if (a.res) {
+                            float rv[8];
+                            Pack<T, 8>::load((const T *)a.res + off, rv);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[p][e] += rv[e];
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[p][e] = apply_act(a.act, acc[p][e]);
+                        Pack<T, 8>::store((T *)a.y + off, acc[p]);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ---------------- grouped convolution, channel concatenation, channel shuffle ------------------------------
 // (the operators of the second workload family: ResNeXt-, DenseNet- and ShuffleNet-style blocks)
 // One thread per output element; the Cin/groups input channels of a tap are contiguous in x and in w, read V at a time.
@@ -609,10 +714,31 @@ int dwconv_pixels_per_thread(const DwConvArgs &a, int n_cu)
     return (total >= 4L * n_cu * 256 && total < (1L << 31)) ? 4 : 1;
 }
 
+// Output rows per thread of the strip kernel (a multiple of its ring size, 4), or 0 when the layer is not a stride-1
+// 3x3 one with at least 4 workgroups of strips per compute unit: the tallest of 24, 16, 12, 8 that leaves that many.
+int dwconv_strip_rows(const DwConvArgs &a, int n_cu)
+{
+    if (dwconv_pixels_per_thread(a, n_cu) != 4 || a.stride != 1) return 0;
+    for (int ph : {24, 16, 12, 8}) {
+        const long strips = (long)a.B * ((a.Ho + ph - 1) / ph) * ((a.Wo + 1) / 2) * (a.C / 8);
+        if (strips >= 4L * n_cu * 256) return ph;
+    }
+    return 0;
+}
+
 hipError_t launch_dwconv(const DwConvArgs &a, int n_cu, hipStream_t s)
 {
     if (dwconv_pixels_per_thread(a, n_cu) == 4) {
         const unsigned wq = (unsigned)(a.Wo + 3) / 4;
+        const int ph = dwconv_strip_rows(a, n_cu);
+        if (ph) {                                            // tall stride-1 images: 2 x ph output pixels per thread
+            const unsigned hq = (unsigned)(a.Ho + ph - 1) / ph, wq2 = (unsigned)(a.Wo + 1) / 2;
+            const long strips = (long)a.B * hq * wq2 * (a.C / 8);
+            const dim3 grid(banded_blocks_for(strips, 256));
+            if (a.dtype == DT_BF16) hipLaunchKernelGGL((dwconv3_strip_kernel<bf16_t, 2, 4>), grid, dim3(256), 0, s, a, (unsigned)strips, wq2, hq, ph);
+            else hipLaunchKernelGGL((dwconv3_strip_kernel<f16_t, 2, 4>), grid, dim3(256), 0, s, a, (unsigned)strips, wq2, hq, ph);
+            return hipGetLastError();
+        }
         const long total = (long)a.B * a.Ho * wq * (a.C / 8);
         {
             const dim3 grid(banded_blocks_for(total, 256));

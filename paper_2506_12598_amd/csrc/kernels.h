@@ -66,6 +66,7 @@ struct DwConvArgs {
     int B, H, W, C, Ho, Wo, KH, KW, stride, pad, act, dtype;
 };
 int dwconv_pixels_per_thread(const DwConvArgs &a, int n_cu);   // 4 (large 3x3 layers, 16-bit types) or 1
+int dwconv_strip_rows(const DwConvArgs &a, int n_cu);          // rows per thread of the strip kernel, or 0
 hipError_t launch_dwconv(const DwConvArgs &a, int n_cu, hipStream_t s);
 
 // grouped convolution, 1 < groups < C: one thread per output element, weights [Cout][KH][KW][Cin/groups]

@@ -113,6 +113,23 @@ def test_depthwise_conv_four_pixels_per_thread(c, h, s, res, dt):
     assert rel_to_range(got, exp) <= (8e-3 if res else 4e-3)
 
 
+@pytest.mark.parametrize("res", [False, True])
+def test_depthwise_conv_strip_kernel(res):
+    """Tall stride-1 images take the strip kernel (a thread walks down 2 x 8..24 output pixels with the input rows in a
+    register ring); 200 x 200 on the 32-CU stream is enough for it.  Ragged height (200 = 8 * 25) and width."""
+    m = wl.single_layer("conv", wl.DT_BF16, seed=21, cin=64, cout=64, h=200, w=201, k=3, stride=1, pad=1, groups=64,
+                        act=wl.ACT_RELU6, bias_std=0.5, residual=res)
+    x = wl.make_input(m, 2)
+    exp = orc.run_model(m, x)
+    g = GpuModel(m, max_batch=2)
+    try:
+        assert g.h.kernel_info(0, 1, 2)["kernel"] == "dwconv3_strip_kernel"
+        got = g.run(x, table=[1])
+    finally:
+        g.free()
+    assert rel_to_range(got, exp) <= (8e-3 if res else 4e-3)
+
+
 # ---------------- linear -------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dt", DTS)
 @pytest.mark.parametrize("rows,k,n,act,res", [(128, 768, 2304, wl.ACT_NONE, False), (48, 512, 128, wl.ACT_GELU, False),
@@ -262,6 +279,9 @@ def test_every_gemm_variant_forced(force):
         check(m, batch=1, tol=2e-4)
         m = wl.single_layer("linear", wl.DT_BF16, seed=13, rows=1100, k=136, n=1100, std=0.1)
         check(m, batch=1, tol=2e-4)
+        # N not a multiple of 8 with bias and GELU: the element-by-element form of the staged epilogue
+        m = wl.single_layer("linear", wl.DT_F16, seed=14, rows=70, k=72, n=76, act=wl.ACT_GELU, bias_std=0.3, std=0.1)
+        check(m, batch=3, tol=3e-4)
     finally:
         os.environ.pop("ECLIP_GEMM_FORCE", None)
 
