@@ -12,6 +12,9 @@
 //      probabilities (4 per block) are already the column operand it must supply, and V^T is read from
 //      an LDS copy transposed on load so that the matching 4 keys are 8 contiguous bytes.
 // Probabilities are rounded to the 16-bit type for the second product, scores are never stored.
+// The key fragments come straight from global memory for up to 256 keys (all loads of the workgroup in flight at
+// once); beyond that the keys too are staged in LDS by the whole workgroup with row-contiguous loads and shared by
+// its wavefronts (fetched per wavefront in fragment order, 48 dependent round trips made S = 384 take 45 us).
 #include "device_common.h"
 #include "kernels.h"
 
@@ -45,7 +48,7 @@ struct AttnDev {
 template <typename T, int D, int KB, int NW>
 __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
 {
-    extern __shared__ __attribute__((aligned(16))) uint16_t vt[];    // [D][ldv]
+    extern __shared__ __attribute__((aligned(16))) uint16_t vt[];    // [D][ldv], then (long sequences) keys [Sp][D + 8]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qblocks = (p.S + NW * 16 - 1) / (NW * 16);
     const int qb = blockIdx.x % qblocks;
@@ -72,6 +75,19 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
     // Short sequences: the K fragments too are fetched before the V^T fill, so that all global loads of the
     // workgroup are in flight together (one memory round trip instead of three).
     constexpr bool PREFETCH_K = KB <= 16;
+    constexpr int KP = D + 8, CPR = D / 8;            // LDS pitch of a key row (conflict-free fragment reads), chunks per row
+    constexpr int K_IT = PREFETCH_K ? 1 : (KB * 16 * CPR) / (NW * 64);
+    static_assert(PREFETCH_K || (KB * 16 * CPR) % (NW * 64) == 0, "whole rounds of key chunks");
+    uint16_t *const kl = vt + D * p.ldv;
+    uint4 kq[K_IT];
+    if constexpr (!PREFETCH_K) {
+#pragma unroll
+        for (int it = 0; it < K_IT; ++it) {
+            const int c = tid + it * NW * 64, key = c / CPR, j0 = (c % CPR) * 8;
+            kq[it] = make_uint4(0, 0, 0, 0);
+            if (key < p.S) kq[it] = *reinterpret_cast<const uint4 *>(kp + (row0 + key) * ld + j0);
+        }
+    }
     uint4 kfr[PREFETCH_K ? KB : 1][D / 32];
     if constexpr (PREFETCH_K) {
 #pragma unroll
@@ -112,6 +128,13 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
         load_v(c, w);
         store_vt(c, w);
     }
+    if constexpr (!PREFETCH_K) {
+#pragma unroll
+        for (int it = 0; it < K_IT; ++it) {
+            const int c = tid + it * NW * 64, key = c / CPR, j0 = (c % CPR) * 8;
+            if (key < p.Sp) *reinterpret_cast<uint4 *>(&kl[key * KP + j0]) = kq[it];
+        }
+    }
     __syncthreads();
 
     // ---- scores
@@ -126,7 +149,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
             for (int ks = 0; ks < D / 32; ++ks) {
                 uint4 kf = make_uint4(0, 0, 0, 0);
                 if constexpr (PREFETCH_K) kf = kfr[kb][ks];
-                else if (key < p.S) kf = *reinterpret_cast<const uint4 *>(kp + (row0 + key) * ld + ks * 32 + g * 8);
+                else kf = *reinterpret_cast<const uint4 *>(&kl[key * KP + ks * 32 + g * 8]);      // key < Sp: rows beyond S hold zeros
                 sc[kb] = MmaA<T>::run(kf, qf[ks], sc[kb]);
             }
         }
@@ -209,26 +232,40 @@ hipError_t launch_d(const AttnDev &d, size_t lds, hipStream_t s)
     const int qblocks = (d.S + NW * 16 - 1) / (NW * 16);
     const dim3 grid((unsigned)(d.B * d.heads * qblocks)), block(NW * 64);
     const int nkb = d.Sp / 16;
-    if (nkb <= 8) hipLaunchKernelGGL((attention_kernel<T, D, 8, NW>), grid, block, lds, s, d);
-    else if (nkb <= 16) hipLaunchKernelGGL((attention_kernel<T, D, 16, NW>), grid, block, lds, s, d);
-    else if (nkb <= 32) hipLaunchKernelGGL((attention_kernel<T, D, 32, NW>), grid, block, lds, s, d);
-    else return hipErrorInvalidValue;
+    if constexpr (NW == 8) {
+        if (nkb > 32) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((attention_kernel<T, D, 32, NW>), grid, block, lds, s, d);
+    } else {
+        if (nkb <= 8) hipLaunchKernelGGL((attention_kernel<T, D, 8, NW>), grid, block, lds, s, d);
+        else if (nkb <= 16) hipLaunchKernelGGL((attention_kernel<T, D, 16, NW>), grid, block, lds, s, d);
+        else if (nkb <= 32 && NW == 4) hipLaunchKernelGGL((attention_kernel<T, D, 32, 4>), grid, block, lds, s, d);
+        else return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
 template <typename T, int D, int NW>
 hipError_t set_attr()
 {
-    hipError_t e;
-    const int lim = 96 * 1024;
-    if ((e = hipFuncSetAttribute((const void *)attention_kernel<T, D, 8, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
-    if ((e = hipFuncSetAttribute((const void *)attention_kernel<T, D, 16, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
-    return hipFuncSetAttribute((const void *)attention_kernel<T, D, 32, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+    const int lim = 144 * 1024;              // 512 keys: 65 KB of V^T + 72 KB of keys
+    if constexpr (NW == 8) {
+        return hipFuncSetAttribute((const void *)attention_kernel<T, D, 32, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+    } else {
+        hipError_t e;
+        if ((e = hipFuncSetAttribute((const void *)attention_kernel<T, D, 8, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+        if ((e = hipFuncSetAttribute((const void *)attention_kernel<T, D, 16, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, lim)) != hipSuccess) return e;
+        if constexpr (NW == 4) return hipFuncSetAttribute((const void *)attention_kernel<T, D, 32, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, lim);
+        else return hipSuccess;
+    }
 }
 
 }  // namespace
 
-size_t attention_lds_bytes(int S, int d) { return (size_t)d * ldv_of(round_up(S, 32)) * sizeof(uint16_t); }
+size_t attention_lds_bytes(int S, int d)
+{
+    const int Sp = round_up(S, 32);
+    return ((size_t)d * ldv_of(Sp) + (Sp > 256 ? (size_t)Sp * (d + 8) : 0)) * sizeof(uint16_t);
+}
 
 hipError_t attention_init()
 {
@@ -237,7 +274,9 @@ hipError_t attention_init()
     if ((e = set_attr<T, 32, 1>()) != hipSuccess) return e;            \
     if ((e = set_attr<T, 32, 4>()) != hipSuccess) return e;            \
     if ((e = set_attr<T, 64, 1>()) != hipSuccess) return e;            \
-    if ((e = set_attr<T, 64, 4>()) != hipSuccess) return e;
+    if ((e = set_attr<T, 64, 4>()) != hipSuccess) return e;            \
+    if ((e = set_attr<T, 32, 8>()) != hipSuccess) return e;            \
+    if ((e = set_attr<T, 64, 8>()) != hipSuccess) return e;
     SET(bf16_t)
     SET(f16_t)
 #undef SET
@@ -257,7 +296,13 @@ hipError_t launch_attention(const AttnArgs &a, int n_cu, hipStream_t s)
     // few (batch, head) pairs: one wavefront per workgroup spreads the query blocks over more CUs
     const long wg4 = (long)a.B * a.heads * ((a.S + 63) / 64);
     const bool small = wg4 < n_cu;
+    // more than 256 keys (keys staged in LDS, one workgroup per CU): 128 queries per workgroup when that still gives
+    // every other CU a workgroup, else 64
+    const bool longseq = d.Sp > 256;
+    const bool wide = longseq && 2L * a.B * a.heads * ((a.S + 127) / 128) >= n_cu;
 #define GO(T)                                                                                  \
+    if (D == 32 && longseq) return wide ? launch_d<T, 32, 8>(d, lds, s) : launch_d<T, 32, 4>(d, lds, s); \
+    if (D == 64 && longseq) return wide ? launch_d<T, 64, 8>(d, lds, s) : launch_d<T, 64, 4>(d, lds, s); \
     if (D == 32) return small ? launch_d<T, 32, 1>(d, lds, s) : launch_d<T, 32, 4>(d, lds, s); \
     if (D == 64) return small ? launch_d<T, 64, 1>(d, lds, s) : launch_d<T, 64, 4>(d, lds, s);
     if (a.dtype == DT_BF16) { GO(bf16_t) }
