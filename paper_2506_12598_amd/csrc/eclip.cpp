@@ -291,6 +291,7 @@ struct LayerPlan {
     size_t w_dev = NONE, b_dev = NONE, g_dev = NONE, be_dev = NONE;   // byte offsets in the device weight arena
     bool gemm = false;         // runs on the matrix-core GEMM kernel
     bool pair_next = false;    // this layer and the next are independent GEMM layers of one group: one launch may carry both
+    bool gapfc_next = false;   // global average pool whose only reader is the linear layer that follows: one launch may do both
 };
 
 struct eclip_req {
@@ -538,6 +539,17 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
         LayerPlan &A = m->layers[i];
         const LayerPlan &B = m->layers[i + 1];
         A.pair_next = A.gemm && B.gemm && d->group_of_layer[i] == d->group_of_layer[i + 1] && B.L.in0 != (int)i && B.L.in1 != (int)i;
+    }
+    // Pool + classifier candidates: a GAP layer read only by the matrix-core linear layer right after it, same group,
+    // the linear layer taking no second operand.  Whether the fused kernel pays depends on the batch (decided per request).
+    for (uint32_t i = 0; i + 1 < d->n_layers; ++i) {
+        LayerPlan &A = m->layers[i];
+        const LayerPlan &B = m->layers[i + 1];
+        if (A.L.op != ECLIP_OP_GAP || B.L.op != ECLIP_OP_LINEAR || !B.gemm || B.L.in0 != (int)i || B.L.in1 >= 0) continue;
+        if (d->group_of_layer[i] != d->group_of_layer[i + 1] || B.in.kind == ECLIP_KIND_IMAGE) continue;
+        bool other_reader = false;
+        for (uint32_t j = i + 2; j < d->n_layers; ++j) other_reader |= m->layers[j].L.in0 == (int)i || m->layers[j].L.in1 == (int)i;
+        A.gapfc_next = !other_reader;
     }
     return ECLIP_OK;
 }
@@ -995,6 +1007,20 @@ static hipError_t launch_pair(eclip_model *m, uint32_t i, int batch, hipStream_t
     return launch_conv_gemm_pair(a[0], pl[0], a[1], pl[1], s, n_launched);
 }
 
+// Launches the GAP layer i and the linear layer i + 1 (gapfc_next) as one kernel when the shape suits it.
+static hipError_t launch_gapfc_pair(eclip_model *m, uint32_t i, int batch, hipStream_t s, const void *d_in, float *d_out32, uint32_t *n_launched, bool *done)
+{
+    *done = false;
+    const LayerPlan &G = m->layers[i], &F = m->layers[i + 1];
+    const int HW = G.in.h * G.in.w, C = G.L.c;
+    if (getenv("ECLIP_NO_PAIRS") || !gapfc_supported(batch, HW, C, m->dtype)) return hipSuccess;
+    const void *x = G.L.in0 == -1 ? (m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in) : (const void *)(m->d_act + m->layers[G.L.in0].out_off);
+    *done = true;
+    *n_launched += 1;
+    return launch_gapfc(x, wptr(m, F.w_dev), wptr(m, F.b_dev), d_out32 ? nullptr : (void *)(m->d_act + F.out_off), d_out32, batch, HW, C, F.L.c, F.L.act,
+                        m->dtype, s);
+}
+
 static hipError_t launch_input_stage(eclip_model *m, int batch, const void *d_in, hipStream_t s, uint32_t *n_launched)
 {
     if (m->in_kind != ECLIP_IN_IMAGE) return hipSuccess;
@@ -1042,6 +1068,11 @@ extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void 
             bool paired = false;
             HIP_TRY(launch_pair(model, i, (int)batch, cur, (int)ps.n_cu, d_in, &r->n_kernels, &paired));
             if (paired) { ++i; continue; }
+        }
+        if (model->layers[i].gapfc_next) {
+            bool fused = false;
+            HIP_TRY(launch_gapfc_pair(model, i, (int)batch, cur, d_in, i + 2 == n_layers ? (float *)d_out : nullptr, &r->n_kernels, &fused));
+            if (fused) { ++i; continue; }
         }
         HIP_TRY(launch_layer(model, i, (int)batch, cur, (int)ps.n_cu, d_in, i + 1 == n_layers ? (float *)d_out : nullptr, &r->n_kernels));
     }

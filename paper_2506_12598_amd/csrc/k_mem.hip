@@ -850,6 +850,120 @@ hipError_t launch_gap(const void *x, void *y, float *y32, float *ws, size_t ws_f
     return hipGetLastError();
 }
 
+// ---------------- global average pool + classifier in one launch ------------------------------------------------
+// y[b][n] = act(bias[n] + sum_c mean_hw(x[b][hw][c]) * w[n][c]) for a small batch.  Every kernel costs a few
+// microseconds whatever it does, and after the pooling a classifier at batch 1 is a matrix-vector product: one launch
+// saves one of the two.  A workgroup first pools all C channels into LDS (float; each thread sums a share of the
+// pixels of one 16-byte channel chunk), then each of its 4 wavefronts takes one block of 16 outputs and walks the
+// weights in their blocked layout (1 KB blocks of 16 outputs x 32 channels, lane l = output l & 15, channels
+// 8 (l >> 4) .. +7), so that every weight load of a wavefront is one contiguous kilobyte.  The pooled vector is read
+// once per workgroup, which is what limits the form to moderate C x HW (the caller decides).
+template <typename T>
+__global__ __launch_bounds__(256) void gapfc_kernel(const T *x, const uint4 *wb, const T *bias, T *y, float *y32, int HW, int C, int N,
+                                                    int KB, int act)
+{
+    extern __shared__ __attribute__((aligned(16))) float gsm[];       // pooled[KB * 32], then part[parts][C]
+    float *pooled = gsm, *part = gsm + KB * 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.y;
+    const int cv = C >> 3, parts = 256 / cv;                           // C % 8 == 0 and C <= 2048 (checked by the caller)
+    if (tid < parts * cv) {
+        const int chunk = tid % cv, pt = tid / cv;
+        const T *src = x + ((long)b * HW) * C + chunk * 8;
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+        int px = pt;
+        for (; px + 3 * parts < HW; px += 4 * parts) {                 // four loads in flight
+            float v[4][8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Pack<T, 8>::load(src + (long)(px + u * parts) * C, v[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += v[u][e];
+        }
+        for (; px < HW; px += parts) {
+            float v[8];
+            Pack<T, 8>::load(src + (long)px * C, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += v[e];
+        }
+        float *dst = part + pt * C + chunk * 8;
+        *reinterpret_cast<float4 *>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4 *>(dst + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    }
+    __syncthreads();
+    const float inv = 1.0f / (float)HW;
+    for (int c = tid; c < KB * 32; c += 256) {
+        float sum = 0.0f;
+        if (c < C)
+            for (int pt = 0; pt < parts; ++pt) sum += part[pt * C + c];
+        pooled[c] = sum * inv;                                         // zero beyond C: the weight blocks are padded too
+    }
+    __syncthreads();
+    const int nb = blockIdx.x * 4 + wave;
+    if (nb * 16 >= N) return;
+    const uint4 *wrow = wb + (long)nb * KB * 64 + lane;
+    const float *pv = pooled + (lane >> 4) * 8;
+    float acc = 0.0f;
+    int kb = 0;
+    for (; kb + 4 <= KB; kb += 4) {
+        uint4 q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) q[u] = wrow[(kb + u) * 64];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t ws4[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+            const float4 p0 = *reinterpret_cast<const float4 *>(pv + (kb + u) * 32), p1 = *reinterpret_cast<const float4 *>(pv + (kb + u) * 32 + 4);
+            const float pe[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc = fmaf(Cvt<T>::from_bits(ws4[e] & 0xffffu), pe[2 * e], acc);
+                acc = fmaf(Cvt<T>::from_bits(ws4[e] >> 16), pe[2 * e + 1], acc);
+            }
+        }
+    }
+    for (; kb < KB; ++kb) {
+        const uint4 q = wrow[kb * 64];
+        const uint32_t ws4[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = fmaf(Cvt<T>::from_bits(ws4[e] & 0xffffu), pv[kb * 32 + 2 * e], acc);
+            acc = fmaf(Cvt<T>::from_bits(ws4[e] >> 16), pv[kb * 32 + 2 * e + 1], acc);
+        }
+    }
+    acc += __shfl_xor(acc, 16, 64);
+    acc += __shfl_xor(acc, 32, 64);
+    const int n = nb * 16 + lane;
+    if (lane < 16 && n < N) {
+        float v = acc + (bias ? Cvt<T>::load(bias + n) : 0.0f);
+        v = apply_act(act, v);
+        if (y32) y32[(long)b * N + n] = v;
+        else Cvt<T>::store(y + (long)b * N + n, v);
+    }
+}
+
+bool gapfc_supported(int B, int HW, int C, int dtype)
+{
+    // the pooled tensor is re-read by every workgroup and the weights by every batch item: small cases only
+    return (dtype == DT_BF16 || dtype == DT_F16) && B <= 8 && C % 8 == 0 && C >= 8 && C <= 2048 && (long)HW * C <= 64 * 1024;
+}
+
+hipError_t launch_gapfc(const void *x, const void *w_blocked, const void *bias, void *y, float *y32, int B, int HW, int C, int N, int act,
+                        int dtype, hipStream_t s)
+{
+    if (!gapfc_supported(B, HW, C, dtype)) return hipErrorInvalidValue;
+    const int KB = (C + 31) / 32, NB = (N + 15) / 16, parts = 256 / (C / 8);
+    const size_t lds = ((size_t)KB * 32 + (size_t)parts * C) * sizeof(float);
+    const dim3 grid((unsigned)((NB + 3) / 4), (unsigned)B);
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(gapfc_kernel<bf16_t>, grid, dim3(256), lds, s, (const bf16_t *)x, (const uint4 *)w_blocked, (const bf16_t *)bias, (bf16_t *)y, y32, HW, C, N, KB, act);
+    else
+        hipLaunchKernelGGL(gapfc_kernel<f16_t>, grid, dim3(256), lds, s, (const f16_t *)x, (const uint4 *)w_blocked, (const f16_t *)bias, (f16_t *)y, y32, HW, C, N, KB, act);
+    return hipGetLastError();
+}
+
 template <bool SOFTMAX>
 static hipError_t launch_row(const RowArgs &a, hipStream_t s)
 {

@@ -92,6 +92,12 @@ int gap_parts(int B, int HW, int C, int n_cu);
 hipError_t launch_gap(const void *x, void *y, float *y32, float *ws, size_t ws_floats, int B, int HW, int C, int dtype, int n_cu,
                       hipStream_t s, uint32_t *n_launched);
 
+// global average pool and the linear layer that follows it in one launch (small batch, moderate C x HW):
+// x [B][HW][C], w in the blocked GEMM layout of an N x C matrix, y [B][N] (model dtype) or y32 (float)
+bool gapfc_supported(int B, int HW, int C, int dtype);
+hipError_t launch_gapfc(const void *x, const void *w_blocked, const void *bias, void *y, float *y32, int B, int HW, int C, int N, int act,
+                        int dtype, hipStream_t s);
+
 struct RowArgs {
     const void *x, *res, *gamma, *beta;
     void *y; float *y32;

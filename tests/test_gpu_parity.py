@@ -141,6 +141,26 @@ def test_linear(rows, k, n, act, res, dt):
     check(m, batch=2, tol=2e-4)
 
 
+# ---------------- global average pool + classifier in one launch ---------------------------------------------
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("c,h,w,n,batch,act,then", [(512, 7, 7, 1000, 1, wl.ACT_NONE, 0), (1280, 7, 7, 1000, 3, wl.ACT_NONE, 0),
+                                                    (64, 5, 3, 10, 8, wl.ACT_RELU, 0), (136, 9, 9, 72, 2, wl.ACT_GELU, 24)])
+def test_gap_and_classifier_share_a_launch(c, h, w, n, batch, act, then, dt):
+    """A pooling layer read only by the linear layer after it goes out as one kernel at small batch (pooled vector in
+    LDS, float; the weights in their blocked layout).  Cases: the ResNet-18 and MobileNetV2 heads, ragged C (136 =
+    4.25 blocks of 32), N (72, 10) and pixel counts, the classifier as last layer (float output) and not."""
+    m = wl.single_layer("gapfc", dt, seed=c + n, c=c, h=h, w=w, n=n, act=act, then=then, bias_std=0.3, std=1.0 / np.sqrt(c))
+    x = wl.make_input(m, batch)
+    exp = orc.run_model(m, x)
+    g = GpuModel(m, max_batch=batch)
+    try:
+        got, (_, n_k, _) = g.run(x, table=[0], timing=True)
+    finally:
+        g.free()
+    assert n_k == (3 if then else 2)          # input re-layout, pool + classifier (, second linear layer)
+    assert rel_to_range(got, exp) <= (4e-3 if dt == wl.DT_BF16 else 1e-3)
+
+
 # ---------------- pooling, row kernels, element-wise, embedding ------------------------------------------------
 @pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
 def test_maxpool_and_gap(dt):

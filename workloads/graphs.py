@@ -517,6 +517,13 @@ def single_layer(op: str, dtype=DT_BF16, seed=0, **kw) -> Model:
     elif op == "gap":
         b = _Builder("gap", dtype, seed, IN_IMAGE, kw["c"], kw["h"], kw["w"])
         b.gap(-1)
+    elif op == "gapfc":
+        # global average pool + classifier (+ an optional second linear layer, so that the classifier is not the last layer)
+        b = _Builder("gapfc", dtype, seed, IN_IMAGE, kw["c"], kw["h"], kw["w"])
+        x = b.gap(-1)
+        x = b.linear(x, kw["n"], kw.get("act", ACT_NONE), std=kw.get("std"), bias_std=kw.get("bias_std", 0.0))
+        if kw.get("then"):
+            b.linear(x, kw["then"], std=kw.get("std"))
     elif op == "layernorm":
         b = _Builder("layernorm", dtype, seed, IN_SEQ, kw["width"], 1, kw["rows"])
         res = -2
