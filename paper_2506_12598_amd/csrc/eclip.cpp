@@ -311,6 +311,8 @@ struct eclip_model {
     uint32_t n_groups = 0;
     std::vector<uint32_t> mask_of_group;
     bool has_alloc = false;
+    bool stem_direct = false;      // layer 0 is the only reader of an IMAGE input of <= 4 channels and a matrix-core convolution:
+                                   // it may read the caller's tensor itself instead of the channels-last copy
 
     char *d_weights = nullptr;
     char *d_act = nullptr;
@@ -539,6 +541,13 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
         LayerPlan &A = m->layers[i];
         const LayerPlan &B = m->layers[i + 1];
         A.pair_next = A.gemm && B.gemm && d->group_of_layer[i] == d->group_of_layer[i + 1] && B.L.in0 != (int)i && B.L.in1 != (int)i;
+    }
+    {
+        const LayerPlan &S = m->layers[0];
+        bool only_reader = true;
+        for (uint32_t j = 1; j < d->n_layers; ++j) only_reader &= m->layers[j].L.in0 != -1 && m->layers[j].L.in1 != -1;
+        m->stem_direct = d->in_kind == ECLIP_IN_IMAGE && d->in_c <= 4 && m->in_cp == 8 && S.L.op == ECLIP_OP_CONV && S.gemm &&
+                         S.L.in0 == -1 && S.L.in1 != -1 && only_reader && d->n_layers > 1;
     }
     // Pool + classifier candidates: a GAP layer read only by the matrix-core linear layer right after it, same group,
     // the linear layer taking no second operand.  Whether the fused kernel pays depends on the batch (decided per request).
@@ -1021,6 +1030,22 @@ static hipError_t launch_gapfc_pair(eclip_model *m, uint32_t i, int batch, hipSt
                         m->dtype, s);
 }
 
+// First layer straight from the caller's NCHW tensor (stem_direct), when a plan of that form is within the cost of the
+// re-layout kernel it saves; *done tells whether it was launched.
+static hipError_t launch_stem_direct(eclip_model *m, int batch, hipStream_t s, int n_cu, const void *d_in, uint32_t *n_launched, bool *done)
+{
+    *done = false;
+    const LayerPlan &P = m->layers[0];
+    const GemmShape g = gemm_shape(P, batch);
+    GemmPlan pl;
+    if (!conv_gemm_plan_stem((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats, 2.0, &pl)) return hipSuccess;
+    ConvGemmArgs a{d_in, wptr(m, P.w_dev), wptr(m, P.b_dev), nullptr, m->d_act + P.out_off, nullptr, m->d_ws,
+                   g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, P.L.act, m->dtype};
+    a.nchw_c = m->in_c;
+    *done = true;
+    return launch_conv_gemm(a, pl, s, n_launched);
+}
+
 static hipError_t launch_input_stage(eclip_model *m, int batch, const void *d_in, hipStream_t s, uint32_t *n_launched)
 {
     if (m->in_kind != ECLIP_IN_IMAGE) return hipSuccess;
@@ -1051,9 +1076,12 @@ extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void 
     HIP_TRY(hipEventRecord(r->start, cur));
     r->n_kernels = 0;
     r->n_switches = 0;
-    HIP_TRY(launch_input_stage(model, (int)batch, d_in, cur, &r->n_kernels));
+    bool stem_done = false;
+    if (model->stem_direct)
+        HIP_TRY(launch_stem_direct(model, (int)batch, cur, (int)pool->streams[model->mask_of_group[0]].n_cu, d_in, &r->n_kernels, &stem_done));
+    if (!stem_done) HIP_TRY(launch_input_stage(model, (int)batch, d_in, cur, &r->n_kernels));
     uint32_t prev_group = 0;
-    for (uint32_t i = 0; i < n_layers; ++i) {
+    for (uint32_t i = stem_done ? 1 : 0; i < n_layers; ++i) {
         const uint32_t g = model->group_of_layer[i];
         const PoolStream &ps = pool->streams[model->mask_of_group[g]];
         if (g != prev_group && ps.stream != cur) {

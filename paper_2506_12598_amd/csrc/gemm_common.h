@@ -15,6 +15,7 @@ struct GemmDev {
     int B, H, W, Cin, Ho, Wo, KH, KW, stride, pad, act;
     int M, N, K, KT, kt_per, splits, tiles_m, tiles_n, raster;
     unsigned x_bytes, w_bytes;               // sizes of the x and w tensors (each below 4 GiB)
+    int nchw_c;                              // > 0: x is the caller's [B][nchw_c][H][W] tensor (first layer), Cin == 8
 };
 
 template <typename T> struct Mma;

@@ -624,6 +624,30 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
 
 // Two independent layers in one launch of the wave-split-K kernel: possible when both are planned on that kernel and
 // one (tile, wavefront count) serves both at a modelled extra cost below what the second launch would cost.
+// Plan for a first layer that reads the caller's NCHW tensor itself (see conv_wsk_kernel): the cheapest of the tile
+// shapes that exist in that form, if it costs at most `stage_us` (the separate re-layout kernel it saves) more than
+// the unrestricted plan.
+bool conv_gemm_plan_stem(long M, long N, long K, int n_cu, size_t ws_floats, double stage_us, GemmPlan *out)
+{
+    if (getenv("ECLIP_GEMM_FORCE") || getenv("ECLIP_NO_PAIRS")) return false;
+    const GemmPlan any = conv_gemm_plan(M, N, K, n_cu, ws_floats);
+    if (any.kind != 1) return false;
+    const double any_cost = wsk_cost(M, N, K, n_cu, any.variant, any.nw);
+    double best = 1e30;
+    int bv = -1;
+    for (int v : {0, 1, 5}) {
+        const double c = wsk_cost(M, N, K, n_cu, v, 4);
+        if (c < best) { best = c; bv = v; }
+    }
+    if (bv < 0 || best > any_cost + stage_us) return false;
+    int bm, bn;
+    conv_wsk_tile(bv, &bm, &bn);
+    GemmPlan pl{1, bv, 1, (int)(cdiv(M, bm) * cdiv(N, bn)), 4, 0};
+    set_xcd_split(pl, M, N);
+    *out = pl;
+    return true;
+}
+
 bool conv_gemm_plan_pair(const GemmPlan &s0, long M0, long N0, long K0, const GemmPlan &s1, long M1, long N1, long K1, int n_cu,
                          GemmPlan *p0, GemmPlan *p1)
 {
@@ -655,7 +679,8 @@ static GemmDev make_dev(const ConvGemmArgs &a, const GemmPlan &pl)
     d.B = a.B; d.H = a.H; d.W = a.W; d.Cin = a.Cin; d.Ho = a.Ho; d.Wo = a.Wo; d.KH = a.KH; d.KW = a.KW;
     d.stride = a.stride; d.pad = a.pad; d.act = a.act;
     d.M = a.B * a.Ho * a.Wo; d.N = a.Cout; d.K = a.KH * a.KW * a.Cin;
-    d.x_bytes = (unsigned)((size_t)a.B * a.H * a.W * a.Cin * 2);
+    d.nchw_c = a.nchw_c;
+    d.x_bytes = (unsigned)((size_t)a.B * a.H * a.W * (a.nchw_c ? a.nchw_c : a.Cin) * 2);
     d.w_bytes = (unsigned)((size_t)((d.N + 15) / 16) * ((d.K + 31) / 32) * 1024);   // blocked layout, see ConvGemmArgs::w
     int bm, bn, bk;
     conv_gemm_tile(pl.variant, &bm, &bn, &bk);

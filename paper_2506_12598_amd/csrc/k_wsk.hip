@@ -62,7 +62,10 @@ __device__ __forceinline__ void wsk_finish(const GemmDev &p, const float4 *red4,
     }
 }
 
-template <typename T, int TM, int TN, int NW, int D>
+// NCHW: the first layer of an image model reads the caller's [B][C][H][W] tensor (C = p.nchw_c <= 4) directly.  Its
+// K runs over (kh, kw, 8 channel slots), one 16-byte chunk per tap as in the channels-last copy with C padded to 8, so
+// weights and bookkeeping are the same; the chunk is put together from C two-byte loads, one per plane.
+template <typename T, int TM, int TN, int NW, int D, bool NCHW = false>
 __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p1, int n0)
 {
     // One launch can carry two independent layers ("horizontal" fusion, e.g. the two convolutions that read a
@@ -117,8 +120,10 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p
         const int oh = r / p.Wo, ow = r - oh * p.Wo;
         a_ih0[i] = oh * p.stride - p.pad;
         a_iw0[i] = ow * p.stride - p.pad;
-        a_off0[i] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * (unsigned)p.Cin * 2u;
+        if constexpr (NCHW) a_off0[i] = ((unsigned)(b * p.nchw_c) * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * 2u;
+        else a_off0[i] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * (unsigned)p.Cin * 2u;
     }
+    const unsigned plane = (unsigned)(p.H * p.W) * 2u;            // NCHW: bytes between the planes of two channels
     // weights: 1 KB blocks of 16 rows x 32 k in lane order, so a fragment is one contiguous load
     const int KB = (p.K + 31) >> 5, NB = (p.N + 15) >> 4;
     int b_ok[TN];
@@ -150,12 +155,20 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p
     // branch-free: a lane whose chunk is padding, beyond M / N or beyond the wavefront's K slice loads zeros
     auto load = [&](Frag &f) {
         const int k_ok = k < k_lim, kb_ok = kb < ks1;
-        const unsigned tap_off = (unsigned)((kh * p.W + kw) * p.Cin + ci) * 2u;
+        const unsigned tap_off = NCHW ? (unsigned)(kh * p.W + kw) * 2u : (unsigned)((kh * p.W + kw) * p.Cin + ci) * 2u;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int ok = a_ok[i] & k_ok & (int)((unsigned)(a_ih0[i] + kh) < (unsigned)p.H) & (int)((unsigned)(a_iw0[i] + kw) < (unsigned)p.W);
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? a_off0[i] + tap_off : OOB, 0, 0);
-            f.a[i] = make_uint4(v.x, v.y, v.z, v.w);
+            if constexpr (NCHW) {
+                unsigned c[4];
+#pragma unroll
+                for (int ch = 0; ch < 4; ++ch)
+                    c[ch] = (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rx, (ok & (int)(ch < p.nchw_c)) ? a_off0[i] + tap_off + (unsigned)ch * plane : OOB, 0, 0) & 0xffffu;
+                f.a[i] = make_uint4(c[0] | (c[1] << 16), c[2] | (c[3] << 16), 0u, 0u);
+            } else {
+                const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? a_off0[i] + tap_off : OOB, 0, 0);
+                f.a[i] = make_uint4(v.x, v.y, v.z, v.w);
+            }
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -242,6 +255,15 @@ hipError_t launch_nw(const GemmDev &d, const GemmDev &d1, int n0, int nw, int ti
     const size_t lds = (size_t)nw * TM * TN * 64 * 16;
     if (lds > 128 * 1024) return hipErrorInvalidValue;
     const dim3 grid((unsigned)tiles);
+    if (d.nchw_c) {                                    // first-layer form: 4 wavefronts, tiles 16x64, 32x64, 32x32
+        if constexpr ((TM == 1 && TN == 4) || (TM == 2 && TN == 4) || (TM == 2 && TN == 2)) {
+            if (nw != 4 || &d != &d1) return hipErrorInvalidValue;
+            hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4, Depth<TM, TN, 4>::value, true>), grid, dim3(256), lds, s, d, d1, n0);
+            return hipGetLastError();
+        } else {
+            return hipErrorInvalidValue;
+        }
+    }
     switch (nw) {
     case 4: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 4, Depth<TM, TN, 4>::value>), grid, dim3(256), lds, s, d, d1, n0); break;
     case 8: hipLaunchKernelGGL((conv_wsk_kernel<T, TM, TN, 8, Depth<TM, TN, 8>::value>), grid, dim3(512), lds, s, d, d1, n0); break;

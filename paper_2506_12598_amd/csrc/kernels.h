@@ -22,6 +22,7 @@ struct ConvGemmArgs {
     float *y32;          // [M][Cout] float output, or null
     float *ws;           // split-K partial sums, >= splits*M*Cout floats when splits > 1
     int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, act, dtype;
+    int nchw_c = 0;      // > 0: x is [B][nchw_c][H][W] with nchw_c <= 4 real channels, Cin == 8 (wave-split-K plans of conv_gemm_plan_stem only)
 };
 struct GemmPlan {
     int kind;      // 0 = LDS-tiled kernel (large problems), 1 = wave-split-K kernel (few tiles, long K)
@@ -31,6 +32,7 @@ struct GemmPlan {
     int nw;        // kind 1: wavefronts per workgroup, each taking 1/nw of K
     int raster;    // kind 0: workgroups walk the tiles in 8 x 4 blocks per XCD (tiles then counts whole blocks)
 };
+bool conv_gemm_plan_stem(long M, long N, long K, int n_cu, size_t ws_floats, double stage_us, GemmPlan *out);   // ConvGemmArgs::nchw_c
 enum { CONV_GEMM_VARIANTS = 5 };         // 128x128x32, 64x64x64, 32x64x64, 256x256x32, 128x256x64
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
 enum { CONV_WSK_VARIANTS = 6 };          // 16x64, 32x64, 64x64, 16x16, 16x32, 32x32

@@ -141,6 +141,26 @@ def test_linear(rows, k, n, act, res, dt):
     check(m, batch=2, tol=2e-4)
 
 
+# ---------------- first layer straight from the NCHW input --------------------------------------------------------
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("cin,cout,h,w,k,s,p,batch", [(3, 64, 56, 56, 7, 2, 3, 1), (3, 32, 45, 37, 3, 2, 1, 3), (1, 16, 30, 30, 5, 1, 2, 2),
+                                                      (4, 24, 33, 20, 3, 1, 1, 2)])
+def test_stem_reads_the_nchw_input_itself(cin, cout, h, w, k, s, p, batch, dt):
+    """With at most 4 input channels the first convolution gathers its operand from the caller's [B][C][H][W] planes
+    (two-byte loads, one per channel) instead of from a channels-last copy written by a kernel of its own: one launch
+    fewer, checked through the kernel count.  Ragged sizes, 1 to 4 channels, strides 1 and 2."""
+    m = wl.single_layer("stem", dt, seed=cin * 7 + cout, cin=cin, cout=cout, h=h, w=w, k=k, stride=s, pad=p, bias_std=0.5)
+    x = wl.make_input(m, batch)
+    exp = orc.run_model(m, x)
+    g = GpuModel(m, max_batch=batch)
+    try:
+        got, (_, n_k, _) = g.run(x, table=[0], timing=True)
+    finally:
+        g.free()
+    assert n_k == 3                           # stem, second convolution, conversion of the image output to float NCHW
+    assert rel_to_range(got, exp) <= (8e-3 if dt == wl.DT_BF16 else 1e-3)
+
+
 # ---------------- global average pool + classifier in one launch ---------------------------------------------
 @pytest.mark.parametrize("dt", DTS)
 @pytest.mark.parametrize("c,h,w,n,batch,act,then", [(512, 7, 7, 1000, 1, wl.ACT_NONE, 0), (1280, 7, 7, 1000, 3, wl.ACT_NONE, 0),

@@ -55,8 +55,9 @@ def test_masked_streams_confine_workgroups():
 def test_independent_layers_share_a_launch():
     """The projection shortcut and the first convolution of a residual block read the same tensor and do not depend on
     each other: the executor sends such a pair to the GPU as one launch; the global average pool and the classifier
-    share one too.  Same logits (within accumulation noise), four kernels fewer per ResNet-18 request;
-    ECLIP_NO_PAIRS=1 turns both fusions off."""
+    share one too, and the stem reads the caller's NCHW tensor itself instead of a channels-last copy made by a kernel of
+    its own.  Same logits (within accumulation noise), five kernels fewer per ResNet-18 request; ECLIP_NO_PAIRS=1 turns
+    the three fusions off."""
     import os
     m = wl.resnet(18, seed=1, hw=64)
     x = wl.make_input(m, 2)
@@ -71,7 +72,7 @@ def test_independent_layers_share_a_launch():
             os.environ.pop("ECLIP_NO_PAIRS", None)
     finally:
         g.free()
-    assert n_plain == 24 and n_fused == 20
+    assert n_plain == 24 and n_fused == 19
     assert rel_to_range(got, exp) <= 2e-2 and rel_to_range(ref, exp) <= 2e-2
     assert np.abs(got - ref).max() <= 4e-3 * (exp.max() - exp.min())
 
@@ -88,8 +89,9 @@ def test_every_mask_and_table_gives_identical_logits():
         for table in ([1, 1, 1, 1], [5, 5, 5, 5], [1, 2, 3, 4], [4, 1, 4, 1], [0, 3, 3, 0], [2, 2, 5, 5]):
             got, (ns, n_k, n_sw) = g.run(x, table=table, timing=True)
             assert n_sw == sum(1 for i in range(1, 4) if table[i] != table[i - 1]) == g.h.switches()
-            # 23 layers + the input re-layout; up to 3 pairs of independent convolutions share a launch, pool + classifier too
-            assert 20 <= n_k <= 26 and ns > 0
+            # 23 layers + the input re-layout; up to 3 pairs of independent convolutions share a launch, pool + classifier
+            # too, and the stem may take over the re-layout
+            assert 19 <= n_k <= 26 and ns > 0
             # split-K slice counts depend on the CU count, so sums may be associated differently:
             # compare within float32 accumulation noise of the 16-bit outputs
             assert rel_to_range(got, exp) <= 2e-2

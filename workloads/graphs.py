@@ -517,6 +517,11 @@ def single_layer(op: str, dtype=DT_BF16, seed=0, **kw) -> Model:
     elif op == "gap":
         b = _Builder("gap", dtype, seed, IN_IMAGE, kw["c"], kw["h"], kw["w"])
         b.gap(-1)
+    elif op == "stem":
+        # first convolution of an image model (few input channels) followed by a second convolution
+        b = _Builder("stem", dtype, seed, IN_IMAGE, kw["cin"], kw["h"], kw["w"])
+        x = b.conv(-1, kw["cout"], kw["k"], kw.get("stride", 1), kw.get("pad", 0), kw.get("act", ACT_RELU), bias_std=kw.get("bias_std", 0.0))
+        b.conv(x, kw.get("cout2", kw["cout"]), 1, 1, 0, ACT_NONE)
     elif op == "gapfc":
         # global average pool + classifier (+ an optional second linear layer, so that the classifier is not the last layer)
         b = _Builder("gapfc", dtype, seed, IN_IMAGE, kw["c"], kw["h"], kw["w"])
