@@ -436,7 +436,7 @@ def policies_mode(args):
     prof_pool = ec.Pool(masks)
     workers = [Worker(ec, torch, prof_pool, m, i, args.depth, batches[i]) for i, m in enumerate(models)]
     # beta[w][k][c]: latency of kernel k of worker w on configuration c, in ns (Sec. III-B, factor (i))
-    beta = [[[int(wk.h.profile_group(k, prof_id[(w, ci)], batch=pb[w], iters=10 if cfg < 4 else 3)[0]) for ci in range(len(configs))]
+    beta = [[[int(wk.h.profile_group(k, prof_id[(w, ci)], batch=pb[w], iters=3 if cfg == 4 else 40)[0]) for ci in range(len(configs))]
              for k in range(len(wk.model.layers))] for w, wk in enumerate(workers)]
     same_ns, pooled_ns, _ = prof_pool.bench_switch(0, 1, 2000, with_create=False)
     switch_cost_ns = max(0, int(pooled_ns - same_ns))
@@ -625,35 +625,87 @@ def main():
     for w, wk in enumerate(workers):
         rows, counts = [], []
         for g in range(wk.model.n_groups):
-            rows.append([int(sum(wk.h.profile_group(g, prof_id[(w, ci)], batch=prof_batch[w], iters=10 if cfg < 4 else 3)))
+            rows.append([int(sum(wk.h.profile_group(g, prof_id[(w, ci)], batch=prof_batch[w], iters=3 if cfg == 4 else 40)))
                          for ci in range(len(configs))])
             counts.append(wk.h.group_size(g))
         beta.append(rows); nk.append(counts)
     same_ns, pooled_ns, _ = prof_pool.bench_switch(0, 1, 2000, with_create=False)
     switch_cost_ns = max(0, int(pooled_ns - same_ns))
     max_configs = max(1, 4 // n_w)
-    assign, objective, switches = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, max_configs=max_configs,
-                                                       switch_cost_ns=switch_cost_ns)
-    log(f"profiled in {time.perf_counter() - t0:.1f}s; switch cost {switch_cost_ns} ns; allocation (CUs) "
-        f"{[[configs[c] for c in a] for a in assign]} switches {switches}")
+    # Slope of the interference law.  The model charges a kernel (1 + alpha) times its solo latency, alpha = CU overlap /
+    # total CUs, a slope the paper calibrated on its GPU (two kernels on the same CUs: twice as long).  Here the slope is
+    # measured with the mix itself: every worker alone, then all together, each time on its full-GPU mask (overlap =
+    # (n_w - 1) x all CUs).  The solver takes the calibrated law as an alpha table over the overlap, in 32-CU steps.
+    full = len(configs) - 1
+    n_cal = max(20, min(300, steps // 4))
+    for w, wk in enumerate(workers):
+        wk.h.alloc_set([prof_id[(w, full)]] * wk.model.n_groups)
+    solo_rate = []
+    for wk in workers:
+        run_closed([wk], max(5, n_cal // 5))
+        dt, served = run_closed([wk], n_cal)
+        solo_rate.append(served / dt)
+    run_closed(workers, max(5, n_cal // 5))
+    dt, _ = run_closed(workers, n_cal)
+    co_rate = [wk.served / dt for wk in workers]
+    torch.cuda.synchronize()
+    slowdown = float(np.mean([s / max(c, 1e-9) for s, c in zip(solo_rate, co_rate)]))
+    slope = min(1.0, max(0.02, (slowdown - 1.0) / max(1, n_w - 1)))
+    alpha_ppm = [int(round(slope * (k * 32 / 256.0) * 1e6)) for k in range((n_w - 1) * 8 + 1)]
+    # Two candidate allocations: the model with the paper's slope (overlap = excess over the GPU, slope 1) and with the
+    # slope measured above.  When they differ, each serves a short closed-loop trial on its own serving pool and the
+    # faster one is kept: the (1 + alpha) law is coarse on this GPU either way (small kernels hardly interfere, a
+    # switch costs more inside a pipelined request stream than in isolation), so the profile picks the candidates and a
+    # measurement picks between them.
+    cand = []
+    for name, kw in (("paper slope", {}), ("measured slope", {"overlap_mode": ec.OVERLAP_TABLE, "alpha_ppm": alpha_ppm, "granule": 32})):
+        a, _, sw = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, max_configs=max_configs, switch_cost_ns=switch_cost_ns, **kw)
+        if not any(a == c[1] for c in cand):
+            cand.append((name, a, sw))
+    log(f"profiled in {time.perf_counter() - t0:.1f}s; switch cost {switch_cost_ns} ns; co-run slowdown {slowdown:.3f} -> "
+        f"overlap slope {slope:.3f}; candidates " + "; ".join(f"{n}: {[[configs[c] for c in w] for w in a]}" for n, a, _ in cand))
 
     # ---- serving pool: id 0 = shared unmasked stream (policy unpart_a); ids 1..n_w = one private unmasked stream per
     # worker (policy unpart_b); then only the masked streams the allocation uses, created back to back so that they
     # land on distinct pipes
-    masks = [(None, -1)] + [(None, w) for w in range(n_w)]
-    mask_id = {}
-    for w in range(n_w):
-        for c in sorted(set(assign[w])):
-            mask_id[(w, c)] = len(masks)
-            masks.append((ec.eclip_mask_layout(256, 32, n_w, w, configs[c] // 32), w))
-    pool = ec.Pool(masks)
-    pipes = [pool.pipe(i) for i in range(1 + n_w, len(masks))]
-    assert len(set(pipes)) == len(pipes) or len(pipes) > 4, f"serving streams share a pipe: {pipes}"
-    for wk in workers:
-        wk.h.rebind(pool)
+    def serving_pool(assign):
+        masks = [(None, -1)] + [(None, w) for w in range(n_w)]
+        mask_id = {}
+        for w in range(n_w):
+            for c in sorted(set(assign[w])):
+                mask_id[(w, c)] = len(masks)
+                masks.append((ec.eclip_mask_layout(256, 32, n_w, w, configs[c] // 32), w))
+        pool = ec.Pool(masks)
+        pipes = [pool.pipe(i) for i in range(1 + n_w, len(masks))]
+        assert len(set(pipes)) == len(pipes) or len(pipes) > 4, f"serving streams share a pipe: {pipes}"
+        return pool, [[mask_id[(w, c)] for c in assign[w]] for w in range(n_w)]
+
+    trials = []
+    for name, a, sw in cand:
+        pool_c, table_c = serving_pool(a)
+        for wk, t in zip(workers, table_c):
+            wk.h.rebind(pool_c)
+            wk.h.alloc_set(t)
+        rate = None
+        if len(cand) > 1:
+            run_closed(workers, max(5, n_cal // 5))
+            dt, served = run_closed(workers, n_cal)
+            torch.cuda.synchronize()
+            rate = served / dt
+            log(f"trial, {name}: {rate:.0f} inf/s")
+        trials.append((rate, name, a, sw, pool_c, table_c))
     prof_pool.destroy()
+    best = max(range(len(trials)), key=lambda i: trials[i][0] or 0.0)
+    _, chosen, assign, switches, pool, eclip_table = trials[best]
+    if best != len(trials) - 1:                      # the workers are bound to the pool of the last trial
+        for wk in workers:
+            wk.h.rebind(pool)
+    for i, t in enumerate(trials):
+        if i != best:
+            t[4].destroy()
+    log(f"allocation ({chosen}) (CUs) {[[configs[c] for c in a] for a in assign]} switches {switches}")
     tables = {
-        "eclip": [[mask_id[(w, c)] for c in assign[w]] for w in range(n_w)],
+        "eclip": eclip_table,
         "unpart_a": [[0] * m.n_groups for m in models],
         "unpart_b": [[1 + w] * m.n_groups for w, m in enumerate(models)],
     }
@@ -798,7 +850,7 @@ def main():
         "config": {"workload": WORKLOADS[cfg] + f", CU-mask pool {configs} per worker, switchMax {args.switch_max}",
                    "policy": args.policy, "inflight_per_worker": args.depth,
                    "allocation_cus": [[configs[c] for c in a] for a in assign], "switches": switches,
-                   "max_configs_per_worker": max_configs, "switch_cost_ns": switch_cost_ns},
+                   "max_configs_per_worker": max_configs, "switch_cost_ns": switch_cost_ns, "overlap_slope": round(slope, 4), "allocation_from": chosen},
         "closed_loop": closed,
         "open_loop_poisson": open_res,
         "roofline": roofline,
