@@ -162,8 +162,11 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p
             if constexpr (NCHW) {
                 unsigned c[4];
 #pragma unroll
-                for (int ch = 0; ch < 4; ++ch)
+                for (int ch = 0; ch < 3; ++ch)
                     c[ch] = (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rx, (ok & (int)(ch < p.nchw_c)) ? a_off0[i] + tap_off + (unsigned)ch * plane : OOB, 0, 0) & 0xffffu;
+                c[3] = 0u;
+                if (p.nchw_c > 3)                      // uniform; RGB inputs skip the fourth load
+                    c[3] = (unsigned)__builtin_amdgcn_raw_buffer_load_b16(rx, ok ? a_off0[i] + tap_off + 3u * plane : OOB, 0, 0) & 0xffffu;
                 f.a[i] = make_uint4(c[0] | (c[1] << 16), c[2] | (c[3] << 16), 0u, 0u);
             } else {
                 const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? a_off0[i] + tap_off : OOB, 0, 0);
