@@ -518,6 +518,8 @@ def policies_mode(args):
     pool.destroy()
     note = " (every request at batch 1 in this mode)" if cfg == 3 else ""
     print(f"# {WORKLOADS[cfg]}{note}; closed loop, {args.depth} requests in flight per worker, {steps} steps; CU configurations {configs}")
+    print("# every kernel is a kernel group of its own in this mode (the unit of the paper's model), so kernels of different layers "
+          "never share a launch: absolute rates are below those of the default bench, which serves the stage groups")
     print(f"{'policy':98s} {'inf/s':>9s} {'ms/step':>8s} {'switches/request':>18s} {'streams':>7s} {'model us':>9s}")
     for r in rows:
         pu = "-" if r["predicted_us"] is None else f"{r['predicted_us']:.1f}"
