@@ -226,3 +226,28 @@ def test_pool_errors_before_any_device_call():
     with pytest.raises(ec.EclipError) as e:
         ec.Pool([([1], -1)] * 65)
     assert e.value.status == ec.ELIMIT
+
+
+# ---------------- bench.py command line (no GPU) ------------------------------------------------------------------------
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys, os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2", "--steps", "1", "--warmup", "0"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_traffic_file_is_tied_to_the_kernel_sources():
+    """The counted HBM traffic in the bench line is only reported while the kernel sources are the ones the counters
+    were taken on: the stored file carries their hash."""
+    import json, os, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    h = bench.source_hash()
+    assert len(h) == 64 and h == bench.source_hash()
+    path = bench.traffic_path(1)
+    if os.path.exists(path):
+        d = json.load(open(path))
+        assert set(("source_sha256", "kernels", "copy_scale_fetch", "copy_scale_write")) <= set(d)
+        assert d["kernels"]["conv_wsk_kernel"]["fetch_bytes_per_launch"] > 0
