@@ -233,7 +233,10 @@ def test_eltwise_and_embed(dt):
 # ---------------- attention -----------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dt", DTS)
 @pytest.mark.parametrize("seq,hidden,heads,batch", [(128, 768, 12, 1), (48, 128, 4, 2), (384, 256, 4, 2), (17, 64, 2, 3),
-                                                    (512, 64, 1, 1)])
+                                                    (512, 64, 1, 1),
+                                                    # beyond 256 keys the keys are staged in LDS: 128 queries per workgroup when
+                                                    # there are enough (batch, head) pairs, head size 32, a ragged length
+                                                    (384, 1024, 16, 3), (300, 128, 4, 2)])
 def test_attention(seq, hidden, heads, batch, dt):
     m = wl.single_layer("attention", dt, seed=seq, seq=seq, hidden=hidden, heads=heads)
     check(m, batch=batch, tol=6e-3)
