@@ -654,14 +654,16 @@ def main():
     slowdown = float(np.mean([s / max(c, 1e-9) for s, c in zip(solo_rate, co_rate)]))
     slope = min(1.0, max(0.02, (slowdown - 1.0) / max(1, n_w - 1)))
     alpha_ppm = [int(round(slope * (k * 32 / 256.0) * 1e6)) for k in range((n_w - 1) * 8 + 1)]
-    # Two candidate allocations: the model with the paper's slope (overlap = excess over the GPU, slope 1) and with the
-    # slope measured above.  When they differ, each serves a short closed-loop trial on its own serving pool and the
-    # faster one is kept: the (1 + alpha) law is coarse on this GPU either way (small kernels hardly interfere, a
+    # Candidate allocations: the model with the paper's slope (overlap = excess over the GPU, slope 1) and with the
+    # slope measured above, each also restricted to one configuration per worker (no switches).  When they differ, each
+    # serves a short closed-loop trial on its own serving pool and the fastest is kept: the (1 + alpha) law is coarse on this GPU either way (small kernels hardly interfere, a
     # switch costs more inside a pipelined request stream than in isolation), so the profile picks the candidates and a
     # measurement picks between them.
     cand = []
-    for name, kw in (("paper slope", {}), ("measured slope", {"overlap_mode": ec.OVERLAP_TABLE, "alpha_ppm": alpha_ppm, "granule": 32})):
-        a, _, sw = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, max_configs=max_configs, switch_cost_ns=switch_cost_ns, **kw)
+    table = {"overlap_mode": ec.OVERLAP_TABLE, "alpha_ppm": alpha_ppm, "granule": 32}
+    for name, kw, mc in (("paper slope", {}, max_configs), ("measured slope", table, max_configs),
+                         ("paper slope, one configuration per worker", {}, 1), ("measured slope, one configuration per worker", table, 1)):
+        a, _, sw = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, max_configs=mc, switch_cost_ns=switch_cost_ns, **kw)
         if not any(a == c[1] for c in cand):
             cand.append((name, a, sw))
     log(f"profiled in {time.perf_counter() - t0:.1f}s; switch cost {switch_cost_ns} ns; co-run slowdown {slowdown:.3f} -> "
