@@ -73,7 +73,8 @@ typedef struct {
 
 /* Create one HIP stream per mask on `device`.  All masks are applied here, once.
  * Errors: EINVAL (null pointers, n_masks == 0, a mask with no bit set, a bit at or above the
- * device's CU count, a mask that leaves one of the device's XCDs without a CU),
+ * device's CU count, a mask that leaves one of the device's XCDs without a CU -- the XCD count is read
+ * from the device, and when the runtime cannot report it every masked stream is refused with EHIP),
  * ELIMIT (n_masks > ECLIP_MAX_POOL_STREAMS), EHIP.  Validation that
  * needs no device (null, zero masks, empty mask, limit) happens before any HIP call. */
 eclip_status eclip_pool_create(int device, const eclip_mask *masks, uint32_t n_masks, eclip_pool **out);
@@ -218,11 +219,17 @@ eclip_status eclip_model_switches(const eclip_model *model, uint32_t *n_switches
  * until eclip_wait succeeds.  Returns at once; kernels of group g run on the stream named by the
  * table, and consecutive groups on different streams are ordered by an event.  Requests of one
  * model execute in submission order.  ESTATE before eclip_alloc_set; EINVAL batch == 0 or
- * > max_batch; ELIMIT more than max_inflight requests outstanding. */
+ * > max_batch; ELIMIT more than max_inflight requests outstanding.  EHIP when a launch fails part-way: the
+ * library then drains the device, drops the request (its slot stays free, nothing of it remains queued) and
+ * leaves earlier requests of the model waitable. */
 eclip_status eclip_submit(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out);
 
+/* Timestamps cost a marker packet at both ends of every request, so requests carry them only while this is on
+ * (off after load).  Takes effect for the next eclip_submit. */
+eclip_status eclip_model_timing(eclip_model *model, int enable);
+
 typedef struct {
-    uint64_t gpu_ns;       /* first kernel start to last kernel end, device clock */
+    uint64_t gpu_ns;       /* first kernel start to last kernel end, device clock; 0 unless eclip_model_timing was on at submit */
     uint32_t n_kernels;    /* kernels launched */
     uint32_t n_switches;   /* cross-stream dependencies inserted */
 } eclip_timing;
@@ -240,7 +247,16 @@ eclip_status eclip_wait(eclip_req *req, uint64_t timeout_ns, eclip_timing *opt_o
 eclip_status eclip_profile_group(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
                                  uint32_t iters, uint64_t *ns_per_kernel_out);
 
-/* Number of kernels in `group`. */
+/* The group as eclip_submit serves it (Sec. III-B: the allocator's beta of a unit): all launches of `group` in
+ * order on pool entry `mask_id` -- including the input re-layout in group 0, two independent layers sharing a
+ * launch, pool + classifier in one launch -- timed as one interval; median over `iters` samples in integer
+ * nanoseconds to *group_ns_out, and the number of kernels launched per pass to *n_launches_out (optional; the
+ * kernel count the allocator's CUAverage should weigh the unit with).  Same preconditions as
+ * eclip_profile_group. */
+eclip_status eclip_profile_group_served(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
+                                        uint32_t iters, uint64_t *group_ns_out, uint32_t *n_launches_out);
+
+/* Number of layers (kernels before any launch sharing) in `group`. */
 eclip_status eclip_model_group_size(const eclip_model *model, uint32_t group, uint32_t *n_kernels);
 
 /* How layer `layer` would be launched for `batch` samples on pool entry `mask_id`: which kernel and
@@ -321,8 +337,9 @@ eclip_status eclip_alloc_solve(const eclip_alloc_problem *problem, uint32_t *cfg
  *   same_stream_ns  all on pool entry mask_a (no repartitioning);
  *   pooled_ns       alternating between pool entries mask_a and mask_b, ordered by events
  *                   (switching through the pre-allocated pool);
- *   create_ns       every kernel on a stream created with words_b as CU mask for that kernel and
- *                   destroyed afterwards (applying the mask at run time).
+ *   create_ns       every kernel on a stream created with mask_b's CU mask for that kernel (applying the mask
+ *                   at run time): host time to create the stream and queue the dependent kernel on it; draining
+ *                   and destroying the previous stream is not counted.
  * Host pointers; any output may be NULL. */
 eclip_status eclip_bench_switch(eclip_pool *pool, uint32_t mask_a, uint32_t mask_b, uint32_t iters,
                                 double *same_stream_ns, double *pooled_ns, double *create_ns);

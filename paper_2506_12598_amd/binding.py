@@ -87,6 +87,9 @@ EXPORTS = {
     "eclip_model_group_size": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]),
     "eclip_model_kernel_info": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(eclip_kernel_info)]),
     "eclip_submit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
+    "eclip_model_timing": (C.c_int, [C.c_void_p, C.c_int]),
+    "eclip_profile_group_served": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                             C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]),
     "eclip_wait": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(eclip_timing)]),
     "eclip_profile_group": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                       C.POINTER(C.c_uint64)]),
@@ -260,6 +263,15 @@ class Model:
         r = C.c_void_p()
         check(lib.eclip_submit(self.handle, C.c_void_p(d_in), C.c_void_p(d_out), batch, C.byref(r)))
         return Request(r)
+
+    def timing(self, enable: bool):
+        check(lib.eclip_model_timing(self.handle, 1 if enable else 0))
+
+    def profile_group_served(self, group: int, mask_id: int, batch: int = 1, iters: int = 20) -> Tuple[int, int]:
+        """(group latency in ns as served, kernels launched per pass)."""
+        ns, n = C.c_uint64(), C.c_uint32()
+        check(lib.eclip_profile_group_served(self.handle, group, mask_id, batch, iters, C.byref(ns), C.byref(n)))
+        return ns.value, n.value
 
     def profile_group(self, group: int, mask_id: int, batch: int = 1, iters: int = 20) -> List[int]:
         n = self.group_size(group)

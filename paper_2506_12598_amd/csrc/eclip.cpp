@@ -108,16 +108,26 @@ extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, u
                 if ((masks[i].words[wd] >> b & 1u) && wd * 32 + b >= cus)
                     return fail(ECLIP_EINVAL, "mask %u enables CU %u but the device has %u", i, wd * 32 + b, cus);
     // Consecutive mask bits rotate over the device's XCDs (bit i belongs to XCD i % n_xcc); the runtime does
-    // not survive a queue mask that leaves an XCD without any CU, so such masks are refused here.
-    uint32_t n_xcc = (cus == 256) ? 8u : 1u;
-    if (const char *ev = getenv("ECLIP_NUM_XCC")) n_xcc = (uint32_t)std::max(1, atoi(ev));
-    for (uint32_t i = 0; i < n_masks; ++i) {
-        if (masks[i].n_words == 0) continue;
-        std::vector<uint32_t> per(n_xcc, 0u);
-        for (uint32_t b = 0; b < masks[i].n_words * 32; ++b)
-            if (masks[i].words[b / 32] >> (b % 32) & 1u) per[b % n_xcc]++;
-        for (uint32_t x = 0; x < n_xcc; ++x)
-            if (per[x] == 0) return fail(ECLIP_EINVAL, "mask %u leaves XCD %u (mask bits congruent to %u modulo %u) without a CU", i, x, x, n_xcc);
+    // not survive a queue mask that leaves an XCD without any CU, so such masks are refused here.  The XCD count
+    // comes from the device; when the runtime cannot tell it, masked streams are refused altogether.
+    bool any_masked = false;
+    for (uint32_t i = 0; i < n_masks; ++i) any_masked |= masks[i].n_words != 0;
+    if (any_masked) {
+        int xcc = 0;
+        const hipError_t xe = hipDeviceGetAttribute(&xcc, hipDeviceAttributeNumberOfXccs, device);
+        if (xe != hipSuccess || xcc < 1 || cus % (uint32_t)xcc)
+            return fail(ECLIP_EHIP, "cannot read the XCD count of device %d (%s, value %d): CU-masked streams are refused", device,
+                        hipGetErrorString(xe), xcc);
+        const uint32_t n_xcc = (uint32_t)xcc;
+        TRACE("device %d: %u XCDs", device, n_xcc);
+        for (uint32_t i = 0; i < n_masks; ++i) {
+            if (masks[i].n_words == 0) continue;
+            std::vector<uint32_t> per(n_xcc, 0u);
+            for (uint32_t b = 0; b < masks[i].n_words * 32; ++b)
+                if (masks[i].words[b / 32] >> (b % 32) & 1u) per[b % n_xcc]++;
+            for (uint32_t x = 0; x < n_xcc; ++x)
+                if (per[x] == 0) return fail(ECLIP_EINVAL, "mask %u leaves XCD %u (mask bits congruent to %u modulo %u) without a CU", i, x, x, n_xcc);
+        }
     }
     HIP_TRY(attention_init());
     HIP_TRY(conv_gemm_init());
@@ -296,8 +306,9 @@ struct LayerPlan {
 
 struct eclip_req {
     eclip_model *model = nullptr;
-    hipEvent_t start = nullptr, done = nullptr;
-    bool pending = false;
+    hipEvent_t done = nullptr;                       // completion only (no timestamps): what eclip_wait blocks on
+    hipEvent_t t_start = nullptr, t_done = nullptr;  // timestamped pair, recorded only while the model's timing is on
+    bool pending = false, timed = false;
     uint32_t n_kernels = 0, n_switches = 0;
 };
 
@@ -318,7 +329,9 @@ struct eclip_model {
     char *d_act = nullptr;
     char *d_in_stage = nullptr;    // channels-last copy of an IMAGE input
     float *d_ws = nullptr;
+    float *ws = nullptr;           // workspace the launches use (d_ws)
     size_t ws_floats = 0;
+    bool timing = false;           // requests record timing events (eclip_model_timing)
     void *d_self_in = nullptr;     // zero input / scratch output for profiling
     float *d_self_out = nullptr;
 
@@ -352,8 +365,9 @@ static void free_model(eclip_model *m)
     (void)hipFree(m->d_self_in);
     (void)hipFree(m->d_self_out);
     for (eclip_req &r : m->reqs) {
-        if (r.start) (void)hipEventDestroy(r.start);
         if (r.done) (void)hipEventDestroy(r.done);
+        if (r.t_start) (void)hipEventDestroy(r.t_start);
+        if (r.t_done) (void)hipEventDestroy(r.t_done);
     }
     for (hipEvent_t e : m->switch_events)
         if (e) (void)hipEventDestroy(e);
@@ -736,6 +750,7 @@ extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_des
     }
     m->ws_floats = std::min<size_t>(ws, (size_t)16 << 20);
     LOAD_TRY(hipMalloc((void **)&m->d_ws, std::max<size_t>(m->ws_floats * 4, 256)));
+    m->ws = m->d_ws;
 
     // ---- profiling buffers, requests, events
     const size_t in_bytes = in_elems(m) * m->max_batch * (size_t)(m->in_kind == ECLIP_IN_TOKENS ? 4 : es);
@@ -745,8 +760,9 @@ extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_des
     m->reqs.resize(desc->max_inflight);
     for (eclip_req &r : m->reqs) {
         r.model = m;
-        LOAD_TRY(hipEventCreate(&r.start));
-        LOAD_TRY(hipEventCreate(&r.done));
+        LOAD_TRY(hipEventCreateWithFlags(&r.done, hipEventDisableTiming));
+        LOAD_TRY(hipEventCreate(&r.t_start));
+        LOAD_TRY(hipEventCreate(&r.t_done));
     }
     m->switch_events.assign(m->n_groups, nullptr);
     for (hipEvent_t &e : m->switch_events) LOAD_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -918,7 +934,7 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
         const GemmShape g = gemm_shape(P, batch);
         if (P.gemm) {
             if (d_out32 && chan_last_out) y32 = d_out32;
-            ConvGemmArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y32 ? nullptr : y, y32, m->d_ws,
+            ConvGemmArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y32 ? nullptr : y, y32, m->ws,
                            g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, dt};
             const GemmPlan pl = conv_gemm_plan((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats);
             *n_launched -= 1;
@@ -947,7 +963,7 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
     case ECLIP_OP_GAP:
         if (d_out32) y32 = d_out32;
         *n_launched -= 1;
-        e = launch_gap(src(L.in0), y, y32, m->d_ws, m->ws_floats, batch, P.in.h * P.in.w, L.c, dt, n_cu, s, n_launched);
+        e = launch_gap(src(L.in0), y, y32, m->ws, m->ws_floats, batch, P.in.h * P.in.w, L.c, dt, n_cu, s, n_launched);
         break;
     case ECLIP_OP_LAYERNORM:
     case ECLIP_OP_SOFTMAX: {
@@ -1005,7 +1021,7 @@ static hipError_t launch_pair(eclip_model *m, uint32_t i, int batch, hipStream_t
             return (const void *)(m->d_act + m->layers[idx].out_off);
         };
         const GemmShape g = gemm_shape(P, batch);
-        a[k] = ConvGemmArgs{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), m->d_act + P.out_off, nullptr, m->d_ws,
+        a[k] = ConvGemmArgs{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), m->d_act + P.out_off, nullptr, m->ws,
                             g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, m->dtype};
         mnk[k][0] = (long)g.B * g.Ho * g.Wo; mnk[k][1] = g.Cout; mnk[k][2] = (long)g.KH * g.KW * g.Cin;
         own[k] = conv_gemm_plan(mnk[k][0], mnk[k][1], mnk[k][2], n_cu, m->ws_floats);
@@ -1039,7 +1055,7 @@ static hipError_t launch_stem_direct(eclip_model *m, int batch, hipStream_t s, i
     const GemmShape g = gemm_shape(P, batch);
     GemmPlan pl;
     if (!conv_gemm_plan_stem((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats, 2.0, &pl)) return hipSuccess;
-    ConvGemmArgs a{d_in, wptr(m, P.w_dev), wptr(m, P.b_dev), nullptr, m->d_act + P.out_off, nullptr, m->d_ws,
+    ConvGemmArgs a{d_in, wptr(m, P.w_dev), wptr(m, P.b_dev), nullptr, m->d_act + P.out_off, nullptr, m->ws,
                    g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, P.L.act, m->dtype};
     a.nchw_c = m->in_c;
     *done = true;
@@ -1053,13 +1069,40 @@ static hipError_t launch_input_stage(eclip_model *m, int batch, const void *d_in
     return launch_nchw_to_nhwc(d_in, m->d_in_stage, batch, m->in_c, m->in_h, m->in_w, m->in_cp, m->dtype, s);
 }
 
-extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out)
+// One launch unit of the served path, starting at layer i: the first layer together with the input re-layout it needs
+// (or reading the caller's tensor itself), two independent matrix-core layers in one launch, pool + classifier in one
+// launch, or a single layer.  *consumed receives the number of layers the unit covered.  eclip_submit and the profiler
+// both walk a model through this function, so what is profiled is what is served.
+static hipError_t launch_unit(eclip_model *m, uint32_t i, int batch, hipStream_t s, int n_cu, const void *d_in, float *d_out,
+                              uint32_t *n_launched, uint32_t *consumed)
 {
-    if (!model || !out) return fail(ECLIP_EINVAL, "null argument");
-    *out = nullptr;
-    if (!d_in || !d_out) return fail(ECLIP_EINVAL, "null device buffer");
-    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
-    std::lock_guard<std::mutex> lk(model->mu);
+    const uint32_t n_layers = (uint32_t)m->layers.size();
+    hipError_t e;
+    *consumed = 1;
+    if (i == 0) {
+        bool stem_done = false;
+        if (m->stem_direct) {
+            if ((e = launch_stem_direct(m, batch, s, n_cu, d_in, n_launched, &stem_done)) != hipSuccess) return e;
+            if (stem_done) return hipSuccess;
+        }
+        if ((e = launch_input_stage(m, batch, d_in, s, n_launched)) != hipSuccess) return e;
+    }
+    if (m->layers[i].pair_next) {
+        bool paired = false;
+        if ((e = launch_pair(m, i, batch, s, n_cu, d_in, n_launched, &paired)) != hipSuccess) return e;
+        if (paired) { *consumed = 2; return hipSuccess; }
+    }
+    if (m->layers[i].gapfc_next) {
+        bool fused = false;
+        if ((e = launch_gapfc_pair(m, i, batch, s, d_in, i + 2 == n_layers ? d_out : nullptr, n_launched, &fused)) != hipSuccess) return e;
+        if (fused) { *consumed = 2; return hipSuccess; }
+    }
+    return launch_layer(m, i, batch, s, n_cu, d_in, i + 1 == n_layers ? d_out : nullptr, n_launched);
+}
+
+// The body of eclip_submit, with the model's mutex held.
+static eclip_status submit_locked(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out)
+{
     if (!model->has_alloc) return fail(ECLIP_ESTATE, "eclip_alloc_set has not been called");
     eclip_req *r = nullptr;
     for (eclip_req &q : model->reqs)
@@ -1070,46 +1113,71 @@ extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void 
 
     const uint32_t n_layers = (uint32_t)model->layers.size();
     hipStream_t cur = pool->streams[model->mask_of_group[0]].stream;
-    // requests of one model run in order: the first kernel waits for the previous request when that
-    // one ended on another stream (on the same stream, queue order already serialises them)
-    if (model->last_done && model->last_stream != cur) HIP_TRY(hipStreamWaitEvent(cur, model->last_done, 0));
-    HIP_TRY(hipEventRecord(r->start, cur));
     r->n_kernels = 0;
     r->n_switches = 0;
-    bool stem_done = false;
-    if (model->stem_direct)
-        HIP_TRY(launch_stem_direct(model, (int)batch, cur, (int)pool->streams[model->mask_of_group[0]].n_cu, d_in, &r->n_kernels, &stem_done));
-    if (!stem_done) HIP_TRY(launch_input_stage(model, (int)batch, d_in, cur, &r->n_kernels));
+    r->timed = model->timing;
+    // Once the first call below has been made, a failure leaves work queued that this request can no longer account
+    // for: the device is drained, the chain to the previous request is dropped (nothing is outstanding after the
+    // drain, and earlier requests keep their own completion events), the slot stays free, and the caller gets EHIP.
+    hipError_t e = hipSuccess;
+    const char *what = "";
+#define SUB_TRY(call)                                                          \
+    do {                                                                       \
+        if (e == hipSuccess && (e = (call)) != hipSuccess) what = #call;       \
+    } while (0)
+    // requests of one model run in order: the first kernel waits for the previous request when that
+    // one ended on another stream (on the same stream, queue order already serialises them)
+    if (model->last_done && model->last_stream != cur) SUB_TRY(hipStreamWaitEvent(cur, model->last_done, 0));
+    if (r->timed) SUB_TRY(hipEventRecord(r->t_start, cur));
     uint32_t prev_group = 0;
-    for (uint32_t i = stem_done ? 1 : 0; i < n_layers; ++i) {
+    for (uint32_t i = 0; i < n_layers && e == hipSuccess;) {
         const uint32_t g = model->group_of_layer[i];
         const PoolStream &ps = pool->streams[model->mask_of_group[g]];
         if (g != prev_group && ps.stream != cur) {
             // group boundary that changes stream: the next group waits for everything queued so far
-            HIP_TRY(hipEventRecord(model->switch_events[g], cur));
-            HIP_TRY(hipStreamWaitEvent(ps.stream, model->switch_events[g], 0));
+            SUB_TRY(hipEventRecord(model->switch_events[g], cur));
+            SUB_TRY(hipStreamWaitEvent(ps.stream, model->switch_events[g], 0));
             cur = ps.stream;
             r->n_switches++;
         }
         prev_group = g;
-        if (model->layers[i].pair_next) {
-            bool paired = false;
-            HIP_TRY(launch_pair(model, i, (int)batch, cur, (int)ps.n_cu, d_in, &r->n_kernels, &paired));
-            if (paired) { ++i; continue; }
-        }
-        if (model->layers[i].gapfc_next) {
-            bool fused = false;
-            HIP_TRY(launch_gapfc_pair(model, i, (int)batch, cur, d_in, i + 2 == n_layers ? (float *)d_out : nullptr, &r->n_kernels, &fused));
-            if (fused) { ++i; continue; }
-        }
-        HIP_TRY(launch_layer(model, i, (int)batch, cur, (int)ps.n_cu, d_in, i + 1 == n_layers ? (float *)d_out : nullptr, &r->n_kernels));
+        uint32_t consumed = 1;
+        SUB_TRY(launch_unit(model, i, (int)batch, cur, (int)ps.n_cu, d_in, (float *)d_out, &r->n_kernels, &consumed));
+        i += consumed;
     }
-    HIP_TRY(hipEventRecord(r->done, cur));
+    if (r->timed) SUB_TRY(hipEventRecord(r->t_done, cur));
+    SUB_TRY(hipEventRecord(r->done, cur));
+#undef SUB_TRY
+    if (e != hipSuccess) {
+        (void)hipDeviceSynchronize();
+        (void)hipGetLastError();
+        model->last_done = nullptr;
+        model->last_stream = nullptr;
+        return fail(ECLIP_EHIP, "%s failed: %s; the device was drained and the request dropped", what, hipGetErrorString(e));
+    }
     r->pending = true;
     model->inflight++;
     model->last_done = r->done;
     model->last_stream = cur;
     *out = r;
+    return ECLIP_OK;
+}
+
+extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out)
+{
+    if (!model || !out) return fail(ECLIP_EINVAL, "null argument");
+    *out = nullptr;
+    if (!d_in || !d_out) return fail(ECLIP_EINVAL, "null device buffer");
+    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
+    std::lock_guard<std::mutex> lk(model->mu);
+    return submit_locked(model, d_in, d_out, batch, out);
+}
+
+extern "C" eclip_status eclip_model_timing(eclip_model *model, int enable)
+{
+    if (!model) return fail(ECLIP_EINVAL, "model is null");
+    std::lock_guard<std::mutex> lk(model->mu);
+    model->timing = enable != 0;
     return ECLIP_OK;
 }
 
@@ -1131,16 +1199,41 @@ extern "C" eclip_status eclip_wait(eclip_req *req, uint64_t timeout_ns, eclip_ti
         }
     }
     if (opt_out) {
-        float ms = 0.0f;
-        HIP_TRY(hipEventElapsedTime(&ms, req->start, req->done));
-        opt_out->gpu_ns = (uint64_t)((double)ms * 1e6);
+        opt_out->gpu_ns = 0;
+        if (req->timed) {
+            float ms = 0.0f;
+            HIP_TRY(hipEventElapsedTime(&ms, req->t_start, req->t_done));
+            opt_out->gpu_ns = (uint64_t)((double)ms * 1e6);
+        }
         opt_out->n_kernels = req->n_kernels;
         opt_out->n_switches = req->n_switches;
     }
     std::lock_guard<std::mutex> lk(m->mu);
     req->pending = false;
     m->inflight--;
-    if (m->last_done == req->done && m->inflight == 0) { /* keep last_done: the event stays valid and signalled */ }
+    return ECLIP_OK;
+}
+
+// Shared front end of the two profilers: argument checks, the lock, and one untimed pass of the whole model through
+// the served launch sequence so that every activation buffer holds finite data.
+static eclip_status profile_prepare(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch, uint32_t iters)
+{
+    if (group >= model->n_groups) return fail(ECLIP_EINVAL, "unknown group %u", group);
+    if (mask_id >= model->pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
+    if (iters == 0 || iters > 10000) return fail(ECLIP_EINVAL, "iters must be 1..10000");
+    if (model->inflight) return fail(ECLIP_ESTATE, "requests in flight");
+    eclip_pool *pool = model->pool;
+    HIP_TRY(hipSetDevice(pool->device));
+    const PoolStream &ps = pool->streams[mask_id];
+    const uint32_t n_layers = (uint32_t)model->layers.size();
+    uint32_t dummy = 0;
+    for (uint32_t i = 0; i < n_layers;) {
+        uint32_t consumed = 1;
+        HIP_TRY(launch_unit(model, i, (int)batch, ps.stream, (int)ps.n_cu, model->d_self_in, model->d_self_out, &dummy, &consumed));
+        i += consumed;
+    }
+    HIP_TRY(hipStreamSynchronize(ps.stream));
     return ECLIP_OK;
 }
 
@@ -1148,28 +1241,17 @@ extern "C" eclip_status eclip_profile_group(eclip_model *model, uint32_t group, 
                                             uint32_t iters, uint64_t *ns_per_kernel_out)
 {
     if (!model || !ns_per_kernel_out) return fail(ECLIP_EINVAL, "null argument");
-    if (group >= model->n_groups) return fail(ECLIP_EINVAL, "unknown group %u", group);
-    if (mask_id >= model->pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
-    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
-    if (iters == 0 || iters > 10000) return fail(ECLIP_EINVAL, "iters must be 1..10000");
     std::lock_guard<std::mutex> lk(model->mu);
-    if (model->inflight) return fail(ECLIP_ESTATE, "requests in flight");
-    eclip_pool *pool = model->pool;
-    HIP_TRY(hipSetDevice(pool->device));
-    const PoolStream &ps = pool->streams[mask_id];
+    eclip_status st = profile_prepare(model, group, mask_id, batch, iters);
+    if (st != ECLIP_OK) return st;
+    const PoolStream &ps = model->pool->streams[mask_id];
     const uint32_t n_layers = (uint32_t)model->layers.size();
     uint32_t dummy = 0;
-    // untimed full pass so that every activation buffer holds finite data
-    HIP_TRY(launch_input_stage(model, (int)batch, model->d_self_in, ps.stream, &dummy));
-    for (uint32_t i = 0; i < n_layers; ++i)
-        HIP_TRY(launch_layer(model, i, (int)batch, ps.stream, (int)ps.n_cu, model->d_self_in, i + 1 == n_layers ? model->d_self_out : nullptr, &dummy));
-    HIP_TRY(hipStreamSynchronize(ps.stream));
     std::vector<uint32_t> idx;
     for (uint32_t i = 0; i < n_layers; ++i)
         if (model->group_of_layer[i] == group) idx.push_back(i);
     const size_t nk = idx.size();
     std::vector<hipEvent_t> ev(2 * nk, nullptr);
-    eclip_status st = ECLIP_OK;
     for (hipEvent_t &e : ev)
         if (hipEventCreate(&e) != hipSuccess) st = fail(ECLIP_EHIP, "hipEventCreate failed");
     std::vector<std::vector<float>> samples(nk);
@@ -1205,6 +1287,51 @@ extern "C" eclip_status eclip_profile_group(eclip_model *model, uint32_t group, 
     return ECLIP_OK;
 }
 
+extern "C" eclip_status eclip_profile_group_served(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
+                                                   uint32_t iters, uint64_t *group_ns_out, uint32_t *n_launches_out)
+{
+    if (!model || !group_ns_out) return fail(ECLIP_EINVAL, "null argument");
+    std::lock_guard<std::mutex> lk(model->mu);
+    eclip_status st = profile_prepare(model, group, mask_id, batch, iters);
+    if (st != ECLIP_OK) return st;
+    const PoolStream &ps = model->pool->streams[mask_id];
+    const uint32_t n_layers = (uint32_t)model->layers.size();
+    uint32_t first = n_layers, last = 0;
+    for (uint32_t i = 0; i < n_layers; ++i)
+        if (model->group_of_layer[i] == group) { first = std::min(first, i); last = i; }
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    if (hipEventCreate(&ev[0]) != hipSuccess || hipEventCreate(&ev[1]) != hipSuccess) st = fail(ECLIP_EHIP, "hipEventCreate failed");
+    std::vector<float> samples;
+    uint32_t launches = 0;
+    // the group's launch units in order, as eclip_submit issues them (pairs never straddle a group boundary), twice
+    // back to back per sample so that the two event markers weigh less against a short group
+    const uint32_t REPS = 2;
+    for (uint32_t it = 0; it < iters + 2 && st == ECLIP_OK; ++it) {       // two warm-up rounds
+        hipError_t e = hipEventRecord(ev[0], ps.stream);
+        launches = 0;
+        for (uint32_t r = 0; r < REPS && e == hipSuccess; ++r)
+            for (uint32_t i = first; i <= last && e == hipSuccess;) {
+                uint32_t consumed = 1;
+                e = launch_unit(model, i, (int)batch, ps.stream, (int)ps.n_cu, model->d_self_in, model->d_self_out, &launches, &consumed);
+                i += consumed;
+            }
+        if (e == hipSuccess) e = hipEventRecord(ev[1], ps.stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(ps.stream);
+        if (e != hipSuccess) { st = fail(ECLIP_EHIP, "profiling launch failed: %s", hipGetErrorString(e)); break; }
+        if (it < 2) continue;
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ev[0], ev[1]) != hipSuccess) { st = fail(ECLIP_EHIP, "hipEventElapsedTime failed"); break; }
+        samples.push_back(ms / (float)REPS);
+    }
+    for (hipEvent_t e : ev)
+        if (e) (void)hipEventDestroy(e);
+    if (st != ECLIP_OK) return st;
+    std::sort(samples.begin(), samples.end());
+    *group_ns_out = (uint64_t)std::llround((double)samples[samples.size() / 2] * 1e6);
+    if (n_launches_out) *n_launches_out = launches / REPS;
+    return ECLIP_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // allocator entry point
 // ------------------------------------------------------------------------------------------------
@@ -1237,6 +1364,7 @@ extern "C" eclip_status eclip_bench_switch(eclip_pool *pool, uint32_t mask_a, ui
     HIP_TRY(hipMalloc(&d, 256));
     HIP_TRY(hipMemset(d, 0, 256));
     hipEvent_t ev[2] = {nullptr, nullptr};
+    hipStream_t prev = nullptr, fresh = nullptr;     // streams of leg (3), destroyed at `done` whatever happens
     eclip_status st = ECLIP_OK;
     auto now = [] { return std::chrono::steady_clock::now(); };
     auto ns = [](std::chrono::steady_clock::time_point a, std::chrono::steady_clock::time_point b) {
@@ -1282,26 +1410,30 @@ extern "C" eclip_status eclip_bench_switch(eclip_pool *pool, uint32_t mask_a, ui
                 for (uint32_t c = 0; c < pool->device_cus; ++c) all_words[c / 32] |= 1u << (c % 32);
                 words = &all_words;
             }
-            hipStream_t prev = nullptr;
-            t0 = now();
+            // Timed: creating the masked stream and queueing the dependent kernel on it -- what applying a mask at run
+            // time adds to a launch.  Draining and destroying the previous stream happen outside the accumulated
+            // interval: that is teardown, not repartitioning.
+            double acc = 0.0;
             for (uint32_t i = 0; i < n; ++i) {
-                hipStream_t sN = nullptr;
-                B_TRY(hipExtStreamCreateWithCUMask(&sN, (uint32_t)words->size(), words->data()));
-                if (prev) {
-                    B_TRY(hipEventRecord(ev[0], prev));
-                    B_TRY(hipStreamWaitEvent(sN, ev[0], 0));
-                }
-                B_TRY(launch_tick(d, sN));
+                t0 = now();
+                B_TRY(hipExtStreamCreateWithCUMask(&fresh, (uint32_t)words->size(), words->data()));
+                if (prev) B_TRY(hipStreamWaitEvent(fresh, ev[0], 0));
+                B_TRY(launch_tick(d, fresh));
+                B_TRY(hipEventRecord(ev[0], fresh));
+                t1 = now();
+                acc += ns(t0, t1);
                 if (prev) { B_TRY(hipStreamSynchronize(prev)); B_TRY(hipStreamDestroy(prev)); }
-                prev = sN;
+                prev = fresh;
+                fresh = nullptr;
             }
-            if (prev) { B_TRY(hipStreamSynchronize(prev)); B_TRY(hipStreamDestroy(prev)); }
-            t1 = now();
-            *create_ns = ns(t0, t1) / n;
+            B_TRY(hipStreamSynchronize(prev));
+            *create_ns = acc / n;
         }
     }
 done:
 #undef B_TRY
+    if (fresh) { (void)hipStreamSynchronize(fresh); (void)hipStreamDestroy(fresh); }
+    if (prev) { (void)hipStreamSynchronize(prev); (void)hipStreamDestroy(prev); }
     if (ev[0]) (void)hipEventDestroy(ev[0]);
     if (ev[1]) (void)hipEventDestroy(ev[1]);
     (void)hipDeviceSynchronize();

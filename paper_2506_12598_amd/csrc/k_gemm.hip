@@ -51,8 +51,7 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
         // that is not unrolled, to keep it out of the way.
         static_assert(TM % 2 == 0, "32 rows per pass");
         constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
-        constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass
-        static_assert(32 % RPP == 0 || RPP > 32, "whole passes per 32 rows");
+        constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass (lanes beyond RPP * LPR idle)
         constexpr int PASSES = (32 + RPP - 1) / RPP;
         __syncthreads();
         float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
@@ -73,7 +72,7 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
             auto pass = [&](int ps) {
                 const int rr = ps * RPP + rr0;
                 const int m = m_base + wm * (BM / WM) + h * 32 + rr;
-                if (rr < 32 && m < p.M && n < p.N) {
+                if (lane < RPP * LPR && rr < 32 && m < p.M && n < p.N) {
                     const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
                     const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
                     float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
@@ -437,9 +436,18 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
 }
 
 struct Variant { int bm, bn, bk; };
-constexpr Variant kVariants[CONV_GEMM_VARIANTS] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}, {128, 256, 64}};
+constexpr Variant kVariants[CONV_GEMM_VARIANTS] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}, {128, 256, 64},
+                                                   {192, 128, 32}, {192, 128, 64}, {128, 128, 64}, {256, 128, 32}, {192, 256, 32},
+                                                   {256, 192, 32}, {64, 128, 64}, {128, 64, 64}};
 
-constexpr size_t lds_bytes(int bm, int bn, int bk, int pad = 8) { return (size_t)2 * (bm + bn) * (bk + pad) * 2; }
+// LDS of a workgroup: the two-slot operand ring, or the epilogue's staging buffers when those are larger (8 wavefronts
+// x 32 rows x (columns of a wavefront + 4) floats on the ping-pong tiles)
+constexpr size_t lds_bytes(int bm, int bn, int bk, int pad = 8)
+{
+    const size_t ring = (size_t)2 * (bm + bn) * (bk + pad) * 2;
+    const size_t stage = pad == 16 ? (size_t)8 * 32 * (bn / 4 + 4) * 4 : 0;
+    return ring > stage ? ring : stage;
+}
 
 template <typename T>
 hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
@@ -449,8 +457,18 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
     case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, dim3(256), lds_bytes(128, 128, 32), s, d); break;
     case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, dim3(256), lds_bytes(64, 64, 64), s, d); break;
     case 2: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, dim3(256), lds_bytes(32, 64, 64), s, d); break;
-    case 3: hipLaunchKernelGGL((conv_gemm_kernel<T, 256, 256, 32, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(256, 256, 32, 16), s, d); break;
-    default: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 256, 64, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(128, 256, 64, 16), s, d); break;
+#define PP(BM, BN, BK) hipLaunchKernelGGL((conv_gemm_kernel<T, BM, BN, BK, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(BM, BN, BK, 16), s, d)
+    case 3: PP(256, 256, 32); break;
+    case 4: PP(128, 256, 64); break;
+    case 5: PP(192, 128, 32); break;
+    case 6: PP(192, 128, 64); break;
+    case 7: PP(128, 128, 64); break;
+    case 8: PP(256, 128, 32); break;
+    case 9: PP(192, 256, 32); break;
+    case 10: PP(256, 192, 32); break;
+    case 11: PP(64, 128, 64); break;
+    default: PP(128, 64, 64); break;
+#undef PP
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.splits == 1) return e;
@@ -469,7 +487,10 @@ hipError_t conv_gemm_init()
     if ((e = hipFuncSetAttribute((const void *)conv_gemm_kernel<T, BM, BN, BK, 2, 4, 2, LOOP_PINGPONG>,                      \
                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(BM, BN, BK, 16))) != hipSuccess) \
         return e;
-    SET(bf16_t, 256, 256, 32) SET(f16_t, 256, 256, 32) SET(bf16_t, 128, 256, 64) SET(f16_t, 128, 256, 64)
+#define SET2(BM, BN, BK) SET(bf16_t, BM, BN, BK) SET(f16_t, BM, BN, BK)
+    SET2(256, 256, 32) SET2(128, 256, 64) SET2(192, 128, 32) SET2(192, 128, 64) SET2(128, 128, 64) SET2(256, 128, 32)
+    SET2(192, 256, 32) SET2(256, 192, 32) SET2(64, 128, 64) SET2(128, 64, 64)
+#undef SET2
 #undef SET
     return hipSuccess;
 }

@@ -41,6 +41,7 @@ class GpuModel:
         if table is not None:
             self.h.alloc_set(table)
         batch = x.shape[0]
+        self.h.timing(timing)
         d_in = dev_input(self.model, x)
         out = torch.full(self.model.out_shape(batch), float("nan"), dtype=torch.float32, device="cuda")
         req = self.h.submit(d_in.data_ptr(), out.data_ptr(), batch)
