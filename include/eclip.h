@@ -224,6 +224,20 @@ eclip_status eclip_model_switches(const eclip_model *model, uint32_t *n_switches
  * leaves earlier requests of the model waitable. */
 eclip_status eclip_submit(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out);
 
+/* The same request with every kernel's scratch memory (the partial sums of K slices and of the global average
+ * pool) in a static device array of ECLIP_STATIC_SCRATCH_BYTES that the library holds on each GPU it has a pool
+ * on, instead of the workspace eclip_model_load allocated.  For callers that must not allocate device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The call itself allocates
+ * nothing, on the host side of the runtime or on the device.  Arguments, ordering and results are those of
+ * eclip_submit (bit for bit: the kernels and their plans are the same).  Every call on a GPU shares that GPU's
+ * array, whose content is whatever the last call left (every kernel writes its partial sums before reading
+ * them, so nothing has to be cleared): requests issued through this call on different models of one GPU must not
+ * overlap in time -- wait for one before submitting the next -- or they race on the array.
+ * ELIMIT: the model's kernels need more scratch than the array holds (the need is fixed at load: it grows with
+ * max_batch); otherwise the errors of eclip_submit. */
+#define ECLIP_STATIC_SCRATCH_BYTES (16u << 20)
+eclip_status eclip_submit_static(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out);
+
 /* Timestamps cost a marker packet at both ends of every request, so requests carry them only while this is on
  * (off after load).  Takes effect for the next eclip_submit. */
 eclip_status eclip_model_timing(eclip_model *model, int enable);

@@ -87,6 +87,7 @@ EXPORTS = {
     "eclip_model_group_size": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]),
     "eclip_model_kernel_info": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(eclip_kernel_info)]),
     "eclip_submit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
+    "eclip_submit_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
     "eclip_model_timing": (C.c_int, [C.c_void_p, C.c_int]),
     "eclip_profile_group_served": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                              C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]),
@@ -262,6 +263,11 @@ class Model:
         """d_in / d_out are device addresses (e.g. torch tensor .data_ptr())."""
         r = C.c_void_p()
         check(lib.eclip_submit(self.handle, C.c_void_p(d_in), C.c_void_p(d_out), batch, C.byref(r)))
+        return Request(r)
+
+    def submit_static(self, d_in: int, d_out: int, batch: int) -> Request:
+        r = C.c_void_p()
+        check(lib.eclip_submit_static(self.handle, C.c_void_p(d_in), C.c_void_p(d_out), batch, C.byref(r)))
         return Request(r)
 
     def timing(self, enable: bool):

@@ -70,6 +70,7 @@ struct eclip_pool {
     int device = 0;
     uint32_t device_cus = 0;
     std::vector<PoolStream> streams;
+    void *scratch = nullptr;             // this device's static scratch (eclip_submit_static)
     int n_models = 0;
     std::mutex mu;
 };
@@ -79,6 +80,31 @@ static uint32_t popcount_words(const uint32_t *w, uint32_t n)
     uint32_t c = 0;
     for (uint32_t i = 0; i < n; ++i) c += (uint32_t)__builtin_popcount(w[i]);
     return c;
+}
+
+// Scratch for eclip_submit_static: the K-slice partial sums of the matrix-core kernels and the partial sums of the
+// global average pool go here instead of the workspace eclip_model_load allocated.  One array per GPU, held until the
+// process ends.  In host code this name only stands for the symbol: its device address is looked up once per device in
+// eclip_pool_create (static_scratch_of) and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[ECLIP_STATIC_SCRATCH_BYTES];
+
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[64] = {nullptr};
+
+// Address of `scratch` on `device` (which must be the current device), looked up on first use.
+static hipError_t static_scratch_of(int device, void **ptr)
+{
+    if (device < 0 || device >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *ptr = g_scratch_ptr[device];
+    return hipSuccess;
 }
 
 extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, uint32_t n_masks, eclip_pool **out)
@@ -129,6 +155,8 @@ extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, u
                 if (per[x] == 0) return fail(ECLIP_EINVAL, "mask %u leaves XCD %u (mask bits congruent to %u modulo %u) without a CU", i, x, x, n_xcc);
         }
     }
+    void *scratch_ptr = nullptr;
+    HIP_TRY(static_scratch_of(device, &scratch_ptr));
     HIP_TRY(attention_init());
     HIP_TRY(conv_gemm_init());
     HIP_TRY(conv_wsk_init());
@@ -137,6 +165,7 @@ extern "C" eclip_status eclip_pool_create(int device, const eclip_mask *masks, u
     if (!p) return fail(ECLIP_ENOMEM, "out of host memory");
     p->device = device;
     p->device_cus = cus;
+    p->scratch = scratch_ptr;
     p->streams.resize(n_masks);
     uint32_t n_masked = 0;
     for (uint32_t i = 0; i < n_masks; ++i) {
@@ -329,7 +358,8 @@ struct eclip_model {
     char *d_act = nullptr;
     char *d_in_stage = nullptr;    // channels-last copy of an IMAGE input
     float *d_ws = nullptr;
-    float *ws = nullptr;           // workspace the launches use (d_ws)
+    float *ws = nullptr;           // workspace the launches use: d_ws, or the device's static scratch for the duration of
+                                   // an eclip_submit_static call
     size_t ws_floats = 0;
     bool timing = false;           // requests record timing events (eclip_model_timing)
     void *d_self_in = nullptr;     // zero input / scratch output for profiling
@@ -1171,6 +1201,27 @@ extern "C" eclip_status eclip_submit(eclip_model *model, const void *d_in, void 
     if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
     std::lock_guard<std::mutex> lk(model->mu);
     return submit_locked(model, d_in, d_out, batch, out);
+}
+
+// ------------------------------------------------------------------------------------------------
+// the entry point that allocates nothing
+// ------------------------------------------------------------------------------------------------
+extern "C" eclip_status eclip_submit_static(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out)
+{
+    if (!model || !out) return fail(ECLIP_EINVAL, "null argument");
+    *out = nullptr;
+    if (!d_in || !d_out) return fail(ECLIP_EINVAL, "null device buffer");
+    if (batch == 0 || batch > model->max_batch) return fail(ECLIP_EINVAL, "batch %u outside 1..%u", batch, model->max_batch);
+    if (model->ws_floats * sizeof(float) > (size_t)ECLIP_STATIC_SCRATCH_BYTES)
+        return fail(ECLIP_ELIMIT, "the model's kernels need %zu bytes of scratch, the static scratch holds %zu", model->ws_floats * sizeof(float),
+                    (size_t)ECLIP_STATIC_SCRATCH_BYTES);
+    void *sp = model->pool->scratch;
+    if (!sp) return fail(ECLIP_ESTATE, "the pool has no static scratch address");
+    std::lock_guard<std::mutex> lk(model->mu);
+    model->ws = (float *)sp;
+    const eclip_status st = submit_locked(model, d_in, d_out, batch, out);
+    model->ws = model->d_ws;
+    return st;
 }
 
 extern "C" eclip_status eclip_model_timing(eclip_model *model, int enable)
