@@ -304,7 +304,9 @@ def test_bert_base_layer_shapes_full_width():
 
 # ---------------- every GEMM kernel variant, forced, on ragged shapes ----------------------------------------------
 GEMM_FORCE = ["0,0,1", "0,0,3", "0,1,1", "0,1,2", "0,2,1", "0,2,5", "0,3,1", "0,3,2", "0,4,1", "0,4,3", "1,0,4", "1,0,8", "1,0,16", "1,1,4", "1,1,8",
-              "1,1,16", "1,2,4", "1,2,8", "1,3,4", "1,3,8", "1,3,16", "1,4,4", "1,4,16", "1,5,8", "1,5,16"]
+              "1,1,16", "1,2,4", "1,2,8", "1,3,4", "1,3,8", "1,3,16", "1,4,4", "1,4,16", "1,5,8", "1,5,16",
+              # the ping-pong tiles for the M ~ 1.5 k class: 192x128 (K step 32, 64), 128x128, 256x128, 192x256, 256x192, 64x128, 128x64
+              "0,5,1", "0,5,2", "0,6,1", "0,7,1", "0,7,3", "0,8,1", "0,9,1", "0,10,1", "0,10,2", "0,11,1", "0,12,1", "0,12,2"]
 
 
 @pytest.mark.parametrize("force", GEMM_FORCE)
