@@ -261,6 +261,17 @@ eclip_status eclip_wait(eclip_req *req, uint64_t timeout_ns, eclip_timing *opt_o
 eclip_status eclip_profile_group(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
                                  uint32_t iters, uint64_t *ns_per_kernel_out);
 
+/* Measured plan selection for the matrix-core layers (an extension of the profiling step of Sec. III-B: the library
+ * writes its own kernels, so next to "how long does this kernel take on c CUs" it can also ask "which of my tile
+ * shapes is fastest on c CUs").  For every distinct GEMM problem (M, N, K) among the model's CONV / LINEAR layers
+ * at `batch`, every candidate launch plan is timed on pool entry `mask_id` (minimum over `iters` samples of 6
+ * back-to-back launches) and the fastest is remembered for streams of that CU count -- unless the cost model's own
+ * choice is within 5 % of it, in which case that one stays.  Later eclip_submit / eclip_profile_* / kernel_info
+ * calls use the remembered plans; problems or CU counts never tuned keep the cost model's plans.  Results stay
+ * within the same tolerances (a different tile only reassociates the fp32 sums).  *n_tuned_out (optional) receives
+ * the number of problems timed.  Same preconditions as eclip_profile_group. */
+eclip_status eclip_model_tune(eclip_model *model, uint32_t mask_id, uint32_t batch, uint32_t iters, uint32_t *n_tuned_out);
+
 /* The group as eclip_submit serves it (Sec. III-B: the allocator's beta of a unit): all launches of `group` in
  * order on pool entry `mask_id` -- including the input re-layout in group 0, two independent layers sharing a
  * launch, pool + classifier in one launch -- timed as one interval; median over `iters` samples in integer
@@ -341,6 +352,24 @@ typedef struct {
  * objective would not fit 128 bits. */
 eclip_status eclip_alloc_solve(const eclip_alloc_problem *problem, uint32_t *cfg_idx_out,
                                eclip_u128 *objective_out, uint32_t *switches_out);
+
+/* The two partitioning scenarios the paper compares its optimizer with (Sec. IV, "Spatial Partitioning Scenarios";
+ * switch counts as in Table I), computed from the same problem description; only configs, units_of_worker and
+ * beta are read.  Exact integer comparisons, no search.  cfg_idx_out[sum units] and switches_out[n_workers]
+ * (optional) as for eclip_alloc_solve.  EINVAL on malformed input.
+ *
+ * Model-Wise (Sec. II-A, Sec. IV): every worker keeps one configuration for the whole request -- the smallest CU
+ * count c with  slo_den * sum_g beta[g][c] <= slo_num * sum_g beta[g][largest]  (the QoS convention of Sec. II-A
+ * is 3x the solo latency: slo_num = 3, slo_den = 1); the largest configuration always qualifies.  No switches. */
+eclip_status eclip_alloc_model_wise(const eclip_alloc_problem *problem, uint32_t slo_num, uint32_t slo_den,
+                                    uint32_t *cfg_idx_out, uint32_t *switches_out);
+
+/* Kernel-Wise on pre-allocated streams (Sec. IV, KW-Prealloc): every unit runs at its own minimum-CU threshold
+ * (Sec. III-B, "Minimum CU Threshold Profiling": the fewest CUs without noticeable slowdown), read as the smallest
+ * c with  100 * beta[c] <= (100 + tol_pct) * beta[largest]  (tol_pct = 5 by default in the benchmark); a switch is
+ * counted wherever consecutive units of a worker differ. */
+eclip_status eclip_alloc_kernel_wise(const eclip_alloc_problem *problem, uint32_t tol_pct, uint32_t *cfg_idx_out,
+                                     uint32_t *switches_out);
 
 /* ------------------------------------------------------------------------------------------
  * Repartitioning overhead (Sec. II-C, Observation 1)

@@ -129,3 +129,32 @@ def solve_exhaustive(p) -> Tuple[List[List[int]], int, List[int]]:
         raise ValueError("no feasible assignment")
     assign, (num, _s, sw) = best
     return [list(a) for a in assign], num, sw
+
+
+# ---- the two comparison policies of Sec. IV ("Spatial Partitioning Scenarios") --------------------------------------
+def model_wise(p, slo_num: int = 3, slo_den: int = 1) -> Tuple[List[List[int]], List[int]]:
+    """Model-Wise: each worker keeps ONE configuration for its whole request: the fewest CUs whose request latency
+    (sum of its units' profiled latencies) is at most slo_num/slo_den times the latency on the largest configuration
+    (Sec. II-A: QoS = 3x the solo latency).  Returns (assignment, switches per worker = 0)."""
+    assign = []
+    last = len(p.configs) - 1
+    for w in p.workers:
+        total = [sum(row[c] for row in w.beta) for c in range(len(p.configs))]
+        ok = [c for c in range(len(p.configs)) if total[c] * slo_den <= total[last] * slo_num]
+        assign.append([min(ok)] * len(w.beta))
+    return assign, [0] * len(p.workers)
+
+
+def kernel_wise(p, tol_pct: int = 5) -> Tuple[List[List[int]], List[int]]:
+    """KW-Prealloc: each unit at its own minimum-CU threshold (Sec. III-B, "Minimum CU Threshold Profiling": the fewest
+    CUs without noticeable slowdown; reading: 100*beta[c] <= (100+tol_pct)*beta[largest]).  Returns (assignment,
+    switches per worker: positions where consecutive units differ, the KW-Prealloc column of Table I)."""
+    assign = []
+    last = len(p.configs) - 1
+    for w in p.workers:
+        a = []
+        for row in w.beta:
+            ok = [c for c in range(len(p.configs)) if 100 * row[c] <= (100 + tol_pct) * row[last]]
+            a.append(min(ok))
+        assign.append(a)
+    return assign, [switch_total(a) for a in assign]

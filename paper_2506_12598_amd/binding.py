@@ -89,6 +89,7 @@ EXPORTS = {
     "eclip_submit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
     "eclip_submit_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
     "eclip_model_timing": (C.c_int, [C.c_void_p, C.c_int]),
+    "eclip_model_tune": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32)]),
     "eclip_profile_group_served": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                              C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]),
     "eclip_wait": (C.c_int, [C.c_void_p, C.c_uint64, C.POINTER(eclip_timing)]),
@@ -96,6 +97,10 @@ EXPORTS = {
                                       C.POINTER(C.c_uint64)]),
     "eclip_alloc_solve": (C.c_int, [C.POINTER(eclip_alloc_problem), C.POINTER(C.c_uint32), C.POINTER(eclip_u128),
                                     C.POINTER(C.c_uint32)]),
+    "eclip_alloc_model_wise": (C.c_int, [C.POINTER(eclip_alloc_problem), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32),
+                                         C.POINTER(C.c_uint32)]),
+    "eclip_alloc_kernel_wise": (C.c_int, [C.POINTER(eclip_alloc_problem), C.c_uint32, C.POINTER(C.c_uint32),
+                                          C.POINTER(C.c_uint32)]),
     "eclip_bench_switch": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_double),
                                      C.POINTER(C.c_double), C.POINTER(C.c_double)]),
 }
@@ -273,6 +278,12 @@ class Model:
     def timing(self, enable: bool):
         check(lib.eclip_model_timing(self.handle, 1 if enable else 0))
 
+    def tune(self, mask_id: int, batch: int = 1, iters: int = 2) -> int:
+        """Time every candidate plan of every GEMM problem on pool entry `mask_id`; returns the number of problems timed."""
+        n = C.c_uint32()
+        check(lib.eclip_model_tune(self.handle, mask_id, batch, iters, C.byref(n)))
+        return n.value
+
     def profile_group_served(self, group: int, mask_id: int, batch: int = 1, iters: int = 20) -> Tuple[int, int]:
         """(group latency in ns as served, kernels launched per pass)."""
         ns, n = C.c_uint64(), C.c_uint32()
@@ -316,3 +327,38 @@ def eclip_alloc_solve(total_cus: int, configs: Sequence[int], n_kernels: Sequenc
         res.append(list(out[pos:pos + g]))
         pos += g
     return res, (obj.hi << 64) | obj.lo, list(sw[:len(units)])
+
+
+def _tables_problem(configs, beta):
+    units = [len(x) for x in beta]
+    flat_b = [v for w in beta for row in w for v in row]
+    cfg, uo = _u32(configs), _u32(units)
+    bb = (C.c_uint64 * len(flat_b))(*[int(v) for v in flat_b])
+    p = eclip_alloc_problem(0, cfg, len(configs), len(units), uo, None, bb, 0, 0, None, 0, 0, 0, 0)
+    return p, units, (cfg, uo, bb)
+
+
+def _split(out, sw, units):
+    res, pos = [], 0
+    for g in units:
+        res.append(list(out[pos:pos + g]))
+        pos += g
+    return res, list(sw[:len(units)])
+
+
+def eclip_alloc_model_wise(configs: Sequence[int], beta: Sequence[Sequence[Sequence[int]]], slo_num: int = 3, slo_den: int = 1):
+    """beta[w][g][c] -> (cfg_idx[w][g], switches[w]): one configuration per worker."""
+    p, units, _keep = _tables_problem(configs, beta)
+    out = (C.c_uint32 * max(1, sum(units)))()
+    sw = (C.c_uint32 * max(1, len(units)))()
+    check(lib.eclip_alloc_model_wise(C.byref(p), slo_num, slo_den, out, sw))
+    return _split(out, sw, units)
+
+
+def eclip_alloc_kernel_wise(configs: Sequence[int], beta: Sequence[Sequence[Sequence[int]]], tol_pct: int = 5):
+    """beta[w][g][c] -> (cfg_idx[w][g], switches[w]): every unit at its own minimum-CU threshold."""
+    p, units, _keep = _tables_problem(configs, beta)
+    out = (C.c_uint32 * max(1, sum(units)))()
+    sw = (C.c_uint32 * max(1, len(units)))()
+    check(lib.eclip_alloc_kernel_wise(C.byref(p), tol_pct, out, sw))
+    return _split(out, sw, units)

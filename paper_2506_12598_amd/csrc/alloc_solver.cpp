@@ -287,4 +287,76 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
     return "";
 }
 
+// ------------------------------------------------------------------------------------------------------------------
+// The two comparison policies of Sec. IV ("Spatial Partitioning Scenarios"), on the same tables as the optimizer.
+// Both are direct rules, no search; all comparisons are exact integer arithmetic.
+// ------------------------------------------------------------------------------------------------------------------
+static std::string check_tables(const eclip_alloc_problem *p, const uint32_t *cfg_out)
+{
+    if (!p || !cfg_out) return "null problem or output";
+    if (!p->configs || !p->units_of_worker || !p->beta) return "null array in problem";
+    if (p->n_configs == 0 || p->n_configs > 64) return "n_configs must be 1..64";
+    if (p->n_workers == 0 || p->n_workers > 16) return "n_workers must be 1..16";
+    for (uint32_t c = 0; c < p->n_configs; ++c) {
+        if (p->configs[c] == 0) return "configuration with zero CUs";
+        if (c && p->configs[c] <= p->configs[c - 1]) return "configs must be strictly increasing";
+    }
+    for (uint32_t w = 0; w < p->n_workers; ++w)
+        if (p->units_of_worker[w] == 0) return "worker with no units";
+    return "";
+}
+
+// Model-Wise (Sec. II-A, Sec. IV): one configuration per worker for the whole request -- the smallest CU count whose
+// request latency (sum of the worker's unit latencies at that configuration) stays within slo_num / slo_den times
+// the latency at the largest configuration (the QoS convention of Sec. II-A: 3x the solo latency).
+std::string policy_model_wise(const eclip_alloc_problem *p, uint32_t slo_num, uint32_t slo_den, uint32_t *cfg_out, uint32_t *sw_out)
+{
+    std::string err = check_tables(p, cfg_out);
+    if (!err.empty()) return err;
+    if (slo_den == 0 || slo_num < slo_den) return "the latency target must be a ratio >= 1";
+    const uint32_t C = p->n_configs;
+    size_t unit0 = 0;
+    for (uint32_t w = 0; w < p->n_workers; ++w) {
+        const uint32_t G = p->units_of_worker[w];
+        std::vector<u128> tot(C, 0);
+        for (uint32_t g = 0; g < G; ++g)
+            for (uint32_t c = 0; c < C; ++c) tot[c] += p->beta[(unit0 + g) * C + c];
+        uint32_t pick = C - 1;
+        for (uint32_t c = 0; c < C; ++c)
+            if (tot[c] * slo_den <= tot[C - 1] * slo_num) { pick = c; break; }
+        for (uint32_t g = 0; g < G; ++g) cfg_out[unit0 + g] = pick;
+        if (sw_out) sw_out[w] = 0;
+        unit0 += G;
+    }
+    return "";
+}
+
+// Kernel-Wise on pre-allocated streams (Sec. IV, KW-Prealloc): every unit runs at its own minimum-CU threshold
+// (Sec. III-B, "Minimum CU Threshold Profiling": the fewest CUs with no noticeable slowdown), read here as the
+// smallest configuration c with 100 * beta[c] <= (100 + tol_pct) * beta[largest configuration]; a switch is charged
+// wherever consecutive units differ (the KW-Prealloc column of Table I).
+std::string policy_kernel_wise(const eclip_alloc_problem *p, uint32_t tol_pct, uint32_t *cfg_out, uint32_t *sw_out)
+{
+    std::string err = check_tables(p, cfg_out);
+    if (!err.empty()) return err;
+    if (tol_pct > 10000) return "tolerance above 10000 percent";
+    const uint32_t C = p->n_configs;
+    size_t unit0 = 0;
+    for (uint32_t w = 0; w < p->n_workers; ++w) {
+        const uint32_t G = p->units_of_worker[w];
+        uint32_t sw = 0;
+        for (uint32_t g = 0; g < G; ++g) {
+            const uint64_t *b = p->beta + (unit0 + g) * C;
+            uint32_t pick = C - 1;
+            for (uint32_t c = 0; c < C; ++c)
+                if ((u128)b[c] * 100u <= (u128)b[C - 1] * (100u + tol_pct)) { pick = c; break; }
+            cfg_out[unit0 + g] = pick;
+            if (g && pick != cfg_out[unit0 + g - 1]) ++sw;
+        }
+        if (sw_out) sw_out[w] = sw;
+        unit0 += G;
+    }
+    return "";
+}
+
 }  // namespace eclip

@@ -4,12 +4,14 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <array>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <string>
 #include <thread>
@@ -19,6 +21,8 @@
 
 namespace eclip {
 std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u128 *obj_out, uint32_t *sw_out, bool *limit);
+std::string policy_model_wise(const eclip_alloc_problem *p, uint32_t slo_num, uint32_t slo_den, uint32_t *cfg_out, uint32_t *sw_out);
+std::string policy_kernel_wise(const eclip_alloc_problem *p, uint32_t tol_pct, uint32_t *cfg_out, uint32_t *sw_out);
 }
 using namespace eclip;
 
@@ -362,6 +366,8 @@ struct eclip_model {
                                    // an eclip_submit_static call
     size_t ws_floats = 0;
     bool timing = false;           // requests record timing events (eclip_model_timing)
+    // plans chosen by measurement (eclip_model_tune), keyed by (M, N, K, CUs of the stream); the cost model decides the rest
+    std::map<std::array<long, 4>, GemmPlan> tuned;
     void *d_self_in = nullptr;     // zero input / scratch output for profiling
     float *d_self_out = nullptr;
 
@@ -716,6 +722,17 @@ static GemmShape gemm_shape(const LayerPlan &P, int batch)
     return g;
 }
 
+// The launch plan of a matrix-core layer: the measured choice when eclip_model_tune has seen this problem on a stream of
+// this CU count, else the planner's cost model.
+static GemmPlan plan_of(const eclip_model *m, long M, long N, long K, int n_cu)
+{
+    if (!m->tuned.empty() && !getenv("ECLIP_GEMM_FORCE")) {
+        const auto it = m->tuned.find(std::array<long, 4>{M, N, K, (long)n_cu});
+        if (it != m->tuned.end()) return it->second;
+    }
+    return conv_gemm_plan(M, N, K, n_cu, m->ws_floats);
+}
+
 extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_desc *desc, const void *weights,
                                          size_t weight_bytes, int weights_on_device, eclip_model **out)
 {
@@ -894,7 +911,7 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
         const GemmShape g = gemm_shape(P, (int)batch);
         out->m = (uint64_t)g.B * g.Ho * g.Wo; out->n = (uint64_t)g.Cout; out->k = (uint64_t)g.KH * g.KW * g.Cin;
         if (P.gemm) {
-            const GemmPlan pl = conv_gemm_plan((long)out->m, (long)out->n, (long)out->k, (int)model->pool->streams[mask_id].n_cu, model->ws_floats);
+            const GemmPlan pl = plan_of(model, (long)out->m, (long)out->n, (long)out->k, (int)model->pool->streams[mask_id].n_cu);
             int bm, bn, bk;
             if (pl.kind == 1) { conv_wsk_tile(pl.variant, &bm, &bn); name = "conv_wsk_kernel"; out->threads = (uint32_t)pl.nw * 64; }
             else { conv_gemm_tile(pl.variant, &bm, &bn, &bk); name = "conv_gemm_kernel"; }
@@ -966,7 +983,7 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
             if (d_out32 && chan_last_out) y32 = d_out32;
             ConvGemmArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y32 ? nullptr : y, y32, m->ws,
                            g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, dt};
-            const GemmPlan pl = conv_gemm_plan((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats);
+            const GemmPlan pl = plan_of(m, (long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu);
             *n_launched -= 1;
             e = launch_conv_gemm(a, pl, s, n_launched);
         } else if (L.op == ECLIP_OP_CONV && L.groups > 1 && !(L.groups == g.Cin && L.c == L.groups)) {
@@ -1054,7 +1071,7 @@ static hipError_t launch_pair(eclip_model *m, uint32_t i, int batch, hipStream_t
         a[k] = ConvGemmArgs{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), m->d_act + P.out_off, nullptr, m->ws,
                             g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, m->dtype};
         mnk[k][0] = (long)g.B * g.Ho * g.Wo; mnk[k][1] = g.Cout; mnk[k][2] = (long)g.KH * g.KW * g.Cin;
-        own[k] = conv_gemm_plan(mnk[k][0], mnk[k][1], mnk[k][2], n_cu, m->ws_floats);
+        own[k] = plan_of(m, mnk[k][0], mnk[k][1], mnk[k][2], n_cu);
     }
     if (!conv_gemm_plan_pair(own[0], mnk[0][0], mnk[0][1], mnk[0][2], own[1], mnk[1][0], mnk[1][1], mnk[1][2], n_cu, &pl[0], &pl[1]))
         return hipSuccess;
@@ -1338,6 +1355,74 @@ extern "C" eclip_status eclip_profile_group(eclip_model *model, uint32_t group, 
     return ECLIP_OK;
 }
 
+extern "C" eclip_status eclip_model_tune(eclip_model *model, uint32_t mask_id, uint32_t batch, uint32_t iters, uint32_t *n_tuned_out)
+{
+    if (!model) return fail(ECLIP_EINVAL, "model is null");
+    std::lock_guard<std::mutex> lk(model->mu);
+    eclip_status st = profile_prepare(model, 0, mask_id, batch, iters);
+    if (st != ECLIP_OK) return st;
+    const PoolStream &ps = model->pool->streams[mask_id];
+    const int n_cu = (int)ps.n_cu;
+    const uint32_t n_layers = (uint32_t)model->layers.size();
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    if (hipEventCreate(&ev[0]) != hipSuccess || hipEventCreate(&ev[1]) != hipSuccess) st = fail(ECLIP_EHIP, "hipEventCreate failed");
+    uint32_t n_tuned = 0;
+    const uint32_t REPS = 6;
+    for (uint32_t i = 0; i < n_layers && st == ECLIP_OK; ++i) {
+        const LayerPlan &P = model->layers[i];
+        if (!P.gemm) continue;
+        const eclip_layer &L = P.L;
+        const GemmShape g = gemm_shape(P, (int)batch);
+        const long M = (long)g.B * g.Ho * g.Wo, N = g.Cout, K = (long)g.KH * g.KW * g.Cin;
+        const std::array<long, 4> key{M, N, K, (long)n_cu};
+        if (model->tuned.count(key)) continue;
+        auto src = [&](int idx) -> const void * {
+            if (idx == -2) return nullptr;
+            if (idx == -1) return model->in_kind == ECLIP_IN_IMAGE ? (const void *)model->d_in_stage : (const void *)model->d_self_in;
+            return (const void *)(model->d_act + model->layers[idx].out_off);
+        };
+        const bool last = i + 1 == n_layers;
+        const bool chan_last_out = P.out.kind != ECLIP_KIND_IMAGE || (P.out.h == 1 && P.out.w == 1);
+        float *y32 = (last && chan_last_out) ? model->d_self_out : nullptr;
+        const ConvGemmArgs a{src(L.in0), wptr(model, P.w_dev), wptr(model, P.b_dev), src(L.in1), y32 ? nullptr : (void *)(model->d_act + P.out_off), y32,
+                             model->ws, g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, model->dtype};
+        const GemmPlan own = conv_gemm_plan(M, N, K, n_cu, model->ws_floats);
+        std::vector<GemmPlan> cand = conv_gemm_candidates(M, N, K, n_cu, model->ws_floats);
+        cand.insert(cand.begin(), own);
+        float best_ms = 1e30f, own_ms = 1e30f;
+        size_t best = 0;
+        for (size_t c = 0; c < cand.size() && st == ECLIP_OK; ++c) {
+            float t_min = 1e30f;
+            for (uint32_t it = 0; it < iters + 1; ++it) {
+                // the first sample is a single launch: it warms the code and the caches up, and a candidate that takes more
+                // than three times the best so far per launch is dropped there and then (the cost model's own plan is timed
+                // first, so the bar is set early)
+                const uint32_t reps = it ? REPS : 1;
+                hipError_t e = hipEventRecord(ev[0], ps.stream);
+                for (uint32_t r = 0; r < reps && e == hipSuccess; ++r) e = launch_conv_gemm(a, cand[c], ps.stream, nullptr);
+                if (e == hipSuccess) e = hipEventRecord(ev[1], ps.stream);
+                if (e == hipSuccess) e = hipStreamSynchronize(ps.stream);
+                float ms = 0.0f;
+                if (e == hipSuccess) e = hipEventElapsedTime(&ms, ev[0], ev[1]);
+                if (e != hipSuccess) { st = fail(ECLIP_EHIP, "tuning launch failed: %s", hipGetErrorString(e)); break; }
+                if (it) t_min = std::min(t_min, ms / (float)REPS);
+                else if (ms > 3.0f * best_ms + 0.02f) break;
+            }
+            if (c == 0) own_ms = t_min;
+            if (t_min < best_ms) { best_ms = t_min; best = c; }
+        }
+        if (st != ECLIP_OK) break;
+        // the cost model's plan stays unless a measured one beats it clearly: its picks keep independent layers on the
+        // kernel that can share a launch, which a per-layer timing does not see
+        model->tuned[key] = best_ms < 0.95f * own_ms ? cand[best] : own;
+        ++n_tuned;
+    }
+    for (hipEvent_t e : ev)
+        if (e) (void)hipEventDestroy(e);
+    if (st == ECLIP_OK && n_tuned_out) *n_tuned_out = n_tuned;
+    return st;
+}
+
 extern "C" eclip_status eclip_profile_group_served(eclip_model *model, uint32_t group, uint32_t mask_id, uint32_t batch,
                                                    uint32_t iters, uint64_t *group_ns_out, uint32_t *n_launches_out)
 {
@@ -1398,6 +1483,20 @@ extern "C" eclip_status eclip_alloc_solve(const eclip_alloc_problem *problem, ui
     }
     if (err.empty()) return ECLIP_OK;
     return fail(limit ? ECLIP_ELIMIT : ECLIP_EINVAL, "%s", err.c_str());
+}
+
+extern "C" eclip_status eclip_alloc_model_wise(const eclip_alloc_problem *problem, uint32_t slo_num, uint32_t slo_den,
+                                               uint32_t *cfg_idx_out, uint32_t *switches_out)
+{
+    const std::string err = policy_model_wise(problem, slo_num, slo_den, cfg_idx_out, switches_out);
+    return err.empty() ? ECLIP_OK : fail(ECLIP_EINVAL, "%s", err.c_str());
+}
+
+extern "C" eclip_status eclip_alloc_kernel_wise(const eclip_alloc_problem *problem, uint32_t tol_pct, uint32_t *cfg_idx_out,
+                                                uint32_t *switches_out)
+{
+    const std::string err = policy_kernel_wise(problem, tol_pct, cfg_idx_out, switches_out);
+    return err.empty() ? ECLIP_OK : fail(ECLIP_EINVAL, "%s", err.c_str());
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -23,385 +23,14 @@
 // GEMM would have to write back the whole L2 of the issuing XCD, which costs far more than a launch.
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
+#include <vector>
 
-#include "gemm_common.h"
-#include "kernels.h"
+#include "gemm_tile.h"
 
 namespace eclip {
 
 namespace {
-
-// Epilogue of one workgroup tile: acc[i][j] is the 16x16 block (i, j) of the wavefront's sub-tile, lane l holding
-// output pixel (l & 15) and channels 4 (l >> 4) .. +3 of the block.  `smem` is the workgroup's LDS (the K loop is
-// done with it); z is the K slice.
-template <typename T, int BM, int BN, int WM, int WN, int TM, int TN, int ACT, bool N8>
-__device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc)[TM][TN], uint16_t *smem, int m_base, int n_base, int z)
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-
-    if (p.splits == 1) {
-        // Row-contiguous stores.  Straight out of the accumulators a store instruction would write 8 bytes to each
-        // of 64 different rows (measured: 6.4 us for the 12.6 MB output of a 1536 x 4096 layer, 2 TB/s).  Instead
-        // each wavefront passes its sub-tile through a private LDS buffer, 32 rows at a time, and writes 16 bytes
-        // (8 channels) per lane along the rows: whole 128-byte lines, and the bias and residual reads get the same
-        // shape.  The buffer is private to the wavefront, so after the one barrier that ends the K loop's use of
-        // LDS only the wavefront's own LDS counter is waited on.  N8: N is a multiple of 8, so a lane's 8 channels
-        // are all inside the row and aligned; otherwise the (rare) ragged form stores them one by one from a loop
-        // that is not unrolled, to keep it out of the way.
-        static_assert(TM % 2 == 0, "32 rows per pass");
-        constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
-        constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass (lanes beyond RPP * LPR idle)
-        constexpr int PASSES = (32 + RPP - 1) / RPP;
-        __syncthreads();
-        float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
-        const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
-        const int n = n_base + wn * (BN / WN) + col8;
-        static_for<TM / 2>([&](auto hc) {
-            constexpr int h = decltype(hc)::value;
-            static_for<2>([&](auto ic) {
-                constexpr int i2 = decltype(ic)::value;
-                static_for<TN>([&](auto jc) {
-                    constexpr int j = decltype(jc)::value;
-                    const f32x4 a4 = acc[2 * h + i2][j];
-                    *reinterpret_cast<float4 *>(&stage[(i2 * 16 + (lane & 15)) * SP + j * 16 + (lane >> 4) * 4]) = make_float4(a4[0], a4[1], a4[2], a4[3]);
-                });
-            });
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): this wavefront's LDS writes have landed
-            auto pass = [&](int ps) {
-                const int rr = ps * RPP + rr0;
-                const int m = m_base + wm * (BM / WM) + h * 32 + rr;
-                if (lane < RPP * LPR && rr < 32 && m < p.M && n < p.N) {
-                    const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
-                    const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
-                    float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                    if constexpr (N8) epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
-                    else epilogue_store8_ragged<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
-                }
-            };
-            if constexpr (N8) {
-#pragma unroll
-                for (int ps = 0; ps < PASSES; ++ps) pass(ps);
-            } else {
-#pragma unroll 1
-                for (int ps = 0; ps < PASSES; ++ps) pass(ps);
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_s_waitcnt(0xc07f);              // reads done before the next 32 rows overwrite the buffer
-        });
-        return;
-    }
-    // lane owns output pixel m0 + (lane & 15) and channels n0 + 4*(lane >> 4) .. +3 of each 16x16 block
-    const int m_l = m_base + wm * (BM / WM) + (lane & 15);
-    const int n_l = n_base + wn * (BN / WN) + (lane >> 4) * 4;
-    // split-K: this slice's partial sums go to ws[z][m][n]; a second kernel adds the slices.  (A single-kernel
-    // form, in which the last slice to arrive at a per-tile counter does the sum, was measured and dropped:
-    // across XCDs it needs either a device-scope fence, i.e. a write-back of the issuing XCD's whole L2 per
-    // workgroup, or write-through stores and cache-bypassing loads for every partial sum; both cost several
-    // times the second launch.)
-    const bool vec = ((p.N & 3) == 0);
-    static_for<TM>([&](auto ic) {
-        constexpr int i = decltype(ic)::value;
-        static_for<TN>([&](auto jc) {
-            constexpr int j = decltype(jc)::value;
-            const int m = m_l + i * 16, n = n_l + j * 16;
-            if (m < p.M && n < p.N) {
-                float *dst = p.ws + ((long)z * p.M + m) * p.N + n;
-                if (vec) {
-                    *reinterpret_cast<float4 *>(dst) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (n + r < p.N) dst[r] = acc[i][j][r];
-                }
-            }
-        });
-    });
-}
-template <typename T, int BM, int BN, int WM, int WN, int TM, int TN>
-__device__ __forceinline__ void tile_epilogue(const GemmDev &p, f32x4 (&acc)[TM][TN], uint16_t *smem, int m_base, int n_base, int z)
-{
-    // the partial sums of a K slice take no activation
-    if (p.splits != 1) { tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN, ACT_NONE, true>(p, acc, smem, m_base, n_base, z); return; }
-    if ((p.N & 7) == 0) {
-#define EPI(A) tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN, A, true>(p, acc, smem, m_base, n_base, z)
-        ECLIP_ACT_SWITCH(p.act, EPI)
-#undef EPI
-    } else {
-#define EPI(A) tile_epilogue_impl<T, BM, BN, WM, WN, TM, TN, A, false>(p, acc, smem, m_base, n_base, z)
-        ECLIP_ACT_SWITCH(p.act, EPI)
-#undef EPI
-    }
-}
-
-// K-loop schedules
-enum { LOOP_PLAIN = 0, LOOP_PINGPONG = 2 };
-
-template <typename T, int BM, int BN, int BK, int WM, int WN, int RS, int LOOP = LOOP_PLAIN>
-__global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
-{
-    constexpr int NT = WM * WN * 64;         // threads per workgroup: 4 wavefronts, 8 for the 256x256 tile
-    static_assert(RS % 2 == 0, "register stages alternate between the two LDS slots");
-    // row pitch in elements.  Measured with a ds_read_b128 / ds_write_b128 micro-benchmark: with 64-byte rows a
-    // pitch of 96 bytes makes the fragment reads (16 rows x 4 chunks per instruction) conflict-free, 80 bytes
-    // costs them about 20 %.
-    constexpr int LDK = (LOOP == LOOP_PINGPONG) ? BK + 16 : BK + 8;
-    constexpr int CPR = BK / 8;              // 16-byte chunks per row
-    constexpr int TM = BM / WM / 16, TN = BN / WN / 16;
-    constexpr int A_CH = BM * CPR, B_CH = BN * CPR;
-    constexpr int A_IT = (A_CH + NT - 1) / NT, B_IT = (B_CH + NT - 1) / NT;
-    static_assert(NT % CPR == 0, "a thread keeps the same k chunk for all of its rows");
-
-    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];     // sA[2][BM*LDK] then sB[2][BN*LDK]
-    uint16_t *const sA0 = smem, *const sB0 = smem + 2 * BM * LDK;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    // Workgroups are handed to the 8 XCDs round-robin (workgroup b runs on XCD b % 8), each XCD has its own
-    // L2, and the 32 CUs of an XCD run 32 consecutive workgroups of that XCD at a time.  With `raster` set
-    // (large problems) those 32 workgroups form an 8 x 4 block of tiles, so that one K step pulls 8 + 4
-    // operand tiles into the L2 instead of up to 32 + 1; blocks are dealt to the XCDs in row-major order.
-    int tile_m, tile_n;
-    if (p.raster == 2) {                      // an XCD owns a contiguous range of tile columns (mid-size problems)
-        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_n + 7) >> 3, r = q / p.tiles_m;
-        tile_m = q - r * p.tiles_m;
-        tile_n = xcd * per + r;
-        if (r >= per || tile_n >= p.tiles_n) return;
-    } else if (p.raster == 3) {               // ... or of tile rows
-        const int xcd = blockIdx.x & 7, q = blockIdx.x >> 3, per = (p.tiles_m + 7) >> 3, r = q / p.tiles_n;
-        tile_n = q - r * p.tiles_n;
-        tile_m = xcd * per + r;
-        if (r >= per || tile_m >= p.tiles_m) return;
-    } else if (p.raster) {
-        const int b = blockIdx.x, l = b >> 3, w = l & 31;
-        const int sb = (l >> 5) * 8 + (b & 7);
-        const int sbm = (p.tiles_m + 7) >> 3;
-        tile_m = (sb % sbm) * 8 + (w & 7);
-        tile_n = (sb / sbm) * 4 + (w >> 3);
-        if (tile_m >= p.tiles_m || tile_n >= p.tiles_n) return;
-    } else {
-        tile_m = blockIdx.x % p.tiles_m;
-        tile_n = blockIdx.x / p.tiles_m;
-    }
-    const int m_base = tile_m * BM, n_base = tile_n * BN;
-
-    // ---- per-thread, per-chunk addressing that does not change along K
-    // Operands are read through buffer descriptors: a lane whose chunk is padding, beyond M / N or beyond K
-    // is given an offset past the end of the buffer, for which the hardware returns zeros.  This keeps the
-    // loads free of branches, so the loads of different K steps are counted apart by the hardware.
-    const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)p.x, 0, (int)p.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)p.w, 0, (int)p.w_bytes, 0x00020000);
-    constexpr unsigned OOB = 0xffffffffu;
-    bool a_ok[A_IT];
-    unsigned a_off0[A_IT];                   // byte offset of pixel (ih0, iw0) of the row's image (modulo 2^32 when padded)
-    int a_ih0[A_IT], a_iw0[A_IT];
-    const int HoWo = p.Ho * p.Wo;
-#pragma unroll
-    for (int it = 0; it < A_IT; ++it) {
-        const int c = tid + it * NT;
-        const int m = m_base + c / CPR;
-        a_ok[it] = (A_CH % NT == 0 || c < A_CH) && (m < p.M);
-        const int mm = a_ok[it] ? m : 0;
-        const int b = mm / HoWo, r = mm - b * HoWo;
-        const int oh = r / p.Wo, ow = r - oh * p.Wo;
-        a_ih0[it] = oh * p.stride - p.pad;
-        a_iw0[it] = ow * p.stride - p.pad;
-        a_off0[it] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[it] * p.W + a_iw0[it])) * (unsigned)p.Cin * 2u;
-    }
-    // The weights are stored in blocks of 16 rows x 32 k, 1 KB each, lane-ordered for the matrix instruction.  A
-    // wavefront copies whole blocks: chunk c of the tile is lane c % 64 of block c / 64, and block b of the tile is
-    // (row block b / (BK/32), k block b % (BK/32)).  Padding rows and k are zeros in memory, so the only checks are
-    // the end of the matrix and the end of this workgroup's K slice.
-    static_assert(NT % 64 == 0 && BK % 32 == 0 && BN % 16 == 0, "whole weight blocks per wavefront");
-    constexpr int KBT = BK / 32;             // k blocks per tile
-    const int KB = (p.K + 31) >> 5, NB = (p.N + 15) >> 4;
-    bool b_ok[B_IT];
-    unsigned b_base[B_IT];                   // byte offset of this lane's 16 bytes in k block 0 of its row block
-    int b_kb[B_IT];                          // k block within the tile
-    int b_lds[B_IT];                         // element offset in the LDS tile
-#pragma unroll
-    for (int it = 0; it < B_IT; ++it) {
-        const int c = tid + it * NT;
-        const int blk = c >> 6, nbl = blk / KBT;
-        b_kb[it] = blk - nbl * KBT;
-        const int nb = (n_base >> 4) + nbl;
-        b_ok[it] = (B_CH % NT == 0 || c < B_CH) && (nb < NB);
-        b_base[it] = ((unsigned)(b_ok[it] ? nb : 0) * (unsigned)KB * 64u + (unsigned)lane) * 16u;
-        b_lds[it] = (nbl * 16 + (lane & 15)) * LDK + b_kb[it] * 32 + (lane >> 4) * 8;
-    }
-    const int kc = (tid % CPR) * 8;          // same for every chunk of this thread: NT % CPR == 0
-    const bool pointwise = (p.KH * p.KW == 1);
-
-    const int kt_begin = blockIdx.y * p.kt_per;
-    const int kt_end = min(p.KT, kt_begin + p.kt_per);
-    // K tiles are loaded strictly in order, so the thread keeps the position of its next 8 k, k = (kh, kw, ci),
-    // and advances it by BK per tile without dividing.  Tiles at or beyond the end of the slice load zeros
-    // (k >= k_lim), which keeps the K loops below free of branches.
-    const int k_lim = min(p.K, kt_end * BK);
-    const int kb_lim = min(KB, kt_end * KBT);
-    int kb_run = kt_begin * KBT;
-    int k_run = kt_begin * BK + kc;
-    int kh_run = 0, kw_run = 0, ci_run = k_run;
-    if (!pointwise) {
-        const int tap = k_run / p.Cin;
-        ci_run = k_run - tap * p.Cin;
-        kh_run = tap / p.KW;
-        kw_run = tap - kh_run * p.KW;
-    }
-    // (written with & and selects rather than && and if: one basic block, so that the scheduler may spread these
-    // instructions between matrix instructions)
-    auto load_next = [&](uint4 (&ra)[A_IT], uint4 (&rb)[B_IT]) {
-        const int k_ok = k_run < k_lim;
-        const unsigned tap_off = (unsigned)((kh_run * p.W + kw_run) * p.Cin + ci_run) * 2u;
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-            const int ok = (int)a_ok[it] & k_ok & (int)((unsigned)(a_ih0[it] + kh_run) < (unsigned)p.H) &
-                           (int)((unsigned)(a_iw0[it] + kw_run) < (unsigned)p.W);
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rx, ok ? a_off0[it] + tap_off : OOB, 0, 0);
-            ra[it] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) {
-            const int kb = kb_run + b_kb[it];
-            const int ok = (int)b_ok[it] & (int)(kb < kb_lim);
-            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rw, ok ? b_base[it] + (unsigned)kb * 1024u : OOB, 0, 0);
-            rb[it] = make_uint4(v.x, v.y, v.z, v.w);
-        }
-        kb_run += KBT;
-        k_run += BK;
-        ci_run += BK;
-        // Cin >= 8, so BK / 8 turns always suffice.  For a 1x1 window Cin == K and a wrap happens only beyond K,
-        // where k_ok is false whatever the tap says.
-#pragma unroll
-        for (int u = 0; u < BK / 8; ++u) {
-            const int wrap = ci_run >= p.Cin;
-            ci_run -= wrap ? p.Cin : 0;
-            kw_run += wrap;
-            const int wrap2 = kw_run == p.KW;
-            kw_run = wrap2 ? 0 : kw_run;
-            kh_run += wrap2;
-        }
-    };
-    auto store_tile = [&](int slot, const uint4 (&ra)[A_IT], const uint4 (&rb)[B_IT]) {
-#pragma unroll
-        for (int it = 0; it < A_IT; ++it) {
-            const int c = tid + it * NT;
-            if (A_CH % NT == 0 || c < A_CH) *reinterpret_cast<uint4 *>(&sA0[slot * BM * LDK + (c / CPR) * LDK + kc]) = ra[it];
-        }
-#pragma unroll
-        for (int it = 0; it < B_IT; ++it) {
-            const int c = tid + it * NT;
-            if (B_CH % NT == 0 || c < B_CH) *reinterpret_cast<uint4 *>(&sB0[slot * BN * LDK + b_lds[it]]) = rb[it];
-        }
-    };
-
-    f32x4 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
-
-    // RS register sets: set (t - kt_begin) % RS carries K step t, so RS steps of loads are in flight
-    uint4 ra[RS][A_IT], rb[RS][B_IT];
-#pragma unroll
-    for (int r = 0; r < RS; ++r) load_next(ra[r], rb[r]);
-
-    auto compute = [&](int slot) {
-#pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            uint4 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *reinterpret_cast<const uint4 *>(&sA0[slot * BM * LDK + (wm * (BM / WM) + i * 16 + frag_row) * LDK + ks * 32 + frag_k]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *reinterpret_cast<const uint4 *>(&sB0[slot * BN * LDK + (wn * (BN / WN) + j * 16 + frag_row) * LDK + ks * 32 + frag_k]);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[j], fa[i], acc[i][j]);
-        }
-    };
-
-    // LDS slot (t - kt_begin) % 2 is rewritten at step t only after every wavefront has passed the barrier
-    // of step t-1, i.e. after all of them finished reading it at step t-2.  RS is even, so the slot of
-    // register set r is r % 2.
-    // The loop body is branch-free: steps at or beyond kt_end load zeros (k >= k_lim in load_next's terms is
-    // forced by passing KT) and multiply them, which costs at most RS-1 idle steps at the end of a slice
-    // and lets the compiler wait for exactly one step's loads at a time.
-    if constexpr (LOOP == LOOP_PINGPONG) {
-        // Two groups of wavefronts, half a step apart.  Wavefronts w and w + 4 share a SIMD, and WN == 4 puts
-        // them in different groups (group = wave / 4 = wm).  Time is cut into phases by workgroup barriers; in
-        // every phase one group runs its memory half-step (fragments of step t from LDS into registers, tile
-        // t+1 from registers into LDS) while the other issues the global loads of tile t+3 and runs the MFMAs of its
-        // previous half-step, so the matrix pipe and the LDS pipe of each SIMD are busy at the same time
-        // instead of taking turns.  Group 1 starts one phase late and group 0 ends one phase late: both pass
-        //   1 + (1 or 0) + 2 * steps + (0 or 1)
-        // barriers, and the trip count is the same for every wavefront of a workgroup.
-        // LDS hazards: slot s = (t+1)%2 is written in the memory half-steps of step t (phases 2t, 2t+1); its
-        // previous content (tile t-1) was last read in phase 2t-1, and it is first read in phase 2t+2.
-        static_assert(LOOP != LOOP_PINGPONG || (RS == 2 && WM == 2 && WN == 4), "ping-pong schedule: 8 wavefronts, two register sets");
-        constexpr int TK = BK / 32;              // matrix instructions along K per step and 16x16 block
-        const bool late = wm != 0;
-        uint4 fa[TK][TM], fb[TK][TN];
-        auto read_frags = [&](int slot) {
-#pragma unroll
-            for (int ks = 0; ks < TK; ++ks) {
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    fb[ks][j] = *reinterpret_cast<const uint4 *>(&sB0[slot * BN * LDK + (wn * (BN / WN) + j * 16 + frag_row) * LDK + ks * 32 + frag_k]);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    fa[ks][i] = *reinterpret_cast<const uint4 *>(&sA0[slot * BM * LDK + (wm * (BM / WM) + i * 16 + frag_row) * LDK + ks * 32 + frag_k]);
-            }
-        };
-        // the loads of a later tile are issued from inside the MFMA half-step (their address arithmetic fills
-        // issue slots between matrix instructions), which keeps the memory half-step down to LDS traffic
-        auto mma = [&](uint4 (&na)[A_IT], uint4 (&nb)[B_IT]) {
-            __builtin_amdgcn_s_setprio(1);
-            load_next(na, nb);
-#pragma unroll
-            for (int ks = 0; ks < TK; ++ks)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::run(fb[ks][j], fa[ks][i], acc[i][j]);
-            __builtin_amdgcn_s_setprio(0);
-        };
-        store_tile(0, ra[0], rb[0]);
-        load_next(ra[0], rb[0]);
-        __syncthreads();
-        if (late) __syncthreads();
-        for (int kt = kt_begin; kt < kt_end; kt += 2) {
-            read_frags(0);
-            store_tile(1, ra[1], rb[1]);
-            __syncthreads();
-            mma(ra[1], rb[1]);
-            __syncthreads();
-            read_frags(1);
-            store_tile(0, ra[0], rb[0]);
-            __syncthreads();
-            mma(ra[0], rb[0]);
-            __syncthreads();
-        }
-        if (!late) __syncthreads();
-    } else {
-        for (int kt = kt_begin; kt < kt_end; kt += RS) {
-#pragma unroll
-            for (int r = 0; r < RS; ++r) {
-                store_tile(r & 1, ra[r], rb[r]);
-                __syncthreads();
-                load_next(ra[r], rb[r]);
-                compute(r & 1);
-            }
-        }
-    }
-
-    tile_epilogue<T, BM, BN, WM, WN, TM, TN>(p, acc, smem, m_base, n_base, blockIdx.y);
-}
 
 // y = act(sum_z ws[z] + bias + res): one thread per 4 consecutive channels (one channel when N % 4 != 0).
 // The slices are read eight at a time so that their loads overlap; the additions keep slice order.
@@ -436,18 +65,14 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
 }
 
 struct Variant { int bm, bn, bk; };
-constexpr Variant kVariants[CONV_GEMM_VARIANTS] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64}, {256, 256, 32}, {128, 256, 64},
-                                                   {192, 128, 32}, {192, 128, 64}, {128, 128, 64}, {256, 128, 32}, {192, 256, 32},
-                                                   {256, 192, 32}, {64, 128, 64}, {128, 64, 64}};
+constexpr Variant kVariants[CONV_GEMM_VARIANTS] = {{128, 128, 32}, {64, 64, 64}, {32, 64, 64},
+#define X(ID, BM, BN, BK, RS, LP) {BM, BN, BK},
+                                                   ECLIP_PP_TILES(X)
+#undef X
+};
 
-// LDS of a workgroup: the two-slot operand ring, or the epilogue's staging buffers when those are larger (8 wavefronts
-// x 32 rows x (columns of a wavefront + 4) floats on the ping-pong tiles)
-constexpr size_t lds_bytes(int bm, int bn, int bk, int pad = 8)
-{
-    const size_t ring = (size_t)2 * (bm + bn) * (bk + pad) * 2;
-    const size_t stage = pad == 16 ? (size_t)8 * 32 * (bn / 4 + 4) * 4 : 0;
-    return ring > stage ? ring : stage;
-}
+template <typename T>
+hipError_t launch_pp_split(const GemmDev &d, const GemmPlan &pl, hipStream_t s, hipError_t e);
 
 template <typename T>
 hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
@@ -457,20 +82,19 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
     case 0: hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, 32, 2, 2, 2>), grid, dim3(256), lds_bytes(128, 128, 32), s, d); break;
     case 1: hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, 64, 2, 2, 4>), grid, dim3(256), lds_bytes(64, 64, 64), s, d); break;
     case 2: hipLaunchKernelGGL((conv_gemm_kernel<T, 32, 64, 64, 1, 4, 4>), grid, dim3(256), lds_bytes(32, 64, 64), s, d); break;
-#define PP(BM, BN, BK) hipLaunchKernelGGL((conv_gemm_kernel<T, BM, BN, BK, 2, 4, 2, LOOP_PINGPONG>), grid, dim3(512), lds_bytes(BM, BN, BK, 16), s, d)
-    case 3: PP(256, 256, 32); break;
-    case 4: PP(128, 256, 64); break;
-    case 5: PP(192, 128, 32); break;
-    case 6: PP(192, 128, 64); break;
-    case 7: PP(128, 128, 64); break;
-    case 8: PP(256, 128, 32); break;
-    case 9: PP(192, 256, 32); break;
-    case 10: PP(256, 192, 32); break;
-    case 11: PP(64, 128, 64); break;
-    default: PP(128, 64, 64); break;
-#undef PP
+#define X(ID, BM, BN, BK, RS, LP) \
+    case ID: return launch_pp_split<T>(d, pl, s, launch_pp<ID>(d, std::is_same<T, bf16_t>::value ? DT_BF16 : DT_F16, grid, s));
+        ECLIP_PP_TILES(X)
+#undef X
+    default: return hipErrorInvalidValue;
     }
-    hipError_t e = hipGetLastError();
+    return launch_pp_split<T>(d, pl, s, hipGetLastError());
+}
+
+// second launch of a layer whose K is cut over the grid: the slice sum
+template <typename T>
+hipError_t launch_pp_split(const GemmDev &d, const GemmPlan &pl, hipStream_t s, hipError_t e)
+{
     if (e != hipSuccess || pl.splits == 1) return e;
     const long threads = (long)d.M * ((d.N & 3) == 0 ? d.N / 4 : d.N);
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((threads + 63) / 64)), dim3(64), 0, s, d.ws, pl.splits, d.M, d.N,
@@ -483,15 +107,10 @@ hipError_t launch_t(const GemmDev &d, const GemmPlan &pl, hipStream_t s)
 hipError_t conv_gemm_init()
 {
     hipError_t e;
-#define SET(T, BM, BN, BK)                                                                                                   \
-    if ((e = hipFuncSetAttribute((const void *)conv_gemm_kernel<T, BM, BN, BK, 2, 4, 2, LOOP_PINGPONG>,                      \
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(BM, BN, BK, 16))) != hipSuccess) \
-        return e;
-#define SET2(BM, BN, BK) SET(bf16_t, BM, BN, BK) SET(f16_t, BM, BN, BK)
-    SET2(256, 256, 32) SET2(128, 256, 64) SET2(192, 128, 32) SET2(192, 128, 64) SET2(128, 128, 64) SET2(256, 128, 32)
-    SET2(192, 256, 32) SET2(256, 192, 32) SET2(64, 128, 64) SET2(128, 64, 64)
-#undef SET2
-#undef SET
+#define X(ID, BM, BN, BK, RS, LP) \
+    if ((e = init_pp<ID>()) != hipSuccess) return e;
+    ECLIP_PP_TILES(X)
+#undef X
     return hipSuccess;
 }
 
@@ -575,6 +194,43 @@ static double wsk_cost(long M, long N, long K, int n_cu, int v, int nw)
     return cost * adj.scale + adj.offset;
 }
 
+// the planner's estimate for one wave-split-K candidate (tuning aid; tile `v`, `nw` wavefronts)
+double conv_wsk_cost_estimate(long M, long N, long K, int n_cu, int v, int nw) { return wsk_cost(M, N, K, n_cu, v, nw); }
+
+// Every plan worth timing for a problem (eclip_model_tune): all wave-split-K tiles and wavefront counts that fit LDS, and
+// every LDS-tiled shape whole and with K cut in two or four where the workspace allows.  Tiles far larger than the
+// problem are left out (a 256-row tile for a 64-row problem only wastes the measurement).
+std::vector<GemmPlan> conv_gemm_candidates(long M, long N, long K, int n_cu, size_t ws_floats)
+{
+    std::vector<GemmPlan> out;
+    for (int v = 0; v < CONV_WSK_VARIANTS; ++v)
+        for (int nw = 4; nw <= 16; nw *= 2) {
+            if (conv_wsk_lds_bytes(v, nw) > 128 * 1024) continue;
+            int bm, bn;
+            conv_wsk_tile(v, &bm, &bn);
+            if (cdiv(M, bm) * cdiv(N, bn) > 65536 * 4) continue;
+            GemmPlan pl{1, v, 1, (int)(cdiv(M, bm) * cdiv(N, bn)), nw, 0};
+            set_xcd_split(pl, M, N);
+            out.push_back(pl);
+        }
+    for (int v : {0, 1, 3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14}) {
+        int bm, bn, bk;
+        conv_gemm_tile(v, &bm, &bn, &bk);
+        if (bm > 2 * M + 32 || bn > 2 * N + 32) continue;
+        const long KT = cdiv(K, bk);
+        for (long sp = 1; sp <= 4; sp *= 2) {
+            if (sp > 1 && (K < 512 * sp || (size_t)(sp * M * N) > ws_floats)) continue;
+            GemmPlan pl{0, v, 1, (int)(cdiv(M, bm) * cdiv(N, bn)), 4, 0};
+            pl.splits = (int)cdiv(KT, cdiv(KT, sp));
+            if (sp > 1 && pl.splits == 1) continue;
+            set_raster(pl, M, N);
+            out.push_back(pl);
+        }
+    }
+    (void)n_cu;
+    return out;
+}
+
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
 {
     auto tiles = [&](int v) { int bm, bn, bk; conv_gemm_tile(v, &bm, &bn, &bk); return cdiv(M, bm) * cdiv(N, bn); };
@@ -615,20 +271,42 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
             const double cost = wsk_cost(M, N, K, n_cu, v, nw);
             if (cost < best) { best = cost; pl = GemmPlan{1, v, 1, (int)wsk_tiles(v), nw, 0}; }
         }
-    // LDS-tiled kernel, optionally with K cut in two (second launch: its cost plus the traffic of the partial sums).
-    // A tile costs `shared` us per K step when workgroups share a compute unit and `alone` when it has one to itself.
-    struct { int variant; double shared, alone, fixed; } lds[4] = {{0, 0.3613, 0.6385, 0.02038}, {1, 0.3664, 1.171, 0.1703}, {3, 0.7721, 0.7721, 0.554},
-                                                                   {4, 1.157, 1.157, 2.62}};
-    for (const auto &c : lds) {
+    // LDS-tiled kernel, optionally with K cut into slices (second launch: its cost plus the traffic of the partial sums).
+    // A tile costs `fixed` us once (fill of the pipeline, epilogue) and `step` us per K step of its own depth when it has
+    // a compute unit to itself; workgroups beyond one per compute unit run in rounds (`pair`: two of them fit a compute
+    // unit together and overlap, a round of two costs 1.74 instead of 2); a full machine slows every step by about 15 %
+    // (shared L2 and vector caches).  Constants from timings of the four BERT-large shapes (M = 1536; N, K in {1024,
+    // 3072, 4096}) on 256 and on 96 compute units, each tile at 16, 64 and 128 K steps: intercept and slope per tile,
+    // minus the 2.5 us launch cost that all single-launch candidates share (as in wsk_cost).  Checked against an exhaustive
+    // sweep of every candidate on every GEMM shape of the benchmark models: the picks cost 0-8 % more than the
+    // per-layer optimum in total on 256 compute units, up to 14 % on 96; eclip_model_tune closes that gap by measurement.
+    struct LdsTile { int variant; double step, fixed; bool pair; };
+    static const LdsTile lds[] = {{0, 0.3613, 0.02038, true}, {1, 0.3664, 0.1703, true},
+                                  {3, 0.582, 5.6, false},  {5, 0.616, 4.6, false},  {6, 0.72, 2.5, false},  {7, 0.36, 1.4, false},
+                                  {8, 0.571, 3.0, false},  {9, 0.473, 0.6, false},  {10, 0.395, 1.5, false}, {11, 0.505, 3.8, false},
+                                  {12, 0.481, 3.8, false}, {13, 0.406, 0.0, true},  {14, 0.373, 0.2, true}};
+    for (const LdsTile &c : lds) {
         int bm, bn, bk;
         conv_gemm_tile(c.variant, &bm, &bn, &bk);
         const long KT = cdiv(K, bk);
-        for (long sp = 1; sp <= (c.variant == 3 ? 1 : 2); ++sp) {
-            if (sp > 1 && (K < 512 || (size_t)(sp * M * N) > ws_floats)) continue;
-            const long wgs = tiles(c.variant) * sp, per_cu = cdiv(wgs, n_cu);
-            double cost = c.fixed + (double)cdiv(KT, sp) * (per_cu == 1 ? c.alone : (double)per_cu * c.shared);
-            if (sp == 1 && c.variant == 1) cost *= 1.35;          // residuals of the fit, as for the other kernel
-            if (sp == 1 && c.variant == 0) cost -= 0.1;
+        for (long sp = 1; sp <= 4; sp *= 2) {
+            if (sp > 1 && (K < 512 * sp || (size_t)(sp * M * N) > ws_floats)) continue;
+            const long wgs = tiles(c.variant) * sp;
+            double cost;
+            if (c.variant <= 1) {
+                // the two 4-wavefront tiles keep the form they were fitted in: per K step `alone` when a workgroup has the
+                // compute unit to itself, `shared` per workgroup otherwise
+                const double alone = c.variant == 0 ? 0.6385 : 1.171;
+                const long per_cu = cdiv(wgs, n_cu);
+                cost = c.fixed + (double)cdiv(KT, sp) * (per_cu == 1 ? alone : (double)per_cu * c.step);
+                if (sp == 1 && c.variant == 1) cost *= 1.35;
+                if (sp == 1 && c.variant == 0) cost -= 0.1;
+            } else {
+                const double load = wgs >= n_cu ? 1.0 : (double)wgs / n_cu;
+                double rounds = (double)cdiv(wgs, n_cu);
+                if (c.pair && rounds >= 2.0) rounds = 0.87 * (double)wgs / n_cu > 1.0 ? 0.87 * (double)wgs / n_cu : 1.0;
+                cost = c.fixed + rounds * (double)cdiv(KT, sp) * c.step * (1.0 + 0.15 * load * load);
+            }
             if (sp > 1) cost += 15.48 + (double)M * N * (4.0 * sp + 2.0) / 4.243e6;
             if (cost < best) {
                 best = cost;

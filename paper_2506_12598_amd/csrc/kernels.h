@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace eclip {
 
 enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
@@ -33,8 +35,10 @@ struct GemmPlan {
     int raster;    // kind 0: workgroups walk the tiles in 8 x 4 blocks per XCD (tiles then counts whole blocks)
 };
 bool conv_gemm_plan_stem(long M, long N, long K, int n_cu, size_t ws_floats, double stage_us, GemmPlan *out);   // ConvGemmArgs::nchw_c
-enum { CONV_GEMM_VARIANTS = 13 };        // 128x128x32, 64x64x64, 32x64x64, 256x256x32, 128x256x64, then the ping-pong tiles
-                                         // 192x128x32, 192x128x64, 128x128x64, 256x128x32, 192x256x32, 256x192x32, 64x128x64, 128x64x64
+enum { CONV_GEMM_VARIANTS = 15 };        // 0..2: 128x128x32, 64x64x64, 32x64x64 (4 wavefronts); 3, 4: 256x256x32, 128x256x64 (8 wavefronts on the
+                                         // ping-pong schedule, both operands in LDS); 5..14: ping-pong with the weights straight from memory:
+                                         // 256x256x32, 128x256x64, 192x128x32, 192x128x64, 128x128x64, 256x128x32, 192x256x32, 256x192x32,
+                                         // 64x128x64, 128x64x64
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
 enum { CONV_WSK_VARIANTS = 6 };          // 16x64, 32x64, 64x64, 16x16, 16x32, 32x32
 void conv_wsk_tile(int variant, int *bm, int *bn);
@@ -43,6 +47,9 @@ hipError_t conv_gemm_init();   // raises the dynamic LDS limit of the 256x256 ti
 hipError_t conv_wsk_init();    // raises the dynamic LDS limit of the wave-split-K kernels once per process
 // Chooses tile shape and K split for a stream restricted to n_cu compute units.
 GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats);
+// every plan worth timing for a problem (measured plan selection)
+std::vector<GemmPlan> conv_gemm_candidates(long M, long N, long K, int n_cu, size_t ws_floats);
+double conv_wsk_cost_estimate(long M, long N, long K, int n_cu, int variant, int nw);   // the planner's estimate, us without the launch
 // *n_launched (optional) is increased by the number of kernels launched (2 when K is split).
 hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &p, hipStream_t s, uint32_t *n_launched);
 // Two layers that do not depend on each other in one launch (wave-split-K kernel only).  conv_gemm_plan_pair takes

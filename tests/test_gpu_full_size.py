@@ -51,11 +51,23 @@ def test_config5_resnet152_batch8_bf16():
     full_check(m, 8, [5, 4, 5, 3])
 
 
-def test_config5_bert_large_seq384_batch4_bf16_six_layers():
-    # the configuration's encoder (hidden 1024, 16 heads, FFN 4096, S = 384, batch 4) with 6 of its 24 layers:
-    # every kernel runs at its full shape (M = 1536) and the oracle needs a quarter of the 16 s of the full stack
-    m = wl.bert(6, 1024, 16, 4096, 384, seed=9, dtype=wl.DT_BF16)
-    full_check(m, 4, [3, 5])
+@pytest.mark.parametrize("worker", [0, 1, 2])
+def test_config5_bert_large_all_24_layers_seq384_batch4_bf16(worker):
+    # the three encoders of the stress configuration as the benchmark loads them (24 layers, hidden 1024, 16 heads, FFN 4096,
+    # S = 384, batch 4, seeds 9-11, 8 kernel groups of 3 layers), each on a table of masked streams that switches at group
+    # boundaries; the oracle's full forward pass takes about 16 s per encoder on the host cores
+    m = wl.bert(24, 1024, 16, 4096, 384, seed=9 + worker, dtype=wl.DT_BF16)       # = wl.config_models(4)[worker]
+    assert len(m.layers) == 2 + 7 * 24 and m.n_groups == 8 and m.in_w == 384 and m.layers[-1].c == 1024
+    full_check(m, 4, [[3, 3, 5, 5, 4, 4, 3, 3], [5, 4, 3, 2, 1, 2, 3, 4], [2, 2, 2, 2, 5, 5, 5, 5]][worker])
+
+
+def test_config4_resnet50_vgg16_and_bert_base_at_batch_8():
+    # configuration 4 draws the batch of every request from 1..8: the three models that the other tests run at batch 1 or 2,
+    # at the top of that range and at full size
+    r50, vgg, _, bert = wl.config_models(3)
+    full_check(r50, 8, [4, 3, 5, 2])
+    full_check(vgg, 8, [5, 4, 5, 3, 4, 2])
+    full_check(bert, 8, [3, 5, 4, 1])
 
 
 def test_second_family_resnext50_and_shufflenet_full_size():

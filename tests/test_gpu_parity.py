@@ -305,8 +305,10 @@ def test_bert_base_layer_shapes_full_width():
 # ---------------- every GEMM kernel variant, forced, on ragged shapes ----------------------------------------------
 GEMM_FORCE = ["0,0,1", "0,0,3", "0,1,1", "0,1,2", "0,2,1", "0,2,5", "0,3,1", "0,3,2", "0,4,1", "0,4,3", "1,0,4", "1,0,8", "1,0,16", "1,1,4", "1,1,8",
               "1,1,16", "1,2,4", "1,2,8", "1,3,4", "1,3,8", "1,3,16", "1,4,4", "1,4,16", "1,5,8", "1,5,16",
-              # the ping-pong tiles for the M ~ 1.5 k class: 192x128 (K step 32, 64), 128x128, 256x128, 192x256, 256x192, 64x128, 128x64
-              "0,5,1", "0,5,2", "0,6,1", "0,7,1", "0,7,3", "0,8,1", "0,9,1", "0,10,1", "0,10,2", "0,11,1", "0,12,1", "0,12,2"]
+              # the ping-pong tiles whose weights bypass LDS: 256x256, 128x256, 192x128 (K step 32, 64), 128x128, 256x128, 192x256,
+              # 256x192, 64x128, 128x64
+              "0,5,1", "0,5,2", "0,6,1", "0,7,1", "0,7,2", "0,8,1", "0,8,3", "0,9,1", "0,10,1", "0,11,1", "0,12,1", "0,12,2", "0,13,1", "0,14,1",
+              "0,14,2"]
 
 
 @pytest.mark.parametrize("force", GEMM_FORCE)
@@ -327,6 +329,15 @@ def test_every_gemm_variant_forced(force):
         # N not a multiple of 8 with bias and GELU: the element-by-element form of the staged epilogue
         m = wl.single_layer("linear", wl.DT_F16, seed=14, rows=70, k=72, n=76, act=wl.ACT_GELU, bias_std=0.3, std=0.1)
         check(m, batch=3, tol=3e-4)
+        # the specialised addressing forms of the LDS-tiled kernel: K a multiple of the K step with a 1x1 window (the operand
+        # is a plain matrix; also with strided rows, a 1x1 stride-2 projection) and Cin a multiple of the K step with a 3x3
+        # window (the tap is uniform over the workgroup), ragged M and N, with and without a K split
+        m = wl.single_layer("linear", wl.DT_BF16, seed=15, rows=300, k=512, n=200, bias_std=0.3, std=0.05, residual=False)
+        check(m, batch=1, tol=2e-4)
+        m = wl.single_layer("conv", wl.DT_F16, seed=16, cin=128, cout=72, h=19, w=17, k=1, stride=2, pad=0, act=wl.ACT_RELU, bias_std=0.5)
+        check(m, batch=2, tol=2.0 ** -8)
+        m = wl.single_layer("conv", wl.DT_BF16, seed=17, cin=64, cout=40, h=15, w=18, k=3, stride=2, pad=1, bias_std=0.5, residual=True)
+        check(m, batch=2, tol=2.0 ** -7)
     finally:
         os.environ.pop("ECLIP_GEMM_FORCE", None)
 

@@ -220,6 +220,87 @@ def test_profile_group_and_allocator_end_to_end():
         g.free()
 
 
+def test_per_kernel_groups_with_switching_tables_match_the_oracle():
+    """Every kernel is a kernel group of its own (the unit of the paper's model, Sec. III-B): per-kernel latency tables
+    are profiled on the masked streams, the optimizer (switch budget 14 per request), the per-kernel minimum-CU policy
+    (KW-Prealloc) and the one-configuration policy (Model-Wise) each give a table, each table is installed and served
+    through eclip_submit, and the output must match the oracle whatever the table.  The switch count of a request is the
+    number of group boundaries that change stream."""
+    import dataclasses
+    configs = [32, 64, 128, 192, 256]
+    for base, batch in ((wl.resnet(18, seed=1, hw=64), 2), (wl.bert(2, 128, 4, 256, 48, vocab=500, seed=4), 1)):
+        m = dataclasses.replace(base, group_of_layer=list(range(len(base.layers))), n_groups=len(base.layers))
+        x = wl.make_input(m, batch)
+        exp = orc.run_model(m, x)
+        g = GpuModel(m, max_batch=batch)
+        try:
+            beta = []
+            for k in range(m.n_groups):
+                assert g.h.group_size(k) == 1
+                beta.append([g.h.profile_group(k, mid, batch=batch, iters=3)[0] for mid in range(1, 6)])
+            ones = [1] * m.n_groups
+            tables = []
+            a, obj, sw = ec.eclip_alloc_solve(256, configs, [ones, ones], [beta, beta], 14)
+            assert obj > 0 and all(s <= 14 for s in sw)
+            tables.append(("optimizer, switchMax 14", a[0], sw[0]))
+            a, sw = ec.eclip_alloc_kernel_wise(configs, [beta], 5)
+            tables.append(("kernel-wise", a[0], sw[0]))
+            a, sw = ec.eclip_alloc_model_wise(configs, [beta], 3, 1)
+            assert sw == [0] and len(set(a[0])) == 1
+            tables.append(("model-wise", a[0], 0))
+            # a table that switches at every boundary, whatever the profile said
+            tables.append(("alternating", [k % 2 * 3 for k in range(m.n_groups)], m.n_groups - 1))
+            for name, assign, n_sw in tables:
+                got, (_, n_k, got_sw) = g.run(x, table=[c + 1 for c in assign], timing=True)
+                assert got_sw == n_sw == g.h.switches(), name
+                assert n_k >= m.n_groups, name                 # no launch is shared across kernel groups
+                assert rel_to_range(got, exp) <= 2e-2, name
+        finally:
+            g.free()
+
+
+def test_served_group_profile_counts_the_launches_that_are_served():
+    m = wl.resnet(18, seed=1, hw=64)
+    g = GpuModel(m)
+    try:
+        x = wl.make_input(m, 1)
+        _, (_, n_served, _) = g.run(x, table=[2, 2, 2, 2], timing=True)
+        total = 0
+        for grp in range(m.n_groups):
+            ns, n = g.h.profile_group_served(grp, 2, batch=1, iters=3)
+            per_layer = g.h.profile_group(grp, 2, batch=1, iters=3)
+            assert ns > 0 and 1 <= n <= g.h.group_size(grp) + (1 if grp == 0 else 0)
+            assert ns < 3 * sum(per_layer) + 50_000            # same order as the per-layer figures
+            total += n
+        assert total == n_served                               # the profiler walks the launch sequence of eclip_submit
+    finally:
+        g.free()
+
+
+def test_measured_plan_selection_keeps_the_results():
+    """eclip_model_tune times every candidate plan of every GEMM problem on a stream and remembers the fastest for that CU
+    count; the logits must stay within tolerance of the oracle (another tile only reassociates fp32 sums), the same table
+    must stay bit-reproducible, and untuned CU counts keep working."""
+    for m, batch in ((wl.resnet(50, seed=3, hw=64), 2), (wl.bert(2, 256, 4, 1024, 96, vocab=500, seed=4), 2)):
+        x = wl.make_input(m, batch)
+        exp = orc.run_model(m, x)
+        g = GpuModel(m, max_batch=batch)
+        try:
+            before = g.run(x, table=[2] * m.n_groups)
+            n = g.h.tune(2, batch=batch, iters=1)
+            assert n >= 3
+            assert g.h.tune(2, batch=batch, iters=1) == 0         # every problem of this CU count is known now
+            after = g.run(x, table=[2] * m.n_groups)
+            assert np.array_equal(after, g.run(x, table=[2] * m.n_groups))
+            other = g.run(x, table=[4] * m.n_groups)              # a CU count that was never tuned
+            for got in (before, after, other):
+                assert rel_to_range(got, exp) <= 2e-2
+            info = g.h.kernel_info(len(m.layers) - 1, 2, batch)
+            assert info["kernel"] in ("conv_wsk_kernel", "conv_gemm_kernel", "gap_kernel", "row_kernel")
+        finally:
+            g.free()
+
+
 def test_switch_overhead_bench_runs():
     same, pooled, create = shared_pool().bench_switch(1, 2, 200)
     assert same > 0 and pooled > 0 and create > 0

@@ -251,3 +251,31 @@ def test_bench_traffic_file_is_tied_to_the_kernel_sources():
         d = json.load(open(path))
         assert set(("source_sha256", "kernels", "copy_scale_fetch", "copy_scale_write")) <= set(d)
         assert d["kernels"]["conv_wsk_kernel"]["fetch_bytes_per_launch"] > 0
+
+
+# ---------------- Model-Wise and KW-Prealloc (Sec. IV scenarios) against the oracle's definitions ----------------
+@pytest.mark.parametrize("seed", range(24))
+def test_policies_match_the_oracle_bit_exact(seed):
+    shape = ("scaling", "random", "ties", "flat")[seed % 4]
+    units = [[5, 3], [2, 2, 2], [7], [1, 4, 2, 3]][seed % 4]
+    configs = [[32, 64, 128, 192, 256], [15, 30, 45, 60], list(range(16, 257, 16)), [64, 128, 256]][(seed // 4) % 4]
+    p = wl.random_problem(700 + seed, len(units), units, configs, configs[-1], 14, shape=shape)
+    beta = [w.beta for w in p.workers]
+    for num, den in ((3, 1), (3, 2), (1, 1), (105, 100)):
+        assert ec.eclip_alloc_model_wise(p.configs, beta, num, den) == oa.model_wise(p, num, den)
+    for tol in (0, 5, 12, 50, 400):
+        got = ec.eclip_alloc_kernel_wise(p.configs, beta, tol)
+        assert got == oa.kernel_wise(p, tol)
+        assert all(s <= len(a) - 1 for a, s in zip(*got))
+
+
+def test_policies_reject_malformed_input():
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_model_wise([32, 64], [[[5, 4]]], 1, 2)          # a target below the solo latency
+    assert e.value.status == ec.EINVAL
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_kernel_wise([64, 32], [[[5, 4]]], 5)           # configurations not increasing
+    assert e.value.status == ec.EINVAL
+    with pytest.raises(ec.EclipError) as e:
+        ec.eclip_alloc_kernel_wise([32, 64], [[]], 5)                 # a worker without units
+    assert e.value.status == ec.EINVAL

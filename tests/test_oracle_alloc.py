@@ -142,3 +142,61 @@ def test_extension_max_configs_and_switch_cost_hand_checked():
     p.max_configs = 1
     assert oa.solve_exhaustive(p)[0] == [[1, 1], [2]]
     assert oa.evaluate(p, [[1, 0], [2]]) is None
+
+
+# ---------------- the comparison policies of Sec. IV: Model-Wise and KW-Prealloc ----------------
+def _worked_instance():
+    return wl.AllocProblem(60, [15, 30, 45, 60], [wl.Worker([1, 1], [[100, 60, 50, 45], [80, 70, 65, 64]]),
+                                                   wl.Worker([1], [[200, 110, 80, 60]])], 1)
+
+
+def _policy_rows(kind):
+    path = os.path.join(os.path.dirname(__file__), "golden", "policies_worked_example.txt")
+    return [[int(v) for v in ln.split()[1:]] for ln in open(path) if ln.startswith(kind + " ")]
+
+
+def test_model_wise_and_kernel_wise_hand_worked_golden():
+    p = _worked_instance()
+    rows = _policy_rows("model_wise")
+    assert len(rows) == 3
+    for num, den, a, b in rows:
+        assign, sw = oa.model_wise(p, num, den)
+        assert assign == [[a, a], [b]] and sw == [0, 0]
+    rows = _policy_rows("kernel_wise")
+    assert len(rows) == 3
+    for tol, a0, a1, b, sa, sb in rows:
+        assign, sw = oa.kernel_wise(p, tol)
+        assert assign == [[a0, a1], [b]] and sw == [sa, sb]
+
+
+def test_policy_ties_flat_tables_and_monotonicity():
+    # a table that does not depend on the CU count: every configuration qualifies, the fewest CUs win
+    flat = wl.AllocProblem(60, [15, 30, 45, 60], [wl.Worker([1, 1, 1], [[70] * 4, [9] * 4, [123] * 4])], 0)
+    assert oa.model_wise(flat, 1, 1) == ([[0, 0, 0]], [0])
+    assert oa.kernel_wise(flat, 0) == ([[0, 0, 0]], [0])
+    # equality counts as meeting the threshold (the inequalities are not strict)
+    eq = wl.AllocProblem(60, [15, 30, 60], [wl.Worker([1], [[210, 105, 100]])], 0)
+    assert oa.kernel_wise(eq, 5)[0] == [[1]] and oa.kernel_wise(eq, 4)[0] == [[2]]
+    assert oa.model_wise(eq, 21, 10)[0] == [[0]] and oa.model_wise(eq, 2, 1)[0] == [[1]]
+    for seed in range(20):
+        p = wl.random_problem(seed, 2, [4, 3], [32, 64, 128, 192, 256], 256, 14)
+        last = len(p.configs) - 1
+        prev_mw, prev_kw = None, None
+        for tol in (0, 5, 20, 100, 1000):
+            kw, sw = oa.kernel_wise(p, tol)
+            mw, _ = oa.model_wise(p, 100 + tol, 100)
+            # the chosen configuration meets the rule and the next smaller one does not
+            for w, a in zip(p.workers, kw):
+                for row, c in zip(w.beta, a):
+                    assert 100 * row[c] <= (100 + tol) * row[last]
+                    assert all(100 * row[d] > (100 + tol) * row[last] for d in range(c))
+            assert sw == [oa.switch_total(a) for a in kw]
+            assert all(len(set(a)) == 1 for a in mw)
+            # a looser target never asks for more CUs
+            if prev_kw is not None:
+                assert all(c <= d for a, b in zip(kw, prev_kw) for c, d in zip(a, b))
+                assert all(a[0] <= b[0] for a, b in zip(mw, prev_mw))
+            prev_mw, prev_kw = mw, kw
+        # a single-unit worker: both policies coincide at the same tolerance
+        one = wl.AllocProblem(256, p.configs, [wl.Worker([1], [p.workers[0].beta[0]])], 0)
+        assert oa.model_wise(one, 105, 100)[0] == oa.kernel_wise(one, 5)[0]
