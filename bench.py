@@ -47,6 +47,7 @@ WORKLOADS = {
     4: "3x BERT-large-style bf16 seq 384 batch 4 + ResNet-152-style bf16 batch 8 (stress)",
     6: "second family: ALBERT-base-style fp16 seq 128 + DenseNet-121-style bf16, batch 1",
     7: "second family: ResNeXt-50-32x4d-style bf16 + ShuffleNet-g8-style bf16, batch 1",
+    8: "VGG-16-style bf16 batch 8 + BERT-large-style bf16 seq 384 batch 4 (kernel groups with very different CU needs)",
 }
 
 
@@ -157,21 +158,31 @@ class Worker:
             self.d_in = torch.from_numpy(s.view(np.int16) if s.dtype == np.uint16 else s).cuda()
         self.d_out = [torch.zeros(model.out_shape(self.max_batch), dtype=torch.float32, device="cuda") for _ in range(depth)]
         self.served = 0
+        self.error = None
 
     def closed_loop(self, n, barrier=None):
-        """n requests, up to `depth` in flight; records the number of inferences served."""
+        """n requests, up to `depth` in flight; records the number of inferences served.  A failure is kept in
+        self.error for the caller (run_closed raises it): a worker thread must never die silently."""
+        self.error = None
+        self.served = 0
         if barrier is not None:
             barrier.wait()
         q = []
         served = 0
-        for i in range(n):
-            if len(q) == self.depth:
-                q.pop(0).wait()
-            b = self.batches[i % len(self.batches)]
-            q.append(self.h.submit(self.d_in.data_ptr(), self.d_out[i % self.depth].data_ptr(), b))
-            served += b
+        try:
+            for i in range(n):
+                if len(q) == self.depth:
+                    q.pop(0).wait()
+                b = self.batches[i % len(self.batches)]
+                q.append(self.h.submit(self.d_in.data_ptr(), self.d_out[i % self.depth].data_ptr(), b))
+                served += b
+        except Exception as e:   # noqa: BLE001
+            self.error = e
         for r in q:
-            r.wait()
+            try:
+                r.wait()
+            except Exception as e:   # noqa: BLE001
+                self.error = self.error or e
         self.served = served
 
     def open_loop(self, arrivals, t_start, lat_out):
@@ -211,7 +222,11 @@ def run_closed(workers, steps):
     bar.wait()
     t0 = time.perf_counter()
     [t.join() for t in th]
-    return time.perf_counter() - t0, sum(w.served for w in workers)
+    dt = time.perf_counter() - t0
+    for w in workers:
+        if w.error is not None:
+            raise RuntimeError(f"worker {w.index} ({w.model.name}) failed: {w.error}")
+    return dt, sum(w.served for w in workers)
 
 
 # ---------------------------------------------------------------------------------------------------
@@ -557,10 +572,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 6, 7],
+    ap.add_argument("--config", type=int, default=4, choices=[1, 2, 3, 4, 6, 7, 8],
                     help="co-location mix (4 = headline workload, the stress mix; 6, 7 = mixes of the second workload family)")
     ap.add_argument("--depth", type=int, default=2, help="requests each worker keeps in flight")
     ap.add_argument("--window", type=float, default=10.0, help="seconds of open-loop Poisson load per policy (0 = skip)")
+    ap.add_argument("--graphs", type=int, default=0, choices=[0, 1], help="serve captured requests (HIP graphs replayed per stream segment)")
+    ap.add_argument("--objective", default="energy", choices=["energy", "throughput"],
+                    help="what picks the served allocation among the candidates: inferences per joule within the throughput floor, or throughput")
+    ap.add_argument("--throughput-floor", type=float, default=0.85, help="with --objective energy: candidates below this fraction of the fastest trial are out")
+    ap.add_argument("--trial-seconds", type=float, default=2.0)
     ap.add_argument("--energy-window", type=float, default=3.0, help="seconds of closed loop per policy and repeat for inferences/J (0 = skip)")
     ap.add_argument("--energy-repeats", type=int, default=3)
     ap.add_argument("--rate", type=float, default=None, help="Poisson arrivals/s per model (default: 200 for config 1, "
@@ -609,11 +629,11 @@ def main():
     idle_w = PowerSampler().read()          # board power before any kernel of this process has run
 
     cfg = args.config
-    steps = args.steps if args.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 30, 6: 500, 7: 500}[cfg]
-    warmup = args.warmup if args.warmup is not None else {1: 200, 2: 100, 3: 30, 4: 3, 6: 50, 7: 50}[cfg]
+    steps = args.steps if args.steps is not None else {1: 2000, 2: 1000, 3: 300, 4: 30, 6: 500, 7: 500, 8: 100}[cfg]
+    warmup = args.warmup if args.warmup is not None else {1: 200, 2: 100, 3: 30, 4: 3, 6: 50, 7: 50, 8: 10}[cfg]
     # lengths of the untimed legs (calibration of the interference slope, trials between candidate allocations,
     # profiling samples): fixed per mix, whatever --steps says, so that a short timed region does not make them noisy
-    n_cal = {1: 300, 2: 200, 3: 80, 4: 20, 6: 100, 7: 100}[cfg]
+    n_cal = {1: 300, 2: 200, 3: 80, 4: 20, 6: 100, 7: 100, 8: 40}[cfg]
     prof_iters = 40 if cfg != 4 else 20
     # CU configurations: the stress mix sweeps 16..256 in steps of 16 (2 CUs per XCD and granule, so no XCD is ever
     # left empty); the other mixes use the five-entry pool of their configuration
@@ -626,6 +646,8 @@ def main():
         batches = [[int(b) for b in rng.integers(1, 9, size=64)] for _ in models]
     elif cfg == 4:
         batches = [[4]] * 3 + [[8]]
+    elif cfg == 8:
+        batches = [[8], [4]]
     else:
         batches = [[1]] * n_w
     prof_batch = [max(1, int(round(np.mean(b)))) for b in batches]
@@ -665,9 +687,24 @@ def main():
     same_ns, pooled_ns, _ = prof_pool.bench_switch(0, 1, 2000, with_create=False)
     switch_cost_ns = max(0, int(pooled_ns - same_ns))
     # The GPU serves one queue per compute pipe at a time (4 pipes), so at most 4 masked streams may be in use over
-    # all workers.  The solver's limit is per worker; with 4 streams and n_w workers every worker gets 4 // n_w
-    # distinct configurations (at least one).
+    # all workers.  The solver's limit is per worker, so the global budget is spent by enumeration: one solve per way
+    # of dealing 4 streams to the workers (at least one each), best objective kept (solve_within_streams).
     max_configs = max(1, 4 // n_w)
+
+    def compositions(total, parts):
+        if parts == 1:
+            return [(total,)]
+        return [(k,) + rest for k in range(1, total - parts + 2) for rest in compositions(total - k, parts - 1)]
+
+    def solve_within_streams(per_worker_cap, sc, kw):
+        """Best allocation with at most 4 streams in use overall and at most `per_worker_cap` per worker."""
+        best = None
+        for comp in compositions(max(4, n_w), n_w):
+            comp = [min(k, per_worker_cap) for k in comp]
+            a, obj, sw = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, switch_cost_ns=sc, max_configs_of_worker=comp, **kw)
+            if best is None or obj < best[1]:
+                best = (a, obj, sw)
+        return best
     # Slope of the interference law.  The model charges a kernel (1 + alpha) times its solo latency, alpha = CU overlap /
     # total CUs, a slope the paper calibrated on its GPU (two kernels on the same CUs: twice as long).  Here the slope is
     # measured with the mix itself: every worker alone, then all together, each time on its full-GPU mask (overlap =
@@ -695,10 +732,13 @@ def main():
     cand = []
     table = {"overlap_mode": ec.OVERLAP_TABLE, "alpha_ppm": alpha_ppm, "granule": granule}
     for name, kw, mc, sc in (("model as printed (Sec. III-B: slope 1, switch budget only)", {}, 0, 0),
-                             ("paper slope", {}, max_configs, switch_cost_ns), ("measured slope", table, max_configs, switch_cost_ns),
+                             ("paper slope", {}, 4, switch_cost_ns), ("measured slope", table, 4, switch_cost_ns),
                              ("paper slope, one configuration per worker", {}, 1, switch_cost_ns),
                              ("measured slope, one configuration per worker", table, 1, switch_cost_ns)):
-        a, _, sw = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, max_configs=mc, switch_cost_ns=sc, **kw)
+        if mc == 0:
+            a, _, sw = ec.eclip_alloc_solve(256, configs, nk, beta, args.switch_max, switch_cost_ns=sc, **kw)
+        else:
+            a, _, sw = solve_within_streams(mc, sc, kw)
         if not any(a == c[1] for c in cand):
             cand.append((name, a, sw))
     # ... and the corner of the configuration space where nothing is partitioned: every worker on a mask of all CUs.  The
@@ -713,47 +753,63 @@ def main():
     # ---- serving pool: id 0 = shared unmasked stream (policy unpart_a); ids 1..n_w = one private unmasked stream per
     # worker (policy unpart_b); then only the masked streams the allocation uses, created back to back so that they
     # land on distinct pipes
+    # (the private streams of policy unpart_b carry a mask of all CUs rather than no mask: a masked stream owns a hardware
+    # queue, while plain streams are dealt onto the runtime's few shared queues, where two workers can land on the same one
+    # and serialise -- measured on the stress mix: 2780 against 3420 inf/s from one run to the next with plain streams)
+    all_cus = ec.eclip_mask_layout(256, 256, 1, 0, 1)
+
     def serving_pool(assign):
-        masks = [(None, -1)] + [(None, w) for w in range(n_w)]
+        masks = [(None, -1)] + [(all_cus, w) for w in range(n_w)]
         mask_id = {}
         for w in range(n_w):
             for c in sorted(set(assign[w])):
                 mask_id[(w, c)] = len(masks)
                 masks.append((ec.eclip_mask_layout(256, granule, n_w, w, configs[c] // granule), w))
         pool = ec.Pool(masks)
-        pipes = [pool.pipe(i) for i in range(1 + n_w, len(masks))]
-        assert len(set(pipes)) == len(pipes) or len(pipes) > 4, f"serving streams share a pipe: {pipes}"
         return pool, [[mask_id[(w, c)] for c in assign[w]] for w in range(n_w)]
 
-    # The profiling pool goes before the trials, and a candidate's serving pool goes as soon as it has lost: dozens of idle
-    # queues next to the serving streams slow dispatch down several times over (measured: the same allocation 816 inf/s
-    # with the 64-stream pool alive, 3100 without).
+    # Every candidate serves a trial on a serving pool of its own: closed loop, warm-up, then `--trial-seconds` with the
+    # board power sampled.  The profiling pool goes before the trials and a candidate's pool goes right after its trial:
+    # dozens of idle queues next to the serving streams slow dispatch down several times over (measured: the same
+    # allocation 816 inf/s with the 64-stream pool alive, 3100 without).
+    # Selection (`--objective`): "energy" (default) takes the candidate with the most inferences per joule among those
+    # within `--throughput-floor` (0.85) of the fastest trial; "throughput" takes the fastest.
+    for wk in workers:
+        wk.h.graphs(bool(args.graphs))
     trials = []
-    best = None                                      # (rate, name, assignment, switches, pool, table)
+    sampler = PowerSampler()
+    prev_pool = prof_pool
     for name, a, sw in cand:
         pool_c, table_c = serving_pool(a)
         for wk, t in zip(workers, table_c):
             wk.h.rebind(pool_c)
             wk.h.alloc_set(t)
-        if prof_pool is not None:
-            prof_pool.destroy()
-            prof_pool = None
-        rate = None
-        if len(cand) > 1:
-            dt, served = run_closed_for(workers, n_cal)
-            torch.cuda.synchronize()
-            rate = served / dt
-            log(f"trial, {name}: {rate:.0f} inf/s")
-        trials.append((rate, name, a, sw))
-        if best is None or (rate or 0.0) > (best[0] or 0.0):
-            if best is not None:
-                best[4].destroy()
-            best = (rate, name, a, sw, pool_c, table_c)
-        else:
-            for wk in workers:
-                wk.h.rebind(best[4])
-            pool_c.destroy()
-    _, chosen, assign, switches, pool, eclip_table = best
+        prev_pool.destroy()
+        prev_pool = pool_c
+        run_closed_for(workers, n_cal, seconds=0.3)
+        sampler.start()
+        time.sleep(0.05)
+        t_a = time.perf_counter()
+        dt, served = run_closed_for(workers, n_cal, seconds=args.trial_seconds, warm_seconds=0.0)
+        torch.cuda.synchronize()
+        t_b = time.perf_counter()
+        sampler.stop()
+        e = sampler.energy_j(t_a, t_b)
+        rate = served / dt
+        ipj = None if not e else rate * (t_b - t_a) / e          # the window holds a short lead-in at the same load
+        log(f"trial, {name}: {rate:.0f} inf/s, {ipj if ipj is None else round(ipj, 4)} inf/J")
+        trials.append((rate, name, a, sw, ipj))
+    fastest = max(t[0] for t in trials)
+    if args.objective == "throughput" or any(t[4] is None for t in trials):
+        best_i = max(range(len(trials)), key=lambda i: trials[i][0])
+    else:
+        ok = [i for i in range(len(trials)) if trials[i][0] >= args.throughput_floor * fastest]
+        best_i = max(ok, key=lambda i: trials[i][4])
+    _, chosen, assign, switches, _ = trials[best_i]
+    pool, eclip_table = serving_pool(assign)
+    for wk in workers:
+        wk.h.rebind(pool)
+    prev_pool.destroy()
     log(f"allocation ({chosen}) (CUs) {[[configs[c] for c in a] for a in assign]} switches {switches}")
     tables = {
         "eclip": eclip_table,
@@ -845,6 +901,8 @@ def main():
         open_res["idle_power_w"] = idle_w
         open_res["power_source"] = sampler.source
 
+    for wk in workers:
+        wk.h.graphs(False)
     # ---- roofline of the dominant kernel: HIP-event timings on the stream the kernels run on.  Each layer of each
     # model is timed on that worker's unpartitioned stream (8 back-to-back launches per sample, see
     # eclip_profile_group); layers are grouped by the kernel function that runs them; the matrix-core function
@@ -923,11 +981,12 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "+".join(dts), "data": "synthetic",
         "config": {"workload": WORKLOADS[cfg] + f", CU-mask pool {configs} per worker, switchMax {args.switch_max}",
-                   "policy": args.policy, "inflight_per_worker": args.depth,
+                   "policy": args.policy, "inflight_per_worker": args.depth, "captured_requests": bool(args.graphs),
                    "allocation_cus": [[configs[c] for c in a] for a in assign], "switches": switches,
-                   "max_configs_per_worker": max_configs, "switch_cost_ns": switch_cost_ns, "overlap_slope": round(slope, 4), "allocation_from": chosen,
+                   "streams_in_use_limit": 4, "switch_cost_ns": switch_cost_ns, "overlap_slope": round(slope, 4), "allocation_from": chosen,
+                   "objective": args.objective, "throughput_floor": args.throughput_floor,
                    "candidate_allocations": [{"from": t[1], "allocation_cus": [_runs([configs[c] for c in a]) for a in t[2]], "switches": t[3],
-                                              "trial_inferences_per_s": t[0]} for t in trials]},
+                                              "trial_inferences_per_s": t[0], "trial_inferences_per_joule": t[4]} for t in trials]},
         "closed_loop": closed,
         "open_loop_poisson": open_res,
         "roofline": roofline,

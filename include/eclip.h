@@ -132,6 +132,10 @@ eclip_status eclip_mask_layout(uint32_t total_cus, uint32_t granule, uint32_t n_
  * the wave's hardware-id registers.  `out` is a host array of n_blocks words. */
 eclip_status eclip_pool_probe(eclip_pool *pool, uint32_t mask_id, uint32_t n_blocks, uint32_t *out);
 
+/* The same probe, launched as a HIP graph captured from and replayed on the pool entry's stream: shows that replayed
+ * kernels stay on the stream's CUs (what eclip_model_graphs relies on). */
+eclip_status eclip_pool_probe_graph(eclip_pool *pool, uint32_t mask_id, uint32_t n_blocks, uint32_t *out);
+
 /* ------------------------------------------------------------------------------------------
  * Models (Sec. III-A "Redirecting Kernel Dispatch"; kernel groups: Sec. III-B)
  * ---------------------------------------------------------------------------------------- */
@@ -238,6 +242,15 @@ eclip_status eclip_submit(eclip_model *model, const void *d_in, void *d_out, uin
 #define ECLIP_STATIC_SCRATCH_BYTES (16u << 20)
 eclip_status eclip_submit_static(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out);
 
+/* Replay instead of re-launch (Sec. III-A: the cost of dispatch is first-order for kernels that last microseconds).
+ * While on, eclip_submit captures a request the first time it sees a combination of (d_in, d_out, batch) under the
+ * current table -- one HIP graph per run of kernel groups that share a pooled stream -- and afterwards replays the
+ * graphs on those streams, with the same events between them at the stream switches.  The kernels, their order,
+ * their streams (and therefore their CU masks) and the results are those of the plain path, bit for bit.  Up to 8
+ * captured requests are kept per model (least recently used first out); eclip_alloc_set with a different table,
+ * eclip_model_rebind and eclip_model_tune discard them.  Off after load.  ESTATE while requests are in flight. */
+eclip_status eclip_model_graphs(eclip_model *model, int enable);
+
 /* Timestamps cost a marker packet at both ends of every request, so requests carry them only while this is on
  * (off after load).  Takes effect for the next eclip_submit. */
 eclip_status eclip_model_timing(eclip_model *model, int enable);
@@ -341,6 +354,10 @@ typedef struct {
      *                 Sec. III-B, which the printed model bounds through switch_max only). */
     uint32_t max_configs;
     uint64_t switch_cost_ns;
+    /* max_configs_of_worker[n_workers] (host, optional): the same limit per worker; when given it replaces max_configs
+     * (0 = no limit for that worker).  Lets a caller spend a global stream budget unevenly: with 4 usable streams and 3
+     * workers, solve for (2,1,1), (1,2,1) and (1,1,2) and keep the best objective. */
+    const uint32_t *max_configs_of_worker;
 } eclip_alloc_problem;
 
 /* Exact minimiser.  cfg_idx_out[sum units] receives the configuration index of every unit

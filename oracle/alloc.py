@@ -30,7 +30,8 @@ Readings where the text is ambiguous (each is a mode or rule below, never silent
 
 Two extensions beyond the printed model, both off (0) by default so that the paper's model is the
 special case:
-  max_configs  a worker may use at most this many *distinct* configurations in one request.  It is the
+  max_configs  a worker may use at most this many *distinct* configurations in one request (max_configs_w: the same
+               limit given per worker, so that a global stream budget can be split unevenly).  It is the
                stream-pool limit of Sec. III-A turned into a constraint: every (worker, configuration)
                pair in use is one pooled stream, and the GPU runs only a few streams without
                oversubscribing its hardware queues (7 on the paper's MI50; 4 on MI355X, one per pipe).
@@ -81,7 +82,9 @@ def evaluate(p, assign: Sequence[Sequence[int]]):
     if any(s > p.switch_max for s in switches):
         return None
     max_configs = getattr(p, "max_configs", 0)
-    if max_configs and any(len(set(a)) > max_configs for a in assign):
+    per_worker = getattr(p, "max_configs_w", None)          # per-worker limits replace the common one (0 = no limit)
+    limits = list(per_worker) if per_worker is not None else [max_configs] * len(assign)
+    if any(lim and len(set(a)) > lim for a, lim in zip(assign, limits)):
         return None
     switch_cost = getattr(p, "switch_cost", 0)
     T = p.total_cus

@@ -64,7 +64,8 @@ class eclip_alloc_problem(C.Structure):
                 ("n_workers", C.c_uint32), ("units_of_worker", C.POINTER(C.c_uint32)),
                 ("n_kernels", C.POINTER(C.c_uint32)), ("beta", C.POINTER(C.c_uint64)), ("switch_max", C.c_uint32),
                 ("overlap_mode", C.c_uint32), ("alpha_ppm", C.POINTER(C.c_uint64)), ("n_alpha", C.c_uint32),
-                ("granule", C.c_uint32), ("max_configs", C.c_uint32), ("switch_cost_ns", C.c_uint64)]
+                ("granule", C.c_uint32), ("max_configs", C.c_uint32), ("switch_cost_ns", C.c_uint64),
+                ("max_configs_of_worker", C.POINTER(C.c_uint32))]
 
 
 EXPORTS = {
@@ -79,6 +80,7 @@ EXPORTS = {
     "eclip_mask_layout": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                     C.POINTER(C.c_uint32), C.c_uint32]),
     "eclip_pool_probe": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32)]),
+    "eclip_pool_probe_graph": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32)]),
     "eclip_model_load": (C.c_int, [C.c_void_p, C.POINTER(eclip_model_desc), C.c_void_p, C.c_size_t, C.c_int,
                                    C.POINTER(C.c_void_p)]),
     "eclip_model_free": (C.c_int, [C.c_void_p]),
@@ -89,6 +91,7 @@ EXPORTS = {
     "eclip_submit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
     "eclip_submit_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.POINTER(C.c_void_p)]),
     "eclip_model_timing": (C.c_int, [C.c_void_p, C.c_int]),
+    "eclip_model_graphs": (C.c_int, [C.c_void_p, C.c_int]),
     "eclip_model_tune": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32)]),
     "eclip_profile_group_served": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
                                              C.POINTER(C.c_uint64), C.POINTER(C.c_uint32)]),
@@ -191,6 +194,11 @@ class Pool:
         check(lib.eclip_pool_probe(self.handle, mask_id, n_blocks, out.ctypes.data_as(C.POINTER(C.c_uint32))))
         return out
 
+    def probe_graph(self, mask_id: int, n_blocks: int) -> np.ndarray:
+        out = np.zeros(n_blocks, np.uint32)
+        check(lib.eclip_pool_probe_graph(self.handle, mask_id, n_blocks, out.ctypes.data_as(C.POINTER(C.c_uint32))))
+        return out
+
     def bench_switch(self, mask_a: int, mask_b: int, iters: int, with_create: bool = True):
         a, b, c = C.c_double(), C.c_double(), C.c_double()
         check(lib.eclip_bench_switch(self.handle, mask_a, mask_b, iters, C.byref(a), C.byref(b),
@@ -275,6 +283,9 @@ class Model:
         check(lib.eclip_submit_static(self.handle, C.c_void_p(d_in), C.c_void_p(d_out), batch, C.byref(r)))
         return Request(r)
 
+    def graphs(self, enable: bool):
+        check(lib.eclip_model_graphs(self.handle, 1 if enable else 0))
+
     def timing(self, enable: bool):
         check(lib.eclip_model_timing(self.handle, 1 if enable else 0))
 
@@ -306,7 +317,7 @@ class Model:
 def eclip_alloc_solve(total_cus: int, configs: Sequence[int], n_kernels: Sequence[Sequence[int]],
                       beta: Sequence[Sequence[Sequence[int]]], switch_max: int, overlap_mode: int = OVERLAP_EXCESS,
                       alpha_ppm: Optional[Sequence[int]] = None, granule: int = 1, max_configs: int = 0,
-                      switch_cost_ns: int = 0):
+                      switch_cost_ns: int = 0, max_configs_of_worker: Optional[Sequence[int]] = None):
     """n_kernels[w][g], beta[w][g][c] -> (cfg_idx[w][g], objective:int, switches[w])."""
     units = [len(x) for x in n_kernels]
     flat_n = [v for w in n_kernels for v in w]
@@ -316,8 +327,9 @@ def eclip_alloc_solve(total_cus: int, configs: Sequence[int], n_kernels: Sequenc
     nk = _u32(flat_n)
     bb = (C.c_uint64 * len(flat_b))(*[int(v) for v in flat_b])
     ap = (C.c_uint64 * len(alpha_ppm))(*[int(v) for v in alpha_ppm]) if alpha_ppm else None
+    mw = _u32(max_configs_of_worker) if max_configs_of_worker is not None else None
     p = eclip_alloc_problem(total_cus, cfg, len(configs), len(units), uo, nk, bb, switch_max, overlap_mode,
-                            ap, len(alpha_ppm) if alpha_ppm else 0, granule, max_configs, switch_cost_ns)
+                            ap, len(alpha_ppm) if alpha_ppm else 0, granule, max_configs, switch_cost_ns, mw)
     out = (C.c_uint32 * max(1, sum(units)))()
     obj = eclip_u128()
     sw = (C.c_uint32 * max(1, len(units)))()
@@ -334,7 +346,7 @@ def _tables_problem(configs, beta):
     flat_b = [v for w in beta for row in w for v in row]
     cfg, uo = _u32(configs), _u32(units)
     bb = (C.c_uint64 * len(flat_b))(*[int(v) for v in flat_b])
-    p = eclip_alloc_problem(0, cfg, len(configs), len(units), uo, None, bb, 0, 0, None, 0, 0, 0, 0)
+    p = eclip_alloc_problem(0, cfg, len(configs), len(units), uo, None, bb, 0, 0, None, 0, 0, 0, 0, None)
     return p, units, (cfg, uo, bb)
 
 

@@ -134,24 +134,29 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
             if (p->alpha_ppm[i] < p->alpha_ppm[i - 1]) return "alpha_ppm must be non-decreasing";
     }
     const int W = (int)p->n_workers, C = (int)p->n_configs;
-    // configuration subsets a worker may draw from: all of them, or every subset of at most max_configs
-    std::vector<std::vector<int>> subsets;
-    {
-        const int K = (p->max_configs == 0 || (int)p->max_configs >= C) ? C : (int)p->max_configs;
-        if (K == C) {
+    // configuration subsets a worker may draw from: all of them, or every subset of at most K configurations, K being the
+    // worker's own limit (max_configs_of_worker) or the common one (max_configs)
+    auto subsets_for = [&](int K, std::vector<std::vector<int>> &subsets) -> bool {
+        subsets.clear();
+        if (K <= 0 || K >= C) {
             std::vector<int> all(C);
             std::iota(all.begin(), all.end(), 0);
             subsets.push_back(all);
-        } else {
-            std::vector<int> cur;
-            // subsets of exactly K configurations (smaller ones are contained in them), in lexicographic order
-            std::function<void(int)> rec = [&](int start) {
-                if ((int)cur.size() == K) { subsets.push_back(cur); return; }
-                for (int c = start; c < C; ++c) { cur.push_back(c); rec(c + 1); cur.pop_back(); }
-            };
-            rec(0);
-            if (subsets.size() > 4096) { *limit = true; return "too many configuration subsets (max_configs)"; }
+            return true;
         }
+        std::vector<int> cur;
+        // subsets of exactly K configurations (smaller ones are contained in them), in lexicographic order
+        std::function<void(int)> rec = [&](int start) {
+            if ((int)cur.size() == K) { subsets.push_back(cur); return; }
+            for (int c = start; c < C; ++c) { cur.push_back(c); rec(c + 1); cur.pop_back(); }
+        };
+        rec(0);
+        return subsets.size() <= 4096;
+    };
+    std::vector<std::vector<std::vector<int>>> subsets_w(W);
+    for (int w = 0; w < W; ++w) {
+        const int K = p->max_configs_of_worker ? (int)p->max_configs_of_worker[w] : (int)p->max_configs;
+        if (!subsets_for(K, subsets_w[w])) { *limit = true; return "too many configuration subsets (max_configs)"; }
     }
     uint32_t cg = 0;
     for (int c = 0; c < C; ++c) cg = std::gcd(cg, p->configs[c]);
@@ -211,7 +216,7 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
     for (int w = 0; w < W; ++w) {
         mult[w] = (uint64_t)cg * (D / Nw[w]);
         std::vector<Point> v;
-        for (const std::vector<int> &sub : subsets) {
+        for (const std::vector<int> &sub : subsets_w[w]) {
             dp[w].allowed = sub;
             dp[w].run();
             for (uint32_t u = 0; u <= dp[w].umax; ++u) {
@@ -268,7 +273,7 @@ std::string solve_alloc(const eclip_alloc_problem *p, uint32_t *cfg_out, eclip_u
             auto it = std::lower_bound(R[w + 1].begin(), R[w + 1].end(), need,
                                        [](const Point &x, const Point &y) { return x.s < y.s; });
             if (it == R[w + 1].end() || it->s != need.s || it->b != need.b) continue;
-            for (const std::vector<int> &sub : subsets) {
+            for (const std::vector<int> &sub : subsets_w[w]) {
                 dp[w].allowed = sub;
                 dp[w].run();
                 const uint32_t u = (uint32_t)(a.s / mult[w]);

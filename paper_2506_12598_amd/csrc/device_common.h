@@ -186,4 +186,20 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+// The same over aligned groups of W lanes (W = 16, 32 or 64): every lane receives the result of its own group.
+template <int W>
+__device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int o = W / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+template <int W>
+__device__ __forceinline__ float group_max(float v)
+{
+#pragma unroll
+    for (int o = W / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
 }  // namespace eclip

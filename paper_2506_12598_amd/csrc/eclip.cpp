@@ -319,6 +319,34 @@ extern "C" eclip_status eclip_pool_probe(eclip_pool *pool, uint32_t mask_id, uin
     return ECLIP_OK;
 }
 
+extern "C" eclip_status eclip_pool_probe_graph(eclip_pool *pool, uint32_t mask_id, uint32_t n_blocks, uint32_t *out)
+{
+    if (!pool || !out) return fail(ECLIP_EINVAL, "null argument");
+    if (mask_id >= pool->streams.size()) return fail(ECLIP_EINVAL, "unknown mask id %u", mask_id);
+    if (n_blocks == 0 || n_blocks > 65536) return fail(ECLIP_EINVAL, "n_blocks must be 1..65536");
+    HIP_TRY(hipSetDevice(pool->device));
+    uint32_t *d = nullptr;
+    HIP_TRY(hipMalloc(&d, (size_t)n_blocks * 4));
+    hipStream_t s = pool->streams[mask_id].stream;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    hipError_t e = hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal);
+    if (e == hipSuccess) {
+        const hipError_t le = launch_probe(d, (int)n_blocks, s);
+        e = hipStreamEndCapture(s, &graph);
+        if (le != hipSuccess) e = le;
+    }
+    if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e == hipSuccess) e = hipGraphLaunch(exec, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(out, d, (size_t)n_blocks * 4, hipMemcpyDeviceToHost);
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipFree(d);
+    if (e != hipSuccess) return fail(ECLIP_EHIP, "graph probe failed: %s", hipGetErrorString(e));
+    return ECLIP_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // model
 // ------------------------------------------------------------------------------------------------
@@ -366,6 +394,19 @@ struct eclip_model {
                                    // an eclip_submit_static call
     size_t ws_floats = 0;
     bool timing = false;           // requests record timing events (eclip_model_timing)
+    // Captured requests (eclip_model_graphs): a request is cut into segments, one per run of kernel groups on the same
+    // pooled stream; each segment is a HIP graph captured once and replayed on that stream.  An entry is good for one
+    // (input buffer, output buffer, batch, workspace) under the table and plans it was captured with (`stamp`).
+    struct GraphSeg { hipGraphExec_t exec; uint32_t mask_id; uint32_t first_group; };
+    struct GraphEntry {
+        const void *d_in; void *d_out; uint32_t batch; float *ws; uint64_t stamp, last_use;
+        uint32_t n_kernels;
+        std::vector<GraphSeg> segs;
+    };
+    bool use_graphs = false;
+    hipStream_t capture_stream = nullptr;  // private to the model: requests are captured here and replayed on pooled streams
+    uint64_t stamp = 1, use_clock = 0;     // stamp changes whenever the table, the pool or the plans change
+    std::vector<GraphEntry> graphs;
     // plans chosen by measurement (eclip_model_tune), keyed by (M, N, K, CUs of the stream); the cost model decides the rest
     std::map<std::array<long, 4>, GemmPlan> tuned;
     void *d_self_in = nullptr;     // zero input / scratch output for profiling
@@ -391,9 +432,19 @@ static size_t in_elems(const eclip_model *m) {
     return (size_t)m->in_c * m->in_h * m->in_w;
 }
 
+static void drop_graphs(eclip_model *m)
+{
+    for (auto &g : m->graphs)
+        for (auto &sg : g.segs)
+            if (sg.exec) (void)hipGraphExecDestroy(sg.exec);
+    m->graphs.clear();
+}
+
 static void free_model(eclip_model *m)
 {
     if (!m) return;
+    drop_graphs(m);
+    if (m->capture_stream) (void)hipStreamDestroy(m->capture_stream);
     (void)hipFree(m->d_weights);
     (void)hipFree(m->d_act);
     (void)hipFree(m->d_in_stage);
@@ -857,6 +908,8 @@ extern "C" eclip_status eclip_model_rebind(eclip_model *model, eclip_pool *new_p
     model->mask_of_group.clear();
     model->last_done = nullptr;
     model->last_stream = nullptr;
+    model->stamp++;
+    drop_graphs(model);
     return ECLIP_OK;
 }
 
@@ -868,6 +921,7 @@ extern "C" eclip_status eclip_alloc_set(eclip_model *model, const uint32_t *mask
         if (mask_id_of_group[g] >= model->pool->streams.size())
             return fail(ECLIP_EINVAL, "group %u: unknown mask id %u", g, mask_id_of_group[g]);
     std::lock_guard<std::mutex> lk(model->mu);
+    if (!model->has_alloc || !std::equal(model->mask_of_group.begin(), model->mask_of_group.end(), mask_id_of_group)) model->stamp++;
     model->mask_of_group.assign(mask_id_of_group, mask_id_of_group + n_groups);
     model->has_alloc = true;
     return ECLIP_OK;
@@ -937,8 +991,16 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
     }
     case ECLIP_OP_MAXPOOL: name = "maxpool_kernel"; break;
     case ECLIP_OP_GAP: name = "gap_kernel"; break;
-    case ECLIP_OP_LAYERNORM: name = "row_kernel"; out->workgroups = (uint32_t)((rows + 3) / 4); break;
-    case ECLIP_OP_SOFTMAX: name = "row_kernel"; out->workgroups = (uint32_t)((rows + 3) / 4); break;
+    case ECLIP_OP_LAYERNORM:
+    case ECLIP_OP_SOFTMAX: {
+        // 4 wavefronts per workgroup, each carrying 64 / (lanes per row) rows (see launch_row)
+        const int v = model->dtype == ECLIP_F32 ? (P.in.c % 4 ? 1 : 4) : (P.in.c % 8 ? 1 : 8);
+        const int nchunk = P.in.c / v, lpr = nchunk <= 48 ? 16 : 64;
+        const long per_wg = 4 * (64 / lpr);
+        name = "row_kernel";
+        out->workgroups = (uint32_t)((rows + per_wg - 1) / per_wg);
+        break;
+    }
     case ECLIP_OP_ATTENTION: name = "attention_kernel"; break;
     case ECLIP_OP_EMBED: name = "embed_kernel"; break;
     case ECLIP_OP_ELTWISE: name = "eltwise_kernel"; break;
@@ -1147,6 +1209,68 @@ static hipError_t launch_unit(eclip_model *m, uint32_t i, int batch, hipStream_t
     return launch_layer(m, i, batch, s, n_cu, d_in, i + 1 == n_layers ? d_out : nullptr, n_launched);
 }
 
+// The captured form of a request on (d_in, d_out, batch) under the current table, plans and workspace: looked up, or
+// captured now.  Every run of kernel groups that shares a pooled stream becomes one HIP graph.  It is captured from a
+// stream private to the model, in thread-local mode -- pooled streams may be shared by several workers, whose launches
+// must not land in (or break) another worker's capture -- and replayed on the pooled stream, whose queue is what
+// confines the kernels to its CUs; the cross-stream dependencies stay outside the graphs, as events between the segments.
+// Nothing runs during capture: the caller replays the entry right away.  At most 8 entries per model, least recently
+// used first out.
+static hipError_t graph_entry(eclip_model *m, const void *d_in, void *d_out, uint32_t batch, eclip_model::GraphEntry **out)
+{
+    *out = nullptr;
+    for (auto &g : m->graphs)
+        if (g.d_in == d_in && g.d_out == d_out && g.batch == batch && g.ws == m->ws && g.stamp == m->stamp) {
+            g.last_use = ++m->use_clock;
+            *out = &g;
+            return hipSuccess;
+        }
+    // stale entries (older stamp) and, beyond 8, the least recently used one make room
+    for (size_t k = 0; k < m->graphs.size();) {
+        if (m->graphs[k].stamp != m->stamp) {
+            for (auto &sg : m->graphs[k].segs) (void)hipGraphExecDestroy(sg.exec);
+            m->graphs.erase(m->graphs.begin() + k);
+        } else ++k;
+    }
+    if (m->graphs.size() >= 8) {
+        size_t lru = 0;
+        for (size_t k = 1; k < m->graphs.size(); ++k)
+            if (m->graphs[k].last_use < m->graphs[lru].last_use) lru = k;
+        for (auto &sg : m->graphs[lru].segs) (void)hipGraphExecDestroy(sg.exec);
+        m->graphs.erase(m->graphs.begin() + lru);
+    }
+    eclip_model::GraphEntry ge{d_in, d_out, batch, m->ws, m->stamp, ++m->use_clock, 0, {}};
+    const uint32_t n_layers = (uint32_t)m->layers.size();
+    hipError_t e = hipSuccess;
+    for (uint32_t i = 0; i < n_layers && e == hipSuccess;) {
+        const uint32_t g0 = m->group_of_layer[i];
+        const uint32_t mask_id = m->mask_of_group[g0];
+        const PoolStream &ps = m->pool->streams[mask_id];
+        e = hipStreamBeginCapture(m->capture_stream, hipStreamCaptureModeThreadLocal);
+        if (e != hipSuccess) break;
+        hipError_t le = hipSuccess;
+        while (i < n_layers && le == hipSuccess && m->pool->streams[m->mask_of_group[m->group_of_layer[i]]].stream == ps.stream) {
+            uint32_t consumed = 1;
+            le = launch_unit(m, i, (int)batch, m->capture_stream, (int)ps.n_cu, d_in, (float *)d_out, &ge.n_kernels, &consumed);
+            i += consumed;
+        }
+        hipGraph_t graph = nullptr;
+        e = hipStreamEndCapture(m->capture_stream, &graph);  // always ended, so that the stream is usable again
+        if (le != hipSuccess) e = le;
+        hipGraphExec_t exec = nullptr;
+        if (e == hipSuccess) e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        if (graph) (void)hipGraphDestroy(graph);
+        if (e == hipSuccess) ge.segs.push_back(eclip_model::GraphSeg{exec, mask_id, g0});
+    }
+    if (e != hipSuccess) {
+        for (auto &sg : ge.segs) (void)hipGraphExecDestroy(sg.exec);
+        return e;
+    }
+    m->graphs.push_back(std::move(ge));
+    *out = &m->graphs.back();
+    return hipSuccess;
+}
+
 // The body of eclip_submit, with the model's mutex held.
 static eclip_status submit_locked(eclip_model *model, const void *d_in, void *d_out, uint32_t batch, eclip_req **out)
 {
@@ -1176,6 +1300,22 @@ static eclip_status submit_locked(eclip_model *model, const void *d_in, void *d_
     // one ended on another stream (on the same stream, queue order already serialises them)
     if (model->last_done && model->last_stream != cur) SUB_TRY(hipStreamWaitEvent(cur, model->last_done, 0));
     if (r->timed) SUB_TRY(hipEventRecord(r->t_start, cur));
+    if (model->use_graphs) {
+        eclip_model::GraphEntry *ge = nullptr;
+        SUB_TRY(graph_entry(model, d_in, d_out, batch, &ge));
+        for (size_t k = 0; ge && k < ge->segs.size() && e == hipSuccess; ++k) {
+            const eclip_model::GraphSeg &sg = ge->segs[k];
+            const PoolStream &ps = pool->streams[sg.mask_id];
+            if (ps.stream != cur) {
+                SUB_TRY(hipEventRecord(model->switch_events[sg.first_group], cur));
+                SUB_TRY(hipStreamWaitEvent(ps.stream, model->switch_events[sg.first_group], 0));
+                cur = ps.stream;
+                r->n_switches++;
+            }
+            SUB_TRY(hipGraphLaunch(sg.exec, cur));
+        }
+        if (ge) r->n_kernels = ge->n_kernels;
+    } else {
     uint32_t prev_group = 0;
     for (uint32_t i = 0; i < n_layers && e == hipSuccess;) {
         const uint32_t g = model->group_of_layer[i];
@@ -1191,6 +1331,7 @@ static eclip_status submit_locked(eclip_model *model, const void *d_in, void *d_
         uint32_t consumed = 1;
         SUB_TRY(launch_unit(model, i, (int)batch, cur, (int)ps.n_cu, d_in, (float *)d_out, &r->n_kernels, &consumed));
         i += consumed;
+    }
     }
     if (r->timed) SUB_TRY(hipEventRecord(r->t_done, cur));
     SUB_TRY(hipEventRecord(r->done, cur));
@@ -1239,6 +1380,21 @@ extern "C" eclip_status eclip_submit_static(eclip_model *model, const void *d_in
     const eclip_status st = submit_locked(model, d_in, d_out, batch, out);
     model->ws = model->d_ws;
     return st;
+}
+
+extern "C" eclip_status eclip_model_graphs(eclip_model *model, int enable)
+{
+    if (!model) return fail(ECLIP_EINVAL, "model is null");
+    std::lock_guard<std::mutex> lk(model->mu);
+    if (model->inflight) return fail(ECLIP_ESTATE, "%u requests still in flight", model->inflight);
+    HIP_TRY(hipSetDevice(model->pool->device));
+    if (enable && !model->capture_stream) HIP_TRY(hipStreamCreateWithFlags(&model->capture_stream, hipStreamNonBlocking));
+    model->use_graphs = enable != 0;
+    if (!enable) {
+        HIP_TRY(hipDeviceSynchronize());
+        drop_graphs(model);
+    }
+    return ECLIP_OK;
 }
 
 extern "C" eclip_status eclip_model_timing(eclip_model *model, int enable)
@@ -1415,6 +1571,7 @@ extern "C" eclip_status eclip_model_tune(eclip_model *model, uint32_t mask_id, u
         // the cost model's plan stays unless a measured one beats it clearly: its picks keep independent layers on the
         // kernel that can share a launch, which a per-layer timing does not see
         model->tuned[key] = best_ms < 0.95f * own_ms ? cand[best] : own;
+        model->stamp++;
         ++n_tuned;
     }
     for (hipEvent_t e : ev)

@@ -502,61 +502,74 @@ __global__ __launch_bounds__(256) void gap_finish_kernel(const float *part_in, T
     else Cvt<T>::store(y + idx, s);
 }
 
-// ---------------- row kernels: one wavefront per row, the row lives in registers ----------------------------
-// lane l owns chunks l, l+64, ... (V elements each); NCH chunks per lane at most.
-template <typename T, int V, int NCH, bool SOFTMAX>
+// ---------------- row kernels: LPR lanes per row, the row lives in registers ----------------------------------
+// A row is shared by LPR lanes of a wavefront (16, 32 or 64), which therefore carries 64 / LPR rows at a time; lane l of
+// a row's group owns chunks l, l + LPR, ... (V elements each), NCH chunks per lane at most.  Narrow rows on a whole
+// wavefront leave lanes idle and very few bytes in flight per wavefront (a 384-element row is 48 chunks of 16 bytes: a
+// quarter of the lanes had nothing to do and a wavefront had 768 bytes on their way); with 16 lanes per row every lane
+// works, the reductions take 4 exchanges instead of 6, and a wavefront has four rows in flight.
+template <typename T, int V, int NCH, int LPR, bool SOFTMAX>
 __global__ __launch_bounds__(256) void row_kernel(RowArgs a)
 {
-    const int lane = threadIdx.x & 63;
-    const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= a.rows) return;
+    constexpr int RPW = 64 / LPR;                     // rows per wavefront
+    const int lane = threadIdx.x & 63, sub = lane & (LPR - 1);
+    const long row = ((long)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LPR;
+    const bool live = row < a.rows;                   // lanes of rows past the end still take part in the exchanges
     const int nchunk = a.width / V;
-    const T *x = (const T *)a.x + row * a.width;
-    const T *r = a.res ? (const T *)a.res + row * a.width : nullptr;
+    const T *x = (const T *)a.x + (live ? row : 0) * a.width;
+    const T *r = a.res ? (const T *)a.res + (live ? row : 0) * a.width : nullptr;
     float v[NCH][V];
     float s = 0.0f, mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-        const int ch = lane + j * 64;
-        if (ch < nchunk) {
-            Pack<T, V>::load(x + ch * V, v[j]);
-            if (r) {
+        const int ch = sub + j * LPR;
+        if (ch < nchunk) Pack<T, V>::load(x + ch * V, v[j]);
+    }
+    if (r) {
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+            const int ch = sub + j * LPR;
+            if (ch < nchunk) {
                 float rv[V];
                 Pack<T, V>::load(r + ch * V, rv);
 #pragma unroll
                 for (int i = 0; i < V; ++i) v[j][i] += rv[i];
             }
-#pragma unroll
-            for (int i = 0; i < V; ++i) { s += v[j][i]; mx = fmaxf(mx, v[j][i]); }
         }
     }
+#pragma unroll
+    for (int j = 0; j < NCH; ++j)
+        if (sub + j * LPR < nchunk)
+#pragma unroll
+            for (int i = 0; i < V; ++i) { s += v[j][i]; mx = fmaxf(mx, v[j][i]); }
     float scale, shift;   // y = (v - shift) * scale  (LayerNorm)   |   y = exp(v - shift) * scale (softmax)
     if (SOFTMAX) {
-        mx = wave_max(mx);
+        mx = group_max<LPR>(mx);
         float es = 0.0f;
 #pragma unroll
         for (int j = 0; j < NCH; ++j)
-            if (lane + j * 64 < nchunk)
+            if (sub + j * LPR < nchunk)
 #pragma unroll
                 for (int i = 0; i < V; ++i) { v[j][i] = __expf(v[j][i] - mx); es += v[j][i]; }
-        es = wave_sum(es);
+        es = group_sum<LPR>(es);
         scale = 1.0f / es;
         shift = 0.0f;
     } else {
-        const float mean = wave_sum(s) / (float)a.width;
+        const float mean = group_sum<LPR>(s) / (float)a.width;
         float q = 0.0f;
 #pragma unroll
         for (int j = 0; j < NCH; ++j)
-            if (lane + j * 64 < nchunk)
+            if (sub + j * LPR < nchunk)
 #pragma unroll
                 for (int i = 0; i < V; ++i) { const float d = v[j][i] - mean; q += d * d; }
-        const float var = wave_sum(q) / (float)a.width;
+        const float var = group_sum<LPR>(q) / (float)a.width;
         scale = rsqrtf(var + a.eps);
         shift = mean;
     }
+    if (!live) return;
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
-        const int ch = lane + j * 64;
+        const int ch = sub + j * LPR;
         if (ch < nchunk) {
             float o[V];
 #pragma unroll
@@ -586,35 +599,55 @@ __global__ __launch_bounds__(256) void row_kernel(RowArgs a)
 }
 
 // ---------------- element-wise epilogue ---------------------------------------------------------------------
-template <typename T, int V>
-__global__ __launch_bounds__(256) void eltwise_kernel(EltArgs a, long total)
+// A thread handles U vectors, `stride` vectors apart (so that a wavefront's accesses stay contiguous for every one of
+// them), and issues all of its loads before the arithmetic of the first.
+template <typename T, int V, int U>
+__global__ __launch_bounds__(256) void eltwise_kernel(EltArgs a, long total, long stride)
 {
-    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const unsigned cv = (unsigned)(a.width / V), ui = (unsigned)idx;
-    const int c = (int)(ui % cv) * V;
-    const long off = (long)(ui / cv) * a.width + c;
-    float v[V];
-    Pack<T, V>::load((const T *)a.x + off, v);
-    if (a.bias) {
-        float t[V];
-        Pack<T, V>::load((const T *)a.bias + c, t);
+    const long idx0 = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const unsigned cv = (unsigned)(a.width / V);
+    float v[U][V], t[U][V];
+    long off[U];
+    int c[U];
+    bool ok[U];
 #pragma unroll
-        for (int i = 0; i < V; ++i) v[i] += t[i];
+    for (int u = 0; u < U; ++u) {
+        const long idx = idx0 + u * stride;
+        ok[u] = idx < total;
+        const unsigned ui = (unsigned)(ok[u] ? idx : 0);
+        c[u] = (int)(ui % cv) * V;
+        off[u] = (long)(ui / cv) * a.width + c[u];
+        if (ok[u]) Pack<T, V>::load((const T *)a.x + off[u], v[u]);
     }
     if (a.res) {
-        float t[V];
-        Pack<T, V>::load((const T *)a.res + off, t);
 #pragma unroll
-        for (int i = 0; i < V; ++i) v[i] += t[i];
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) {
+                Pack<T, V>::load((const T *)a.res + off[u], t[u]);
+#pragma unroll
+                for (int i = 0; i < V; ++i) v[u][i] += t[u][i];
+            }
+    }
+    if (a.bias) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) {
+                Pack<T, V>::load((const T *)a.bias + c[u], t[u]);
+#pragma unroll
+                for (int i = 0; i < V; ++i) v[u][i] += t[u][i];
+            }
     }
 #pragma unroll
-    for (int i = 0; i < V; ++i) v[i] = apply_act(a.act, v[i]);
-    if (a.y32) {
+    for (int u = 0; u < U; ++u) {
+        if (!ok[u]) continue;
 #pragma unroll
-        for (int i = 0; i < V; ++i) a.y32[off + i] = v[i];
-    } else {
-        Pack<T, V>::store((T *)a.y + off, v);
+        for (int i = 0; i < V; ++i) v[u][i] = apply_act(a.act, v[u][i]);
+        if (a.y32) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) a.y32[off[u] + i] = v[u][i];
+        } else {
+            Pack<T, V>::store((T *)a.y + off[u], v[u]);
+        }
     }
 }
 
@@ -967,17 +1000,25 @@ hipError_t launch_gapfc(const void *x, const void *w_blocked, const void *bias, 
 template <bool SOFTMAX>
 static hipError_t launch_row(const RowArgs &a, hipStream_t s)
 {
-    const dim3 grid(blocks_for(a.rows, 4)), block(256);
+    // rows of up to 48 chunks share a wavefront four at a time (16 lanes each: softmax over 384 keys 62 -> 69 % of the HBM
+    // peak); wider rows take a whole wavefront (two rows of 128 chunks per wavefront on 32 lanes each measured slower:
+    // LayerNorm over 1024 elements 72 -> 69 %)
+#define ROWK(T, V, NCH, LPR) \
+    hipLaunchKernelGGL((row_kernel<T, V, NCH, LPR, SOFTMAX>), dim3(blocks_for(a.rows, 4 * (64 / LPR))), dim3(256), 0, s, a)
 #define CALL(T, V)                                                                                  \
     {                                                                                               \
-        const int per_lane = (a.width / V + 63) / 64;                                               \
-        if (per_lane <= 2) hipLaunchKernelGGL((row_kernel<T, V, 2, SOFTMAX>), grid, block, 0, s, a);      \
-        else if (per_lane <= 4) hipLaunchKernelGGL((row_kernel<T, V, 4, SOFTMAX>), grid, block, 0, s, a); \
-        else if (per_lane <= 16) hipLaunchKernelGGL((row_kernel<T, V, 16, SOFTMAX>), grid, block, 0, s, a); \
+        const int nchunk = a.width / V;                                                             \
+        if (nchunk <= 16) ROWK(T, V, 1, 16);                                                        \
+        else if (nchunk <= 32) ROWK(T, V, 2, 16);                                                   \
+        else if (nchunk <= 48) ROWK(T, V, 3, 16);                                                   \
+        else if (nchunk <= 128) ROWK(T, V, 2, 64);                                                  \
+        else if (nchunk <= 256) ROWK(T, V, 4, 64);                                                  \
+        else if (nchunk <= 1024) ROWK(T, V, 16, 64);                                                \
         else return hipErrorInvalidValue;                                                           \
     }
     ECLIP_DISPATCH(a.dtype, a.width, CALL);
 #undef CALL
+#undef ROWK
     return hipGetLastError();
 }
 hipError_t launch_layernorm(const RowArgs &a, int, hipStream_t s) { return launch_row<false>(a, s); }
@@ -988,7 +1029,8 @@ hipError_t launch_eltwise(const EltArgs &a, int, hipStream_t s)
 #define CALL(T, V)                                                                                           \
     {                                                                                                        \
         const long total = a.rows * (a.width / V);                                                           \
-        hipLaunchKernelGGL((eltwise_kernel<T, V>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a, total); \
+        /* one vector per thread: four per thread with all loads issued first measured slower (copy 79 -> 71 % of the HBM peak) */ \
+        hipLaunchKernelGGL((eltwise_kernel<T, V, 1>), dim3(blocks_for(total, 256)), dim3(256), 0, s, a, total, 0L); \
     }
     ECLIP_DISPATCH(a.dtype, a.width, CALL);
 #undef CALL

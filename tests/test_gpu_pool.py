@@ -277,6 +277,44 @@ def test_served_group_profile_counts_the_launches_that_are_served():
         g.free()
 
 
+def test_replayed_graphs_stay_on_the_streams_cus_and_give_the_same_bits():
+    """eclip_model_graphs: a request is captured once per (buffers, batch, table) as one HIP graph per run of kernel groups
+    on the same stream and replayed afterwards.  A graph replayed on a CU-masked stream must stay on that stream's CUs;
+    the replayed request must give the bits of the launched one, on every replay, across table changes, with the program's
+    own eager work in between (the layout kernels of the input copies, synchronisations)."""
+    pool = shared_pool()
+    for mid, n in [(1, 32), (2, 64), (4, 192)]:
+        ids = pool.probe_graph(mid, 2048)
+        assert len(set(ids.tolist())) == n and set(ids.tolist()) == set(pool.probe(mid, 2048).tolist())
+    m = wl.resnet(18, seed=1, hw=64)
+    g = GpuModel(m, max_batch=2)
+    try:
+        xs = [wl.make_input(m, 2, seed=50 + i) for i in range(3)]
+        tables = ([1, 1, 1, 1], [1, 3, 3, 2], [4, 1, 4, 1])
+        ref = {(ti, xi): g.run(x, table=list(t)) for ti, t in enumerate(tables) for xi, x in enumerate(xs)}
+        g.h.graphs(True)
+        d_in = [dev_input(m, x) for x in xs]
+        outs = [torch.zeros(m.out_shape(2), dtype=torch.float32, device="cuda") for _ in xs]
+        for rep in range(3):                                    # replays after the first, with eager work between them
+            for ti, t in enumerate(tables):
+                g.h.alloc_set(list(t))
+                for xi in range(3):
+                    outs[xi].zero_()
+                    r = g.h.submit(d_in[xi].data_ptr(), outs[xi].data_ptr(), 2)
+                    _, n_k, n_sw = r.wait(timing=True)
+                    assert n_sw == sum(1 for i in range(1, 4) if t[i] != t[i - 1]) and n_k >= 19
+                    torch.cuda.synchronize()
+                    assert np.array_equal(outs[xi].cpu().numpy().astype(np.float64), ref[(ti, xi)]), (rep, ti, xi)
+        # batch 1 through the same buffers is another captured request
+        r = g.h.submit(d_in[0].data_ptr(), outs[0].data_ptr(), 1)
+        r.wait()
+        assert np.array_equal(outs[0][:1].cpu().numpy().astype(np.float64), ref[(2, 0)][:1])
+        g.h.graphs(False)
+        assert np.array_equal(g.run(xs[1], table=[1, 1, 1, 1]), ref[(0, 1)])
+    finally:
+        g.free()
+
+
 def test_measured_plan_selection_keeps_the_results():
     """eclip_model_tune times every candidate plan of every GEMM problem on a stream and remembers the fastest for that CU
     count; the logits must stay within tolerance of the oracle (another tile only reassociates fp32 sums), the same table

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
 
 def solve_lib(p):
     return ec.eclip_alloc_solve(p.total_cus, p.configs, [w.n_kernels for w in p.workers], [w.beta for w in p.workers],
-                                p.switch_max, p.overlap_mode, p.alpha_ppm, p.granule, p.max_configs, p.switch_cost)
+                                p.switch_max, p.overlap_mode, p.alpha_ppm, p.granule, p.max_configs, p.switch_cost, p.max_configs_w)
 
 
 CASES = []
@@ -279,3 +279,36 @@ def test_policies_reject_malformed_input():
     with pytest.raises(ec.EclipError) as e:
         ec.eclip_alloc_kernel_wise([32, 64], [[]], 5)                 # a worker without units
     assert e.value.status == ec.EINVAL
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_per_worker_stream_limits_match_exhaustive_oracle_bit_exact(seed):
+    """A global budget of 4 usable streams split unevenly over the workers: every composition is one solve with per-worker
+    limits on the number of distinct configurations; each must equal exhaustive search, and the best of them is what a
+    global limit would give."""
+    units, configs = ([3, 2, 2], [32, 64, 128, 256]) if seed % 2 else ([3, 3], [32, 64, 128, 192, 256])
+    p = wl.random_problem(900 + seed, len(units), units, configs, 256, 2, oa.OVERLAP_EXCESS, "scaling")
+    p.switch_cost = 300 * (seed % 3)
+    comps = [(2, 1, 1), (1, 2, 1), (1, 1, 2)] if len(units) == 3 else [(2, 2), (3, 1), (1, 3)]
+    best = None
+    for comp in comps:
+        p.max_configs_w = list(comp)
+        exp = oa.solve_exhaustive(p)
+        got = solve_lib(p)
+        assert got[0] == exp[0] and got[1] == exp[1] and got[2] == exp[2]
+        assert all(len(set(a)) <= k for a, k in zip(got[0], comp))
+        best = exp[1] if best is None else min(best, exp[1])
+    # brute force over the union: total distinct (worker, configuration) pairs <= 4
+    import itertools
+    p.max_configs_w = None
+    glob = None
+    for flat in itertools.product(range(len(configs)), repeat=sum(units)):
+        assign, pos = [], 0
+        for g in units:
+            assign.append(flat[pos:pos + g]); pos += g
+        if sum(len(set(a)) for a in assign) > 4:
+            continue
+        r = oa.evaluate(p, assign)
+        if r is not None:
+            glob = r[0] if glob is None else min(glob, r[0])
+    assert best == glob

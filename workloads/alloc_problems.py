@@ -30,6 +30,7 @@ class AllocProblem:
     granule: int = 1                        # TABLE mode: CUs per granule
     max_configs: int = 0                    # distinct configurations a worker may use (0 = no limit)
     switch_cost: int = 0                    # ns added to a worker's time per configuration switch
+    max_configs_w: Optional[List[int]] = None   # per-worker limits on distinct configurations (replace max_configs)
 
 
 def random_problem(seed: int, n_workers: int, units: List[int], configs: List[int], total_cus: int,

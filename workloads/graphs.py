@@ -623,4 +623,12 @@ def config_models(cfg: int, small: bool = False) -> List[Model]:
         if small:
             return [resnext((2, 1, 1), 8, 4, seed=23, hw=64, res_scale=0.5), shufflenet(4, (2, 2), 128, seed=24, hw=64)]
         return [resnext(seed=23, res_scale=0.5), shufflenet(seed=24)]
+    # a two-worker mix of large-batch models whose kernel groups need very different CU counts: VGG-16's convolution
+    # blocks scale with the CUs they get while its fully connected block streams 250 MB of weights and saturates the
+    # memory system on a fraction of them; BERT-large is matrix-core-bound throughout (the paper's "feasible combinations"
+    # of a high- and a low-CU-need model, Sec. IV-A)
+    if cfg == 7:
+        if small:
+            return [vgg16(seed=31, hw=32, width=16, fc=256), bert(2, 128, 4, 512, 48, vocab=1000, seed=32, dtype=DT_BF16)]
+        return [vgg16(seed=31), bert(24, 1024, 16, 4096, 384, seed=32, dtype=DT_BF16)]
     raise ValueError(cfg)
