@@ -306,7 +306,7 @@ def traffic_from(cfg, fetch_csv, write_csv, command):
 # ---------------------------------------------------------------------------------------------------
 # single kernels at roofline shapes
 # ---------------------------------------------------------------------------------------------------
-def kernels_mode(only=None):
+def kernels_mode(only=None, extra_gemms=None):
     import workloads as wl
     import workloads.graphs as G
     import paper_2506_12598_amd as ec
@@ -379,8 +379,12 @@ def kernels_mode(only=None):
              ("proj", lambda: gemm("BERT-large projection b4", 1536, 1024, 1024)),
              ("base_ffn1", lambda: gemm("BERT-base FFN1 b1", 128, 768, 3072))]
     for key, fn in cases:
-        if only is None or key in only.split(","):
+        if (only is None and not extra_gemms) or (only is not None and key in only.split(",")):
             fn()
+    for shape in (extra_gemms or "").split(";"):
+        if shape:
+            m_, n_, k_ = (int(v) for v in shape.split(","))
+            gemm("linear", m_, k_, n_)
     pool.destroy()
     print(f"{'case':66s} {'kernel':18s} {'bound':5s} {'achieved':>10s} {'peak':>8s} {'unit':8s} {'frac':>6s} {'us/launch':>10s}")
     for name, kern, bound, ach, peak, unit, us in rows:
@@ -590,6 +594,7 @@ def main():
     ap.add_argument("--no-tune", action="store_true", help="keep the planner's cost-model choices (skip eclip_model_tune)")
     ap.add_argument("--policy", default="eclip", choices=["eclip", "unpart_a", "unpart_b"], help="policy of the timed region")
     ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
+    ap.add_argument("--gemm", default=None, help="with --kernels: time linear layers of these shapes, 'M,N,K;M,N,K;...'")
     ap.add_argument("--only", default=None, help="with --kernels: comma-separated case keys (layernorm, softmax, maxpool, dwconv, "
                     "gap, gelu, copy, fc, gemm8192, gemm4096, ffn1, ffn2, qkv, proj, base_ffn1)")
     ap.add_argument("--policies", action="store_true", help="compare the paper's partitioning scenarios and sweep the switch budget")
@@ -615,7 +620,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.init()
     if args.kernels:
-        kernels_mode(args.only)
+        kernels_mode(args.only, args.gemm)
         return
     if args.characterize:
         characterize_mode()

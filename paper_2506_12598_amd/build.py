@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libeclip.so")
-SOURCES = ["eclip.cpp", "alloc_solver.cpp", "k_gemm.hip", "k_wsk.hip", "k_mem.hip", "k_attn.hip"]
+SOURCES = ["eclip.cpp", "alloc_solver.cpp", "k_gemm.hip", "k_wsk.hip", "k_mem.hip", "k_attn.hip", "k_gconv.hip"]
 
 
 def pp_tile_ids():

@@ -361,6 +361,7 @@ struct LayerPlan {
     size_t out_off = 0;        // byte offset of this layer's output in the activation arena
     size_t w_dev = NONE, b_dev = NONE, g_dev = NONE, be_dev = NONE;   // byte offsets in the device weight arena
     bool gemm = false;         // runs on the matrix-core GEMM kernel
+    int gc_super = 0;          // grouped CONV on the matrix cores: groups per super-group (0: the direct kernel)
     bool pair_next = false;    // this layer and the next are independent GEMM layers of one group: one launch may carry both
     bool gapfc_next = false;   // global average pool whose only reader is the linear layer that follows: one launch may do both
 };
@@ -541,6 +542,10 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
             if (L.b_off >= 0 && (st = check_off(L.b_off, L.c, "bias", i))) return st;
             if (!f32 && L.groups == 1 && in.c % 8) return fail(ECLIP_EINVAL, "layer %u: 16-bit CONV needs an input channel count that is a multiple of 8 (got %d)", i, in.c);
             P.gemm = !f32 && L.groups == 1;
+            if (grouped && !getenv("ECLIP_GCONV_DIRECT")) {
+                int S = 0;
+                if (gconv_mfma_pick(L.groups, P.in_c_logical / L.groups, L.c / L.groups, &S)) P.gc_super = S;
+            }
             break;
         }
         case ECLIP_OP_LINEAR: {
@@ -689,6 +694,35 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
             const bool dw = L.op == ECLIP_OP_CONV && L.groups > 1 && L.groups == cin_l && L.c == L.groups;
             const bool grouped = L.op == ECLIP_OP_CONV && L.groups > 1 && !dw;
             const E *src = w + L.w_off;
+            if (grouped && P.gc_super) {
+                // Block-diagonal dense weights of every super-group (gc_super neighbouring groups), in the 1 KB blocks of
+                // 16 output channels x 32 k that the matrix instruction consumes: block (sg, nb, t) at
+                // ((sg * NB + nb) * KT + t) KB with t = tap * (SI / 32) + kb; lane l of a block owns
+                // W[16 nb + (l & 15)][32 kb + 8 (l >> 4) .. +7] of the super-group's SO x SI block of that tap, which is
+                // zero wherever output and input channel belong to different groups.
+                const int cig = cin_l / L.groups, cog = L.c / L.groups, S = P.gc_super;
+                const size_t SI = (size_t)S * cig, SO = (size_t)S * cog, n_sg = (size_t)L.groups / S;
+                const size_t KBS = SI / 32, NB = SO / 16, KT = (size_t)kh * kw * KBS;
+                size_t off;
+                put(arena, cursor, nullptr, n_sg * NB * KT * 512 * es, &off);
+                E *dst = reinterpret_cast<E *>(arena.data() + off);
+                memset(dst, 0, n_sg * NB * KT * 512 * es);
+                for (size_t sg = 0; sg < n_sg; ++sg)
+                    for (size_t nb = 0; nb < NB; ++nb)
+                        for (size_t t = 0; t < KT; ++t)
+                            for (int l = 0; l < 64; ++l) {
+                                const size_t tap = t / KBS, kb = t % KBS;
+                                const size_t n = nb * 16 + (size_t)(l & 15), k0 = kb * 32 + (size_t)(l >> 4) * 8;
+                                E *d8 = dst + (((sg * NB + nb) * KT + t) * 64 + (size_t)l) * 8;
+                                for (int e = 0; e < 8; ++e) {
+                                    const size_t k = k0 + e;
+                                    if (n / cog != k / cig) continue;                  // off the diagonal
+                                    const size_t co = sg * SO + n, ci = k % cig;
+                                    d8[e] = src[(co * cig + ci) * kh * kw + tap];
+                                }
+                            }
+                P.w_dev = off;
+            } else
             if (grouped) {                              // [cout][cig][kh][kw] -> [cout][kh][kw][cig]
                 const int cig = cin_l / L.groups;
                 std::vector<E> t((size_t)L.c * kh * kw * cig);
@@ -974,7 +1008,7 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
             out->workgroups = (uint32_t)pl.tiles * (uint32_t)pl.splits;
             out->launches = pl.splits > 1 ? 2 : 1;
         } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1 && !(P.L.groups == P.in.c && P.L.c == P.L.groups)) {
-            name = "gconv_kernel";
+            name = P.gc_super ? "gconv_mfma_kernel" : "gconv_kernel";
             out->workgroups = (uint32_t)((rows * P.L.c + 255) / 256);
         } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1) {
             DwConvArgs da{};
@@ -1051,7 +1085,7 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
         } else if (L.op == ECLIP_OP_CONV && L.groups > 1 && !(L.groups == g.Cin && L.c == L.groups)) {
             GConvArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y, g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout,
                         g.KH, g.KW, g.stride, g.pad, L.groups, L.act, dt};
-            e = launch_gconv(a, n_cu, s);
+            e = P.gc_super ? launch_gconv_mfma(a, P.gc_super, n_cu, s) : launch_gconv(a, n_cu, s);
         } else if (L.op == ECLIP_OP_CONV && L.groups > 1) {
             DwConvArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y, g.B, g.H, g.W, L.c, g.Ho, g.Wo, g.KH, g.KW, g.stride, g.pad, L.act, dt};
             e = launch_dwconv(a, n_cu, s);

@@ -86,6 +86,11 @@ struct GConvArgs {
     int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, groups, act, dtype;
 };
 hipError_t launch_gconv(const GConvArgs &a, int n_cu, hipStream_t s);
+// The same on the matrix cores (k_gconv.hip): S neighbouring groups form a dense block-diagonal problem.  gconv_mfma_pick
+// returns false when no S <= 16 dividing `groups` makes S*cig a multiple of 32 and S*cog a multiple of 16; the weights
+// must then be in the direct kernel's layout, otherwise in the super-group blocks described in k_gconv.hip.
+bool gconv_mfma_pick(int groups, int cig, int cog, int *S_out);
+hipError_t launch_gconv_mfma(const GConvArgs &a, int S, int n_cu, hipStream_t s);
 // y[m][0 .. c0) = a[m][:], y[m][c0 .. c0 + c1) = b[m][:]
 hipError_t launch_concat(const void *a, const void *b, void *y, long rows, int c0, int c1, int dtype, hipStream_t s);
 // y[m][j] = x[m][(j % groups) * (c / groups) + j / groups]

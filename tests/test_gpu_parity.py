@@ -5,6 +5,8 @@ configurations max-abs error <= 2e-2 x (max - min of the oracle output).  Single
 rounding is float32 accumulation are held to a much tighter bound so that a dropped K-slice, a wrong tap
 or a transposed operand cannot hide inside the model-level tolerance.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -18,6 +20,7 @@ if not torch.cuda.is_available():
     pytest.skip("no GPU", allow_module_level=True)
 
 from gpu_util import GpuModel, run_gpu, rel_to_range, shared_pool  # noqa: E402
+import paper_2506_12598_amd as ec  # noqa: E402
 
 TOL_16 = 2e-2
 TOL_F32 = 1e-4
@@ -338,6 +341,9 @@ def test_every_gemm_variant_forced(force):
         check(m, batch=2, tol=2.0 ** -8)
         m = wl.single_layer("conv", wl.DT_BF16, seed=17, cin=64, cout=40, h=15, w=18, k=3, stride=2, pad=1, bias_std=0.5, residual=True)
         check(m, batch=2, tol=2.0 ** -7)
+        # 128 input channels under a 3x3 window: two K steps of 64 (four of 32) per tap in the uniform-tap form
+        m = wl.single_layer("conv", wl.DT_BF16, seed=18, cin=128, cout=88, h=11, w=13, k=3, stride=1, pad=1, act=wl.ACT_RELU, bias_std=0.5)
+        check(m, batch=2, tol=2.0 ** -8)
     finally:
         os.environ.pop("ECLIP_GEMM_FORCE", None)
 
@@ -350,6 +356,65 @@ def test_grouped_conv(cin, cout, groups, k, s, res, dt):
     m = wl.single_layer("conv", dt, seed=cin + groups, cin=cin, cout=cout, h=13, w=11, k=k, stride=s, pad=k // 2, groups=groups,
                         act=wl.ACT_RELU, bias_std=0.5, residual=res)
     check(m, batch=2, tol=4e-3 if not res else 8e-3)
+
+
+def _kernel_of_single_layer(m):
+    h = ec.Model(shared_pool(), m, wl.to_storage(m.weights, m.dtype), max_batch=1)
+    try:
+        return h.kernel_info(0, 0, 1)["kernel"]
+    finally:
+        h.free()
+
+
+# Grouped convolution on the matrix cores: S neighbouring groups as one block-diagonal dense problem.  The cases cover
+# S = 8, 4, 2, 1 (ResNeXt's four stages), super-groups deeper than 32 channels (several 32-channel blocks per tap),
+# output blocks that do not fill a chunk of four (48 channels per super-group), six chunks per super-group, stride 2,
+# a 5 x 5 window, and an image large enough for two pixel blocks per wavefront; every one is also run through the
+# direct kernel, which the same layers took before.
+GCONV_MFMA_CASES = [
+    # cin, cout, groups, k, stride, h, w, act, residual
+    (128, 128, 32, 3, 1, 19, 17, wl.ACT_RELU, False),       # cig 4: S = 8
+    (256, 256, 32, 3, 2, 19, 17, wl.ACT_RELU, True),        # cig 8: S = 4, stride 2
+    (512, 512, 32, 3, 1, 9, 7, wl.ACT_NONE, False),         # cig 16: S = 2
+    (1024, 1024, 32, 3, 1, 7, 7, wl.ACT_RELU, False),       # cig 32: S = 1
+    (384, 96, 8, 1, 1, 14, 14, wl.ACT_RELU, False),         # cig 48, cog 12: S = 4, 6 blocks of 32 k, 3 of 4 output blocks
+    (96, 384, 8, 1, 1, 14, 14, wl.ACT_RELU, True),          # cig 12, cog 48: S = 8 (the whole layer), 6 chunks
+    (128, 256, 2, 5, 1, 10, 12, wl.ACT_GELU, False),        # cig 64, 5 x 5: 50 steps
+    (256, 256, 32, 3, 1, 128, 128, wl.ACT_RELU6, False),    # 16384 pixels: two pixel blocks per wavefront
+]
+
+
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("direct", [False, True])
+@pytest.mark.parametrize("case", GCONV_MFMA_CASES, ids=lambda c: "x".join(str(v) for v in c[:7]))
+def test_grouped_conv_matrix_core_and_direct(case, direct, dt):
+    cin, cout, groups, k, s, h, w, act, res = case
+    if direct and h * w > 4096:
+        pytest.skip("the direct kernel is covered by the smaller cases")
+    m = wl.single_layer("conv", dt, seed=cin + cout + groups, cin=cin, cout=cout, h=h, w=w, k=k, stride=s, pad=k // 2, groups=groups,
+                        act=act, bias_std=0.5, residual=res)
+    if direct:
+        os.environ["ECLIP_GCONV_DIRECT"] = "1"
+    try:
+        assert _kernel_of_single_layer(m) == ("gconv_kernel" if direct else "gconv_mfma_kernel")
+        check(m, batch=1 if h * w > 4096 else 3, tol=4e-3 if not res else 8e-3)
+        if h * w > 4096:
+            # on the 32-CU stream the grid exceeds 16 workgroups per CU: two pixel blocks per wavefront
+            x = wl.make_input(m, 1)
+            g = GpuModel(m, max_batch=1)
+            try:
+                got = g.run(x, table=[1] * m.n_groups)
+            finally:
+                g.free()
+            assert rel_to_range(got, orc.run_model(m, x)) <= 4e-3
+    finally:
+        os.environ.pop("ECLIP_GCONV_DIRECT", None)
+
+
+def test_grouped_conv_without_a_matching_super_group_takes_the_direct_kernel():
+    # 3 groups of 16 -> 32 channels: no divisor of 3 makes the input span a multiple of 32
+    m = wl.single_layer("conv", wl.DT_BF16, seed=5, cin=48, cout=96, h=6, w=6, k=1, stride=1, pad=0, groups=3)
+    assert _kernel_of_single_layer(m) == "gconv_kernel"
 
 
 @pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
