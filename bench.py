@@ -303,10 +303,75 @@ def traffic_from(cfg, fetch_csv, write_csv, command):
     print(json.dumps(out, indent=1))
 
 
+def counters_from(csv_paths):
+    """Reduces counter_collection CSVs of `rocprofv3 --pmc ...` runs to the mean of every counter per kernel (template
+    arguments kept, so that tile shapes stay apart)."""
+    import csv
+    acc = {}
+    for path in csv_paths:
+        for r in csv.DictReader(open(path)):
+            name = r["Kernel_Name"].replace("void ", "").replace("eclip::(anonymous namespace)::", "").replace("eclip::", "")
+            name = name.split("(")[0][:96]
+            a = acc.setdefault(name, {}).setdefault(r["Counter_Name"], [0.0, 0])
+            a[0] += float(r["Counter_Value"]); a[1] += 1
+    for name in sorted(acc):
+        print(name)
+        for c in sorted(acc[name]):
+            v, n = acc[name][c]
+            print(f"    {c:34s} dispatches {n:6d}  mean {v / n:.6g}")
+
+
+def stats_from(trace_csv):
+    """Reduces the kernel_trace CSV of `rocprofv3 --kernel-trace -- python3 bench.py ...` to a table per kernel function:
+    all dispatches of the process, and those of the per-layer timing pass alone (between the last two probe_kernel
+    dispatches, which bench.py launches around that pass).  In that pass every layer runs 8 times back to back on its
+    worker's stream with nothing else on the GPU, which is what `roofline.avg_layer_us` times with HIP events.
+
+    The profiler stamps a dispatch's start when its queue reaches it, which for a queue that has run dry is long
+    before the host has even launched the kernel (one such row read 21 ms for a 5 us kernel), so the plain mean of
+    End - Start is useless.  Durations are therefore reduced per (template instantiation, grid size), i.e. per tile shape
+    and output size, to the median and to the mean over the dispatches within 8x that median (layers that share both
+    differ in K by at most 4x here); the table pools them per function, weighting by calls."""
+    import csv
+    import re
+    rd = csv.DictReader(open(trace_csv))
+    col = {c.lower(): c for c in rd.fieldnames}
+    c_name, c_st, c_en = col["kernel_name"], col["start_timestamp"], col["end_timestamp"]
+    rows = []
+    for r in rd:
+        full = r[c_name].replace("void ", "").replace("eclip::(anonymous namespace)::", "").replace("eclip::", "")
+        m = re.match(r"([\w:]+)", full)
+        rows.append((int(r[c_st]), int(r[c_en]), m.group(1) if m else full, full.split("(")[0] + " grid " + r.get(col.get("grid_size_x", ""), "")))
+    rows.sort()
+    marks = [i for i, r in enumerate(rows) if r[2] == "probe_kernel"]
+
+    def table(sel, title):
+        by_inst = {}
+        for i in sel:
+            st, en, fn, inst = rows[i]
+            by_inst.setdefault((fn, inst), []).append((en - st) / 1e3)
+        acc = {}
+        for (fn, inst), d in by_inst.items():
+            d.sort()
+            med = d[len(d) // 2]
+            kept = [v for v in d if v <= 8.0 * med]
+            a = acc.setdefault(fn, [0, 0, 0.0, 0.0])
+            a[0] += len(d); a[1] += len(kept); a[2] += sum(kept); a[3] += med * len(d)
+        tot = sum(a[2] for a in acc.values())
+        print(f"# {title}")
+        print(f"{'kernel':28s} {'calls':>9s} {'outliers':>9s} {'mean_us':>9s} {'median_us':>10s} {'share_%':>8s}")
+        for fn, a in sorted(acc.items(), key=lambda kv: -kv[1][2]):
+            print(f"{fn:28s} {a[0]:9d} {a[0] - a[1]:9d} {a[2] / a[1]:9.2f} {a[3] / a[0]:10.2f} {100.0 * a[2] / tot:8.2f}")
+
+    table(range(len(rows)), "all dispatches of the process (outliers: beyond 8x the median of their tile shape and grid, left out of the mean)")
+    if len(marks) >= 2:
+        table(range(marks[-2] + 1, marks[-1]), "per-layer timing pass (each layer 8 times back to back, alone on the GPU)")
+
+
 # ---------------------------------------------------------------------------------------------------
 # single kernels at roofline shapes
 # ---------------------------------------------------------------------------------------------------
-def kernels_mode(only=None, extra_gemms=None):
+def kernels_mode(only=None, extra_gemms=None, tune=True):
     import workloads as wl
     import workloads.graphs as G
     import paper_2506_12598_amd as ec
@@ -317,7 +382,8 @@ def kernels_mode(only=None, extra_gemms=None):
     def time_first(model, batch=1):
         h = ec.Model(pool, model, wl.to_storage(model.weights, model.dtype), max_batch=batch)
         h.alloc_set([0] * model.n_groups)
-        h.tune(0, batch, 2)
+        if tune:
+            h.tune(0, batch, 2)
         ns = h.profile_group(0, 0, batch, 5)[0]
         info = h.kernel_info(0, 0, batch)
         h.free()
@@ -591,6 +657,7 @@ def main():
                                                              "else 70%% of the measured closed-loop rate)")
     ap.add_argument("--switch-max", type=int, default=14)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true", help="run only the per-layer timing pass behind the `roofline` entry and print it")
     ap.add_argument("--no-tune", action="store_true", help="keep the planner's cost-model choices (skip eclip_model_tune)")
     ap.add_argument("--policy", default="eclip", choices=["eclip", "unpart_a", "unpart_b"], help="policy of the timed region")
     ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
@@ -600,6 +667,10 @@ def main():
     ap.add_argument("--policies", action="store_true", help="compare the paper's partitioning scenarios and sweep the switch budget")
     ap.add_argument("--slo", type=float, default=3.0, help="with --policies: Model-Wise latency target as a multiple of solo latency")
     ap.add_argument("--pmc-copy", action="store_true", help="also run the calibration copy (for rocprofv3 --pmc runs)")
+    ap.add_argument("--stats-from", default=None, metavar="KERNEL_TRACE_CSV",
+                    help="reduce the kernel_trace CSV of a `rocprofv3 --kernel-trace` run of this file to per-kernel tables and exit")
+    ap.add_argument("--counters-from", nargs="+", default=None, metavar="COUNTER_CSV",
+                    help="reduce counter_collection CSVs of `rocprofv3 --pmc` runs of this file to per-kernel means and exit")
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
                     help="reduce two rocprofv3 --pmc counter_collection CSVs to profiles/traffic_config<N>.json and exit")
     ap.add_argument("--characterize", action="store_true", help="CU-mask geometry, switch cost and stream-count sweep")
@@ -609,10 +680,16 @@ def main():
               "placed on different GPUs without any exchange step. Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    if args.stats_from:
+        stats_from(args.stats_from)
+        return
+    if args.counters_from:
+        counters_from(args.counters_from)
+        return
     if args.traffic_from:
         traffic_from(args.config, args.traffic_from[0], args.traffic_from[1],
                      "rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) --output-format csv -- python3 bench.py --pmc-copy "
-                     f"--config {args.config} --steps 200 --warmup 20 --window 0 --no-cpu-baseline")
+                     f"--config {args.config} --roofline-only")
         return
     import torch
     import workloads as wl
@@ -620,7 +697,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.init()
     if args.kernels:
-        kernels_mode(args.only, args.gemm)
+        kernels_mode(args.only, args.gemm, tune=not args.no_tune)
         return
     if args.characterize:
         characterize_mode()
@@ -668,6 +745,74 @@ def main():
     prof_pool = ec.Pool(masks)
     workers = [Worker(ec, torch, prof_pool, m, i, args.depth, batches[i]) for i, m in enumerate(models)]
     log(f"config {cfg}: loaded {n_w} models in {time.perf_counter() - t0:.1f}s, profiling pool of {len(masks)} masked streams")
+
+    def measure_roofline(pool):
+        # ---- roofline of the dominant kernel: HIP-event timings on the stream the kernels run on.  Each layer of each
+        # model is timed on that worker's unpartitioned stream (8 back-to-back launches per sample, see
+        # eclip_profile_group); layers are grouped by the kernel function that runs them; the matrix-core function
+        # with the largest launch-weighted time is reported against the roofline that bounds its work.
+        for w, wk in enumerate(workers):
+            wk.h.alloc_set([1 + w] * wk.model.n_groups)
+        pool.probe(0, 8)                 # marks the start of this pass in a kernel trace (see --stats-from)
+        per_kernel = {}
+        for w, wk in enumerate(workers):
+            ns_all = []
+            for g in range(wk.model.n_groups):
+                ns_all.extend(wk.h.profile_group(g, 1 + w, batch=prof_batch[w], iters=20 if cfg != 4 else 10))
+            work = gemm_work(wk.model, prof_batch[w])
+            for li, ns in enumerate(ns_all):
+                info = wk.h.kernel_info(li, 1 + w, prof_batch[w])
+                e = per_kernel.setdefault(info["kernel"], {"ns": 0.0, "bytes": 0.0, "flops": 0.0, "launches": 0, "layers": 0})
+                e["ns"] += ns
+                e["launches"] += info["launches"]
+                e["layers"] += 1
+                if work[li] is not None:
+                    e["bytes"] += work[li][0]
+                    e["flops"] += work[li][1]
+        pool.probe(0, 8)                 # ... and its end
+        total_ns = sum(v["ns"] for v in per_kernel.values())
+        # a layer whose K is cut over the grid runs two kernels (GEMM + slice sum): its time is attributed per launch
+        dom = max((k for k in per_kernel if per_kernel[k]["bytes"] > 0),
+                  key=lambda k: per_kernel[k]["ns"] * per_kernel[k]["layers"] / per_kernel[k]["launches"])
+        d = per_kernel[dom]
+        ai = d["flops"] / d["bytes"]
+        if ai > RIDGE:
+            ach, peak, unit, bound = d["flops"] / d["ns"] / 1e3, MFMA_PEAK_TFLOPS, "TFLOP/s", "mfma"
+        else:
+            ach, peak, unit, bound = d["bytes"] / d["ns"], HBM_PEAK_GBS, "GB/s", "hbm"
+        # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counters of an earlier profiled run of this workload;
+        # null when there is none or when a kernel source has changed since
+        traffic = None
+        if os.path.exists(traffic_path(cfg)):
+            t = json.load(open(traffic_path(cfg)))
+            if t.get("source_sha256") == source_hash() and dom in t["kernels"]:
+                traffic = t["kernels"][dom]["fetch_bytes_per_launch"] + t["kernels"][dom]["write_bytes_per_launch"]
+        roofline = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak, "traffic": traffic,
+                    "kernel": dom, "flop_per_byte": ai, "layers_per_step": d["layers"], "launches_per_step": d["launches"],
+                    "avg_layer_us": d["ns"] / d["layers"] / 1e3, "avg_bytes_per_layer": d["bytes"] / d["layers"],
+                    "achieved_tflops": d["flops"] / d["ns"] / 1e3, "achieved_gbs": d["bytes"] / d["ns"],
+                    "time_share_by_kernel": {k: v["ns"] / total_ns for k, v in per_kernel.items()}}
+        return roofline
+
+    if args.roofline_only:
+        # only the per-layer timing pass behind the `roofline` entry: models on one full-GPU stream each (the unpartitioned
+        # policy), plans tuned for that CU count.  Short enough to run under a profiler with a trace small enough to keep.
+        all_cus = ec.eclip_mask_layout(256, 256, 1, 0, 1)
+        pool = ec.Pool([(None, -1)] + [(all_cus, w) for w in range(n_w)])
+        for wk in workers:
+            wk.h.rebind(pool)
+        prof_pool.destroy()
+        if not args.no_tune:
+            for w, wk in enumerate(workers):
+                for b in sorted(set(wk.batches)):
+                    wk.h.tune(1 + w, batch=b, iters=1)
+        print(json.dumps({"roofline": measure_roofline(pool), "n_gpus": 1, "data": "synthetic",
+                          "config": {"workload": WORKLOADS[cfg], "leg": "per-layer timing pass only"}}))
+        torch.cuda.synchronize()
+        for wk in workers:
+            wk.h.free()
+        pool.destroy()
+        return
 
     # ---- latency-vs-CU tables (Sec. III-B profiling), the measured cost of a switch, and the allocation.
     # Every group is timed as eclip_submit serves it (launch sharing and input re-layout included); the kernel count
@@ -908,48 +1053,7 @@ def main():
 
     for wk in workers:
         wk.h.graphs(False)
-    # ---- roofline of the dominant kernel: HIP-event timings on the stream the kernels run on.  Each layer of each
-    # model is timed on that worker's unpartitioned stream (8 back-to-back launches per sample, see
-    # eclip_profile_group); layers are grouped by the kernel function that runs them; the matrix-core function
-    # with the largest launch-weighted time is reported against the roofline that bounds its work.
-    set_policy("unpart_b")
-    per_kernel = {}
-    for w, wk in enumerate(workers):
-        ns_all = []
-        for g in range(wk.model.n_groups):
-            ns_all.extend(wk.h.profile_group(g, 1 + w, batch=prof_batch[w], iters=20 if cfg != 4 else 10))
-        work = gemm_work(wk.model, prof_batch[w])
-        for li, ns in enumerate(ns_all):
-            info = wk.h.kernel_info(li, 1 + w, prof_batch[w])
-            e = per_kernel.setdefault(info["kernel"], {"ns": 0.0, "bytes": 0.0, "flops": 0.0, "launches": 0, "layers": 0})
-            e["ns"] += ns
-            e["launches"] += info["launches"]
-            e["layers"] += 1
-            if work[li] is not None:
-                e["bytes"] += work[li][0]
-                e["flops"] += work[li][1]
-    total_ns = sum(v["ns"] for v in per_kernel.values())
-    # a layer whose K is cut over the grid runs two kernels (GEMM + slice sum): its time is attributed per launch
-    dom = max((k for k in per_kernel if per_kernel[k]["bytes"] > 0),
-              key=lambda k: per_kernel[k]["ns"] * per_kernel[k]["layers"] / per_kernel[k]["launches"])
-    d = per_kernel[dom]
-    ai = d["flops"] / d["bytes"]
-    if ai > RIDGE:
-        ach, peak, unit, bound = d["flops"] / d["ns"] / 1e3, MFMA_PEAK_TFLOPS, "TFLOP/s", "mfma"
-    else:
-        ach, peak, unit, bound = d["bytes"] / d["ns"], HBM_PEAK_GBS, "GB/s", "hbm"
-    # HBM bytes per launch from the FETCH_SIZE / WRITE_SIZE counters of an earlier profiled run of this workload;
-    # null when there is none or when a kernel source has changed since
-    traffic = None
-    if os.path.exists(traffic_path(cfg)):
-        t = json.load(open(traffic_path(cfg)))
-        if t.get("source_sha256") == source_hash() and dom in t["kernels"]:
-            traffic = t["kernels"][dom]["fetch_bytes_per_launch"] + t["kernels"][dom]["write_bytes_per_launch"]
-    roofline = {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak, "traffic": traffic,
-                "kernel": dom, "flop_per_byte": ai, "layers_per_step": d["layers"], "launches_per_step": d["launches"],
-                "avg_layer_us": d["ns"] / d["layers"] / 1e3, "avg_bytes_per_layer": d["bytes"] / d["layers"],
-                "achieved_tflops": d["flops"] / d["ns"] / 1e3, "achieved_gbs": d["bytes"] / d["ns"],
-                "time_share_by_kernel": {k: v["ns"] / total_ns for k, v in per_kernel.items()}}
+    roofline = measure_roofline(pool)
 
     # ---- CPU oracle on the host cores, same models and inputs: one full forward pass per worker on the batch of its
     # last timed request.  The passes are the parity check of every worker's output (in the launch configuration that
@@ -999,6 +1103,10 @@ def main():
         "parity": parity,
     }
     print(json.dumps(out))
+    torch.cuda.synchronize()
+    for wk in workers:
+        wk.h.free()
+    pool.destroy()
 
 
 if __name__ == "__main__":

@@ -24,7 +24,7 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
         // LDS only the wavefront's own LDS counter is waited on.  N8: N is a multiple of 8, so a lane's 8 channels
         // are all inside the row and aligned; otherwise the (rare) ragged form stores them one by one from a loop
         // that is not unrolled, to keep it out of the way.
-        static_assert(TM % 2 == 0, "32 rows per pass");
+        // 32 rows (two 16-row blocks) per round; an odd TM ends with a round of 16
         constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
         constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass (lanes beyond RPP * LPR idle)
         constexpr int PASSES = (32 + RPP - 1) / RPP;
@@ -32,9 +32,10 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
         float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
         const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
         const int n = n_base + wn * (BN / WN) + col8;
-        static_for<TM / 2>([&](auto hc) {
+        static_for<(TM + 1) / 2>([&](auto hc) {
             constexpr int h = decltype(hc)::value;
-            static_for<2>([&](auto ic) {
+            constexpr int NBLK = (2 * h + 1 < TM) ? 2 : 1;       // 16-row blocks in this round
+            static_for<NBLK>([&](auto ic) {
                 constexpr int i2 = decltype(ic)::value;
                 static_for<TN>([&](auto jc) {
                     constexpr int j = decltype(jc)::value;
@@ -47,7 +48,7 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
             auto pass = [&](int ps) {
                 const int rr = ps * RPP + rr0;
                 const int m = m_base + wm * (BM / WM) + h * 32 + rr;
-                if (lane < RPP * LPR && rr < 32 && m < p.M && n < p.N) {
+                if (lane < RPP * LPR && rr < NBLK * 16 && m < p.M && n < p.N) {
                     const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
                     const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
                     float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
@@ -532,7 +533,7 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
     X(5, 256, 256, 32, 2, LOOP_PP_BDIRECT) X(6, 128, 256, 64, 2, LOOP_PP_BDIRECT) X(7, 192, 128, 32, 2, LOOP_PP_BDIRECT)    \
     X(8, 192, 128, 64, 2, LOOP_PP_BDIRECT) X(9, 128, 128, 64, 2, LOOP_PP_BDIRECT) X(10, 256, 128, 32, 2, LOOP_PP_BDIRECT)   \
     X(11, 192, 256, 32, 2, LOOP_PP_BDIRECT) X(12, 256, 192, 32, 2, LOOP_PP_BDIRECT) X(13, 64, 128, 64, 2, LOOP_PP_BDIRECT)  \
-    X(14, 128, 64, 64, 2, LOOP_PP_BDIRECT)
+    X(14, 128, 64, 64, 2, LOOP_PP_BDIRECT) X(15, 96, 64, 64, 2, LOOP_PP_BDIRECT) X(16, 96, 192, 64, 2, LOOP_PP_BDIRECT)
 
 struct PPTile { int id, bm, bn, bk, rs, loop; };
 constexpr PPTile kPPTiles[] = {

@@ -213,7 +213,7 @@ std::vector<GemmPlan> conv_gemm_candidates(long M, long N, long K, int n_cu, siz
             set_xcd_split(pl, M, N);
             out.push_back(pl);
         }
-    for (int v : {0, 1, 3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14}) {
+    for (int v : {0, 1, 3, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16}) {
         int bm, bn, bk;
         conv_gemm_tile(v, &bm, &bn, &bk);
         if (bm > 2 * M + 32 || bn > 2 * N + 32) continue;
@@ -284,7 +284,8 @@ GemmPlan conv_gemm_plan(long M, long N, long K, int n_cu, size_t ws_floats)
     static const LdsTile lds[] = {{0, 0.3613, 0.02038, true}, {1, 0.3664, 0.1703, true},
                                   {3, 0.582, 5.6, false},  {5, 0.616, 4.6, false},  {6, 0.72, 2.5, false},  {7, 0.36, 1.4, false},
                                   {8, 0.571, 3.0, false},  {9, 0.473, 0.6, false},  {10, 0.395, 1.5, false}, {11, 0.505, 3.8, false},
-                                  {12, 0.481, 3.8, false}, {13, 0.406, 0.0, true},  {14, 0.373, 0.2, true}};
+                                  {12, 0.481, 3.8, false}, {13, 0.406, 0.0, true},  {14, 0.373, 0.2, true},
+                                  {15, 0.3134, 0.83, true}, {16, 0.4837, 4.2, false}};
     for (const LdsTile &c : lds) {
         int bm, bn, bk;
         conv_gemm_tile(c.variant, &bm, &bn, &bk);

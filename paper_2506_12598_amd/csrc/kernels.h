@@ -35,10 +35,10 @@ struct GemmPlan {
     int raster;    // kind 0: workgroups walk the tiles in 8 x 4 blocks per XCD (tiles then counts whole blocks)
 };
 bool conv_gemm_plan_stem(long M, long N, long K, int n_cu, size_t ws_floats, double stage_us, GemmPlan *out);   // ConvGemmArgs::nchw_c
-enum { CONV_GEMM_VARIANTS = 15 };        // 0..2: 128x128x32, 64x64x64, 32x64x64 (4 wavefronts); 3, 4: 256x256x32, 128x256x64 (8 wavefronts on the
+enum { CONV_GEMM_VARIANTS = 17 };        // 0..2: 128x128x32, 64x64x64, 32x64x64 (4 wavefronts); 3, 4: 256x256x32, 128x256x64 (8 wavefronts on the
                                          // ping-pong schedule, both operands in LDS); 5..14: ping-pong with the weights straight from memory:
                                          // 256x256x32, 128x256x64, 192x128x32, 192x128x64, 128x128x64, 256x128x32, 192x256x32, 256x192x32,
-                                         // 64x128x64, 128x64x64
+                                         // 64x128x64, 128x64x64, 96x64x64, 96x192x64
 void conv_gemm_tile(int variant, int *bm, int *bn, int *bk);
 enum { CONV_WSK_VARIANTS = 6 };          // 16x64, 32x64, 64x64, 16x16, 16x32, 32x32
 void conv_wsk_tile(int variant, int *bm, int *bn);

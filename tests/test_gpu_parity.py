@@ -311,7 +311,9 @@ GEMM_FORCE = ["0,0,1", "0,0,3", "0,1,1", "0,1,2", "0,2,1", "0,2,5", "0,3,1", "0,
               # the ping-pong tiles whose weights bypass LDS: 256x256, 128x256, 192x128 (K step 32, 64), 128x128, 256x128, 192x256,
               # 256x192, 64x128, 128x64
               "0,5,1", "0,5,2", "0,6,1", "0,7,1", "0,7,2", "0,8,1", "0,8,3", "0,9,1", "0,10,1", "0,11,1", "0,12,1", "0,12,2", "0,13,1", "0,14,1",
-              "0,14,2"]
+              "0,14,2",
+              # 96 rows (three 16-row blocks per wavefront: the staged epilogue's odd last round): 96x64, 96x192
+              "0,15,1", "0,15,2", "0,16,1", "0,16,3"]
 
 
 @pytest.mark.parametrize("force", GEMM_FORCE)
