@@ -649,6 +649,8 @@ def main():
     ap.add_argument("--graphs", type=int, default=0, choices=[0, 1], help="serve captured requests (HIP graphs replayed per stream segment)")
     ap.add_argument("--objective", default="energy", choices=["energy", "throughput"],
                     help="what picks the served allocation among the candidates: inferences per joule within the throughput floor, or throughput")
+    ap.add_argument("--serve", default=None, metavar="NAME",
+                    help="serve the candidate allocation whose name contains NAME in the timed region, whatever its trial says")
     ap.add_argument("--throughput-floor", type=float, default=0.85, help="with --objective energy: candidates below this fraction of the fastest trial are out")
     ap.add_argument("--trial-seconds", type=float, default=2.0)
     ap.add_argument("--energy-window", type=float, default=3.0, help="seconds of closed loop per policy and repeat for inferences/J (0 = skip)")
@@ -955,6 +957,12 @@ def main():
     else:
         ok = [i for i in range(len(trials)) if trials[i][0] >= args.throughput_floor * fastest]
         best_i = max(ok, key=lambda i: trials[i][4])
+    if args.serve:
+        # serve a named candidate whatever its trial says (e.g. "as printed": the pure Sec. III-B output, switches and all)
+        hits = [i for i, t in enumerate(trials) if args.serve.lower() in t[1].lower()]
+        if not hits:
+            raise SystemExit(f"--serve {args.serve!r} matches none of: {[t[1] for t in trials]}")
+        best_i = hits[0]
     _, chosen, assign, switches, _ = trials[best_i]
     pool, eclip_table = serving_pool(assign)
     for wk in workers:

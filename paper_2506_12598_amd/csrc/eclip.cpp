@@ -1010,6 +1010,9 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
         } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1 && !(P.L.groups == P.in.c && P.L.c == P.L.groups)) {
             name = P.gc_super ? "gconv_mfma_kernel" : "gconv_kernel";
             out->workgroups = (uint32_t)((rows * P.L.c + 255) / 256);
+            if (P.gc_super)
+                out->workgroups = (uint32_t)gconv_mfma_workgroups(rows, P.L.groups, P.L.c / P.L.groups, P.gc_super,
+                                                                  (int)model->pool->streams[mask_id].n_cu);
         } else if (P.L.op == ECLIP_OP_CONV && P.L.groups > 1) {
             DwConvArgs da{};
             da.B = (int)batch; da.C = P.L.c; da.Ho = P.L.h; da.Wo = P.L.w; da.KH = P.L.kh; da.KW = P.L.kw; da.stride = P.L.stride;

@@ -11,7 +11,8 @@
 //   3. out^T = V^T . P^T: the contraction index of one MFMA covers two key blocks; the lane's own 8
 //      probabilities (4 per block) are already the column operand it must supply, and V^T is read from
 //      an LDS copy transposed on load so that the matching 4 keys are 8 contiguous bytes.
-// Probabilities are rounded to the 16-bit type for the second product, scores are never stored.
+// The unnormalised probabilities (exp of score minus row maximum, in (0, 1]) are rounded to the 16-bit type for the
+// second product and the division by the row sum is applied to the outputs; scores are never stored.
 // The key fragments come straight from global memory for up to 256 keys (all loads of the workgroup in flight at
 // once); beyond that the keys too are staged in LDS by the whole workgroup with row-contiguous loads and shared by
 // its wavefronts (fetched per wavefront in fragment order, 48 dependent round trips made S = 384 take 45 us).
@@ -155,27 +156,32 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
         }
     }
 
-    // ---- softmax over keys (lane holds keys kb*16 + 4*g + r)
+    // ---- softmax over keys (lane holds keys kb*16 + 4*g + r).  The vector ALU is what this kernel waits for (96 scores
+    // per lane at 384 keys), so the row is touched as few times as possible: the maximum is taken over the raw scores
+    // (the scale is positive), exp((s - max) * scale) is one fused multiply-add and one exp2, padded keys are masked only
+    // in the blocks that contain any, and the division by the sum is applied to the 16 outputs instead of the scores.
     float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
-        if (kb < nkb)
+        if (kb < nkb) {
+            if ((kb + 1) * 16 > p.S) {           // wavefront-uniform: only the last blocks hold padded keys
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int key = kb * 16 + 4 * g + r;
-                const float v = key < p.S ? sc[kb][r] * p.scale : -INFINITY;
-                sc[kb][r] = v;
-                mx = fmaxf(mx, v);
+                for (int r = 0; r < 4; ++r)
+                    if (kb * 16 + 4 * g + r >= p.S) sc[kb][r] = -INFINITY;
             }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, sc[kb][r]);
+        }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float c2 = p.scale * 1.4426950408889634f, off2 = -mx * c2;
     float sum = 0.0f;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
         if (kb < nkb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float e = __expf(sc[kb][r] - mx);      // exp(-inf) = 0 for padded keys
+                const float e = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], c2, off2));      // exp2(-inf) = 0 for padded keys
                 sc[kb][r] = e;
                 sum += e;
             }
@@ -192,10 +198,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
         if (2 * kp2 < nkb) {
             // contraction slot e of lane group g  <->  key (2*kp2 + e/4)*16 + 4*g + e%4
             uint4 pf;
-            pf.x = Cvt<T>::pack2(sc[2 * kp2][0] * inv, sc[2 * kp2][1] * inv);
-            pf.y = Cvt<T>::pack2(sc[2 * kp2][2] * inv, sc[2 * kp2][3] * inv);
-            pf.z = Cvt<T>::pack2(sc[2 * kp2 + 1][0] * inv, sc[2 * kp2 + 1][1] * inv);
-            pf.w = Cvt<T>::pack2(sc[2 * kp2 + 1][2] * inv, sc[2 * kp2 + 1][3] * inv);
+            pf.x = Cvt<T>::pack2(sc[2 * kp2][0], sc[2 * kp2][1]);
+            pf.y = Cvt<T>::pack2(sc[2 * kp2][2], sc[2 * kp2][3]);
+            pf.z = Cvt<T>::pack2(sc[2 * kp2 + 1][0], sc[2 * kp2 + 1][1]);
+            pf.w = Cvt<T>::pack2(sc[2 * kp2 + 1][2], sc[2 * kp2 + 1][3]);
 #pragma unroll
             for (int jb = 0; jb < D / 16; ++jb) {
                 const uint16_t *vr = vt + (jb * 16 + (lane & 15)) * p.ldv + 4 * g;
@@ -207,6 +213,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
     }
 
     // lane holds head dims jb*16 + 4*g .. +3 of its query
+#pragma unroll
+    for (int jb = 0; jb < D / 16; ++jb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[jb][r] *= inv;
     if (q_ok) {
         const long off = (row0 + q_row) * p.Hd + h * D + 4 * g;
 #pragma unroll

@@ -158,6 +158,14 @@ bool gconv_mfma_pick(int groups, int cig, int cog, int *S_out)
     return false;
 }
 
+long gconv_mfma_workgroups(long M, int groups, int cog, int S, int n_cu)
+{
+    const int NB = S * cog / 16, nbc = NB <= 2 ? 2 : 4;
+    const long units = (long)(groups / S) * ((NB + nbc - 1) / nbc);
+    const long wg1 = (M + 63) / 64 * units;
+    return wg1 >= 16L * n_cu ? (M + 127) / 128 * units : wg1;
+}
+
 hipError_t launch_gconv_mfma(const GConvArgs &a, int S, int n_cu, hipStream_t s)
 {
     const int cig = a.Cin / a.groups, cog = a.Cout / a.groups;

@@ -637,15 +637,11 @@ __global__ __launch_bounds__(256) void eltwise_kernel(EltArgs a, long total, lon
                 for (int i = 0; i < V; ++i) v[u][i] += t[u][i];
             }
     }
-    // one branch on the activation for the whole vector, not one per element
-#define ACT_ALL(A)                                                  \
-    _Pragma("unroll") for (int u = 0; u < U; ++u)                   \
-        _Pragma("unroll") for (int i = 0; i < V; ++i) v[u][i] = apply_act_c<A>(v[u][i]);
-    ECLIP_ACT_SWITCH(a.act, ACT_ALL)
-#undef ACT_ALL
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (!ok[u]) continue;
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[u][i] = apply_act(a.act, v[u][i]);
         if (a.y32) {
 #pragma unroll
             for (int i = 0; i < V; ++i) a.y32[off[u] + i] = v[u][i];

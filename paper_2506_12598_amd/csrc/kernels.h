@@ -91,6 +91,7 @@ hipError_t launch_gconv(const GConvArgs &a, int n_cu, hipStream_t s);
 // must then be in the direct kernel's layout, otherwise in the super-group blocks described in k_gconv.hip.
 bool gconv_mfma_pick(int groups, int cig, int cog, int *S_out);
 hipError_t launch_gconv_mfma(const GConvArgs &a, int S, int n_cu, hipStream_t s);
+long gconv_mfma_workgroups(long M, int groups, int cog, int S, int n_cu);   // the grid launch_gconv_mfma uses (M = B*Ho*Wo)
 // y[m][0 .. c0) = a[m][:], y[m][c0 .. c0 + c1) = b[m][:]
 hipError_t launch_concat(const void *a, const void *b, void *y, long rows, int c0, int c1, int dtype, hipStream_t s);
 // y[m][j] = x[m][(j % groups) * (c / groups) + j / groups]
