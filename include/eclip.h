@@ -26,6 +26,16 @@
  *   - Thread safety: calls on different models may run on different threads at once;
  *     calls on one model are serialised inside the library.  Pool creation and
  *     destruction are not thread safe with respect to calls on the same pool.
+ *
+ * Environment variables (read by the library; for tuning and tests, never needed in service)
+ *   ECLIP_GEMM_FORCE="kind,variant,n"  every matrix-core layer takes this plan instead of the planner's or the tuned
+ *                         one: kind 0 = LDS-tiled kernel (variant = tile id, n = K slices), kind 1 = wave-split-K
+ *                         kernel (variant = tile id, n = 4, 8 or 16 wavefronts); also turns launch sharing off
+ *   ECLIP_NO_PAIRS=1      independent layers never share a launch (pairs of convolutions, pool + classifier, first
+ *                         convolution reading the caller's tensor)
+ *   ECLIP_GCONV_DIRECT=1  read at eclip_model_load: grouped convolutions take the direct kernel, not the matrix cores
+ *   ECLIP_CONCAT_COPY=1   read at eclip_model_load: every CONCAT layer copies its operands (no concatenation in place)
+ *   ECLIP_TRACE=1         the set-up steps of the library (pool, model load) on stderr
  */
 #ifndef ECLIP_H
 #define ECLIP_H

@@ -362,6 +362,12 @@ struct LayerPlan {
     size_t w_dev = NONE, b_dev = NONE, g_dev = NONE, be_dev = NONE;   // byte offsets in the device weight arena
     bool gemm = false;         // runs on the matrix-core GEMM kernel
     int gc_super = 0;          // grouped CONV on the matrix cores: groups per super-group (0: the direct kernel)
+    // Concatenation in place: the output of a layer may be a channel range of another layer's (wider) buffer.
+    int buf = -1;              // layer whose arena buffer holds this layer's output (itself unless in place)
+    int ld = 0;                // channels between consecutive pixels of that buffer (0: this layer's own channel count)
+    int c_off = 0;             // first channel of this layer's output in it
+    bool concat_copy = false;  // CONCAT in place, head of a chain: the first operand is copied into the buffer, the second is there
+    bool concat_noop = false;  // CONCAT in place whose operands are both already in the buffer: nothing to launch
     bool pair_next = false;    // this layer and the next are independent GEMM layers of one group: one launch may carry both
     bool gapfc_next = false;   // global average pool whose only reader is the linear layer that follows: one launch may do both
 };
@@ -521,6 +527,7 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
         const Dims in = L.in0 == -1 ? in_dims : m->layers[L.in0].out;
         P.in = in;
         P.in_c_logical = (L.in0 == -1 && d->in_kind == ECLIP_IN_IMAGE) ? d->in_c : in.c;
+        P.buf = (int)i;
         Dims out{L.kind, L.c, L.h, L.w};
         if (L.c <= 0 || L.h <= 0 || L.w <= 0) return fail(ECLIP_EINVAL, "layer %u: non-positive output dims", i);
         if (L.act < ECLIP_ACT_NONE || L.act > ECLIP_ACT_GELU) return fail(ECLIP_EINVAL, "layer %u: unknown activation %d", i, L.act);
@@ -665,6 +672,61 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
         bool other_reader = false;
         for (uint32_t j = i + 2; j < d->n_layers; ++j) other_reader |= m->layers[j].L.in0 == (int)i || m->layers[j].L.in1 == (int)i;
         A.gapfc_next = !other_reader;
+    }
+    // Concatenation in place (DenseNet-style blocks: y = concat(x, f(x)), again and again).  Copying makes the block
+    // quadratic in traffic and costs a launch per layer.  Instead a chain of concatenations shares ONE buffer with the
+    // channel count of the last of them: the matrix-core convolution that produces a second operand writes its channels
+    // straight into its range of that buffer (row pitch = the buffer's channel count), every earlier concatenation of
+    // the chain is the buffer's first channels, read with that pitch, and the CONCAT layers themselves launch nothing,
+    // except the head of a chain, which copies its first operand in.  Conditions, all checked here: 16-bit model; the
+    // second operand comes from a matrix-core CONV without residual that nobody else reads; channel counts are multiples
+    // of 8; and a concatenation that is not the last of its chain is read only by the next concatenation (as its first
+    // operand) and by matrix-core convolutions (as their input), the two readers that know about the pitch.
+    if (m->dtype != ECLIP_F32 && !getenv("ECLIP_CONCAT_COPY")) {
+        const int n = (int)d->n_layers;
+        std::vector<std::vector<int>> readers(n);
+        for (int j = 0; j < n; ++j) {
+            const eclip_layer &L = m->layers[j].L;
+            if (L.in0 >= 0) readers[L.in0].push_back(j);
+            if (L.in1 >= 0 && L.in1 != L.in0) readers[L.in1].push_back(j);
+        }
+        std::vector<int> chain(n, -1);
+        std::vector<char> extended(n, 0);
+        for (int i = 0; i < n; ++i) {
+            LayerPlan &C = m->layers[i];
+            if (C.L.op != ECLIP_OP_CONCAT) continue;
+            const int a = C.L.in0, b = C.L.in1;
+            if (a < 0 || b < 0 || a == b) continue;
+            const LayerPlan &B = m->layers[b];
+            if (B.L.op != ECLIP_OP_CONV || !B.gemm || B.L.in1 != -2 || readers[b].size() != 1 || b == n - 1) continue;
+            if (C.in.c % 8 || B.out.c % 8) continue;
+            bool extend = m->layers[a].L.op == ECLIP_OP_CONCAT && chain[a] >= 0 && !extended[a];
+            if (extend)
+                for (int r : readers[a]) {
+                    const LayerPlan &R = m->layers[r];
+                    const bool next_concat = r == i;
+                    const bool conv_input = R.L.op == ECLIP_OP_CONV && R.gemm && R.L.in0 == a && R.L.in1 != a;
+                    extend &= next_concat || conv_input;
+                }
+            chain[i] = extend ? chain[a] : i;
+            if (extend) extended[a] = 1;
+            C.concat_noop = extend;
+            C.concat_copy = !extend;
+        }
+        for (int i = n - 1; i >= 0; --i) {
+            if (chain[i] < 0) continue;
+            int last = i;                                       // the last concatenation of this layer's chain owns the buffer
+            for (int j = n - 1; j > i; --j)
+                if (chain[j] == chain[i]) { last = j; break; }
+            const int ld = m->layers[last].out.c;
+            LayerPlan &C = m->layers[i];
+            C.buf = last;
+            C.ld = i == last ? 0 : ld;
+            LayerPlan &B = m->layers[C.L.in1];
+            B.buf = last;
+            B.ld = ld;
+            B.c_off = C.in.c;
+        }
     }
     return ECLIP_OK;
 }
@@ -863,6 +925,7 @@ extern "C" eclip_status eclip_model_load(eclip_pool *pool, const eclip_model_des
     size_t act = 0;
     for (LayerPlan &P : m->layers) {
         P.out_off = act;
+        if (&m->layers[P.buf] != &P) continue;               // in place: lives in another layer's buffer
         act += align_up((size_t)P.out.c * P.out.h * P.out.w * m->max_batch * (size_t)es, 256);
     }
     LOAD_TRY(hipMalloc((void **)&m->d_act, std::max<size_t>(act, 256)));
@@ -1041,7 +1104,10 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
     case ECLIP_OP_ATTENTION: name = "attention_kernel"; break;
     case ECLIP_OP_EMBED: name = "embed_kernel"; break;
     case ECLIP_OP_ELTWISE: name = "eltwise_kernel"; break;
-    case ECLIP_OP_CONCAT: name = "concat_kernel"; break;
+    case ECLIP_OP_CONCAT:
+        name = P.concat_noop ? "(in place)" : P.concat_copy ? "chancopy_kernel" : "concat_kernel";
+        if (P.concat_noop) out->launches = 0;
+        break;
     case ECLIP_OP_SHUFFLE: name = "shuffle_kernel"; break;
     default: break;
     }
@@ -1053,6 +1119,13 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
 // executor
 // ------------------------------------------------------------------------------------------------
 static const void *wptr(const eclip_model *m, size_t off) { return off == NONE ? nullptr : (const void *)(m->d_weights + off); }
+// where layer P's output lives: its own buffer, or its channel range of the buffer of a concatenation done in place
+static char *out_ptr(const eclip_model *m, const LayerPlan &P)
+{
+    return m->d_act + m->layers[P.buf].out_off + (size_t)P.c_off * (size_t)m->esize;
+}
+// pixel pitch (in channels) a reader of layer idx must use, 0 when the tensor is contiguous
+static int pitch_of(const eclip_model *m, int idx) { return idx >= 0 ? m->layers[idx].ld : 0; }
 
 // Launches layer i on `s`.  `d_out32` non-null: this is the last layer and its result goes to the caller.
 static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_t s, int n_cu, const void *d_in, float *d_out32,
@@ -1064,9 +1137,9 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
     auto src = [&](int idx) -> const void * {
         if (idx == -2) return nullptr;
         if (idx == -1) return m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in;
-        return (const void *)(m->d_act + m->layers[idx].out_off);
+        return (const void *)out_ptr(m, m->layers[idx]);
     };
-    void *y = m->d_act + P.out_off;
+    void *y = out_ptr(m, P);
     // the last layer writes float32 straight into the caller's buffer when its internal layout is the
     // logical one (SEQ / VEC) and its kernel has a float output path
     const bool chan_last_out = P.out.kind != ECLIP_KIND_IMAGE || (P.out.h == 1 && P.out.w == 1);
@@ -1082,6 +1155,8 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
             if (d_out32 && chan_last_out) y32 = d_out32;
             ConvGemmArgs a{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), y32 ? nullptr : y, y32, m->ws,
                            g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, dt};
+            a.ldx = pitch_of(m, L.in0);
+            a.ldy = P.ld;
             const GemmPlan pl = plan_of(m, (long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu);
             *n_launched -= 1;
             e = launch_conv_gemm(a, pl, s, n_launched);
@@ -1136,7 +1211,9 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
         break;
     }
     case ECLIP_OP_CONCAT:
-        e = launch_concat(src(L.in0), src(L.in1), y, rows, P.in.c, L.c - P.in.c, dt, s);
+        if (P.concat_noop) *n_launched -= 1;                 // both operands were written into this buffer by their producers
+        else if (P.concat_copy) e = launch_chancopy(src(L.in0), y, rows, P.in.c, P.ld ? P.ld : L.c, dt, s);
+        else e = launch_concat(src(L.in0), src(L.in1), y, rows, P.in.c, L.c - P.in.c, dt, s);
         break;
     case ECLIP_OP_SHUFFLE:
         e = launch_shuffle(src(L.in0), y, rows, L.c, L.groups, dt, s);
@@ -1164,11 +1241,13 @@ static hipError_t launch_pair(eclip_model *m, uint32_t i, int batch, hipStream_t
         auto src = [&](int idx) -> const void * {
             if (idx == -2) return nullptr;
             if (idx == -1) return m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in;
-            return (const void *)(m->d_act + m->layers[idx].out_off);
+            return (const void *)out_ptr(m, m->layers[idx]);
         };
         const GemmShape g = gemm_shape(P, batch);
-        a[k] = ConvGemmArgs{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), m->d_act + P.out_off, nullptr, m->ws,
+        a[k] = ConvGemmArgs{src(L.in0), wptr(m, P.w_dev), wptr(m, P.b_dev), src(L.in1), out_ptr(m, P), nullptr, m->ws,
                             g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, m->dtype};
+        a[k].ldx = pitch_of(m, L.in0);
+        a[k].ldy = P.ld;
         mnk[k][0] = (long)g.B * g.Ho * g.Wo; mnk[k][1] = g.Cout; mnk[k][2] = (long)g.KH * g.KW * g.Cin;
         own[k] = plan_of(m, mnk[k][0], mnk[k][1], mnk[k][2], n_cu);
     }
@@ -1185,10 +1264,10 @@ static hipError_t launch_gapfc_pair(eclip_model *m, uint32_t i, int batch, hipSt
     const LayerPlan &G = m->layers[i], &F = m->layers[i + 1];
     const int HW = G.in.h * G.in.w, C = G.L.c;
     if (getenv("ECLIP_NO_PAIRS") || !gapfc_supported(batch, HW, C, m->dtype)) return hipSuccess;
-    const void *x = G.L.in0 == -1 ? (m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in) : (const void *)(m->d_act + m->layers[G.L.in0].out_off);
+    const void *x = G.L.in0 == -1 ? (m->in_kind == ECLIP_IN_IMAGE ? (const void *)m->d_in_stage : d_in) : (const void *)out_ptr(m, m->layers[G.L.in0]);
     *done = true;
     *n_launched += 1;
-    return launch_gapfc(x, wptr(m, F.w_dev), wptr(m, F.b_dev), d_out32 ? nullptr : (void *)(m->d_act + F.out_off), d_out32, batch, HW, C, F.L.c, F.L.act,
+    return launch_gapfc(x, wptr(m, F.w_dev), wptr(m, F.b_dev), d_out32 ? nullptr : (void *)out_ptr(m, F), d_out32, batch, HW, C, F.L.c, F.L.act,
                         m->dtype, s);
 }
 
@@ -1201,7 +1280,7 @@ static hipError_t launch_stem_direct(eclip_model *m, int batch, hipStream_t s, i
     const GemmShape g = gemm_shape(P, batch);
     GemmPlan pl;
     if (!conv_gemm_plan_stem((long)g.B * g.Ho * g.Wo, g.Cout, (long)g.KH * g.KW * g.Cin, n_cu, m->ws_floats, 2.0, &pl)) return hipSuccess;
-    ConvGemmArgs a{d_in, wptr(m, P.w_dev), wptr(m, P.b_dev), nullptr, m->d_act + P.out_off, nullptr, m->ws,
+    ConvGemmArgs a{d_in, wptr(m, P.w_dev), wptr(m, P.b_dev), nullptr, out_ptr(m, P), nullptr, m->ws,
                    g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, P.L.act, m->dtype};
     a.nchw_c = m->in_c;
     *done = true;
@@ -1572,13 +1651,15 @@ extern "C" eclip_status eclip_model_tune(eclip_model *model, uint32_t mask_id, u
         auto src = [&](int idx) -> const void * {
             if (idx == -2) return nullptr;
             if (idx == -1) return model->in_kind == ECLIP_IN_IMAGE ? (const void *)model->d_in_stage : (const void *)model->d_self_in;
-            return (const void *)(model->d_act + model->layers[idx].out_off);
+            return (const void *)out_ptr(model, model->layers[idx]);
         };
         const bool last = i + 1 == n_layers;
         const bool chan_last_out = P.out.kind != ECLIP_KIND_IMAGE || (P.out.h == 1 && P.out.w == 1);
         float *y32 = (last && chan_last_out) ? model->d_self_out : nullptr;
-        const ConvGemmArgs a{src(L.in0), wptr(model, P.w_dev), wptr(model, P.b_dev), src(L.in1), y32 ? nullptr : (void *)(model->d_act + P.out_off), y32,
-                             model->ws, g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, model->dtype};
+        ConvGemmArgs a{src(L.in0), wptr(model, P.w_dev), wptr(model, P.b_dev), src(L.in1), y32 ? nullptr : (void *)out_ptr(model, P), y32,
+                       model->ws, g.B, g.H, g.W, g.Cin, g.Ho, g.Wo, g.Cout, g.KH, g.KW, g.stride, g.pad, L.act, model->dtype};
+        a.ldx = pitch_of(model, L.in0);
+        a.ldy = P.ld;
         const GemmPlan own = conv_gemm_plan(M, N, K, n_cu, model->ws_floats);
         std::vector<GemmPlan> cand = conv_gemm_candidates(M, N, K, n_cu, model->ws_floats);
         cand.insert(cand.begin(), own);

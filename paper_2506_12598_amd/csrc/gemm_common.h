@@ -16,6 +16,8 @@ struct GemmDev {
     int M, N, K, KT, kt_per, splits, tiles_m, tiles_n, raster;
     unsigned x_bytes, w_bytes;               // sizes of the x and w tensors (each below 4 GiB)
     int nchw_c;                              // > 0: x is the caller's [B][nchw_c][H][W] tensor (first layer), Cin == 8
+    int ldx, ldy;                            // elements between consecutive pixels of x / rows of y (Cin and N unless the tensor is
+                                             // a channel range of a wider buffer: concatenation in place); res is null when ldy != N
 };
 
 template <typename T> struct Mma;
@@ -35,10 +37,10 @@ template <> struct Mma<f16_t> {
 // bias + residual + activation + store of 4 consecutive channels n..n+3 of output row m
 template <typename T, int ACT>
 __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32,
-                                               int M, int N, int m, int n, f32x4 v, int nvalid = 4)
+                                               int M, int N, int m, int n, f32x4 v, int nvalid = 4, int ld = 0)
 {
     if (m >= M || n >= N) return;
-    const long off = (long)m * N + n;
+    const long off = (long)m * (ld ? ld : N) + n;      // ld: row pitch of y when it differs from N (a multiple of 8)
     float o[4] = {v[0], v[1], v[2], v[3]};
     if ((N & 3) == 0 && nvalid == 4) {       // then n + 3 < N and every access below is aligned
         if (bias) {
@@ -76,12 +78,12 @@ __device__ __forceinline__ void epilogue_store(const uint16_t *bias, const uint1
 }
 
 // The same for 8 consecutive channels n..n+7 of row m, with 16-byte accesses: requires N % 8 == 0, n % 8 == 0,
-// m < M and n < N (checked by the caller).  `o` holds the sums without bias.
+// m < M and n < N (checked by the caller).  `o` holds the sums without bias; ld = row pitch of y (and of res).
 template <typename T, int ACT>
-__device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N,
+__device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int ld,
                                                 int m, int n, float (&o)[8])
 {
-    const long off = (long)m * N + n;
+    const long off = (long)m * ld + n;
     if (bias) {
         float bv[8];
         Pack<T, 8>::load(reinterpret_cast<const T *>(bias) + n, bv);
@@ -106,10 +108,10 @@ __device__ __forceinline__ void epilogue_store8(const uint16_t *bias, const uint
 
 // The same for any N: channels n..n+7 of row m that lie below N, one element at a time.
 template <typename T, int ACT>
-__device__ __forceinline__ void epilogue_store8_ragged(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N,
+__device__ __forceinline__ void epilogue_store8_ragged(const uint16_t *bias, const uint16_t *res, uint16_t *y, float *y32, int N, int ld,
                                                        int m, int n, const float (&o)[8])
 {
-    const long off = (long)m * N + n;
+    const long off = (long)m * ld + n;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         if (n + e >= N) break;

@@ -52,8 +52,8 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
                     const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
                     const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
                     float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                    if constexpr (N8) epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
-                    else epilogue_store8_ragged<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
+                    if constexpr (N8) epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.ldy, m, n, o);
+                    else epilogue_store8_ragged<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, p.ldy, m, n, o);
                 }
             };
             if constexpr (N8) {
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
         const int oh = r / p.Wo, ow = r - oh * p.Wo;
         a_ih0[it] = oh * p.stride - p.pad;
         a_iw0[it] = ow * p.stride - p.pad;
-        a_off0[it] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[it] * p.W + a_iw0[it])) * (unsigned)p.Cin * 2u;
+        a_off0[it] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[it] * p.W + a_iw0[it])) * (unsigned)p.ldx * 2u;
     }
     // The weights are stored in blocks of 16 rows x 32 k, 1 KB each, lane-ordered for the matrix instruction.  A
     // wavefront copies whole blocks: chunk c of the tile is lane c % 64 of block c / 64, and block b of the tile is
@@ -275,7 +275,7 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
             return;
         } else if constexpr (AMODE == A_UNIFORM) {
             const bool live = kt_run < kt_end;
-            const unsigned tap_off = (unsigned)((u_kh * p.W + u_kw) * p.Cin + u_ci) * 2u;      // scalar
+            const unsigned tap_off = (unsigned)((u_kh * p.W + u_kw) * p.ldx + u_ci) * 2u;      // scalar
 #pragma unroll
             for (int it = 0; it < A_IT; ++it) {
                 const int ok = (int)a_ok[it] & (int)live & (int)((unsigned)(a_ih0[it] + u_kh) < (unsigned)p.H) &
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(WM * WN * 64) void conv_gemm_kernel(GemmDev p)
             return;
         }
         const int k_ok = k_run < k_lim;
-        const unsigned tap_off = (unsigned)((kh_run * p.W + kw_run) * p.Cin + ci_run) * 2u;
+        const unsigned tap_off = (unsigned)((kh_run * p.W + kw_run) * p.ldx + ci_run) * 2u;
 #pragma unroll
         for (int it = 0; it < A_IT; ++it) {
             const int ok = (int)a_ok[it] & k_ok & (int)((unsigned)(a_ih0[it] + kh_run) < (unsigned)p.H) &

@@ -36,7 +36,7 @@ namespace {
 // The slices are read eight at a time so that their loads overlap; the additions keep slice order.
 template <typename T>
 __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int splits, int M, int N, const uint16_t *bias,
-                                                           const uint16_t *res, uint16_t *y, float *y32, int act)
+                                                           const uint16_t *res, uint16_t *y, float *y32, int act, int ldy)
 {
     const bool vec = ((N & 3) == 0);
     const int per_row = vec ? N / 4 : N;
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(64) void splitk_reduce_kernel(const float *ws, int 
     } else {
         for (int z = 0; z < splits; ++z) s[0] += src[z * slice];
     }
-#define EPI(A) epilogue_store<T, A>(bias, res, y, y32, M, N, m, n, s, vec ? 4 : 1)
+#define EPI(A) epilogue_store<T, A>(bias, res, y, y32, M, N, m, n, s, vec ? 4 : 1, ldy)
     ECLIP_ACT_SWITCH(act, EPI)
 #undef EPI
 }
@@ -98,7 +98,7 @@ hipError_t launch_pp_split(const GemmDev &d, const GemmPlan &pl, hipStream_t s, 
     if (e != hipSuccess || pl.splits == 1) return e;
     const long threads = (long)d.M * ((d.N & 3) == 0 ? d.N / 4 : d.N);
     hipLaunchKernelGGL((splitk_reduce_kernel<T>), dim3((unsigned)((threads + 63) / 64)), dim3(64), 0, s, d.ws, pl.splits, d.M, d.N,
-                       d.bias, d.res, d.y, d.y32, d.act);
+                       d.bias, d.res, d.y, d.y32, d.act, d.ldy);
     return hipGetLastError();
 }
 
@@ -380,7 +380,9 @@ static GemmDev make_dev(const ConvGemmArgs &a, const GemmPlan &pl)
     d.stride = a.stride; d.pad = a.pad; d.act = a.act;
     d.M = a.B * a.Ho * a.Wo; d.N = a.Cout; d.K = a.KH * a.KW * a.Cin;
     d.nchw_c = a.nchw_c;
-    d.x_bytes = (unsigned)((size_t)a.B * a.H * a.W * (a.nchw_c ? a.nchw_c : a.Cin) * 2);
+    d.ldx = a.ldx ? a.ldx : a.Cin;
+    d.ldy = a.ldy ? a.ldy : a.Cout;
+    d.x_bytes = (unsigned)((size_t)a.B * a.H * a.W * (a.nchw_c ? a.nchw_c : d.ldx) * 2);
     d.w_bytes = (unsigned)((size_t)((d.N + 15) / 16) * ((d.K + 31) / 32) * 1024);   // blocked layout, see ConvGemmArgs::w
     int bm, bn, bk;
     conv_gemm_tile(pl.variant, &bm, &bn, &bk);
@@ -400,6 +402,8 @@ static GemmDev make_dev(const ConvGemmArgs &a, const GemmPlan &pl)
 
 hipError_t launch_conv_gemm(const ConvGemmArgs &a, const GemmPlan &pl, hipStream_t s, uint32_t *n_launched)
 {
+    if ((a.ldx && (a.ldx % 8 || a.ldx < a.Cin || a.nchw_c)) || (a.ldy && (a.ldy % 8 || a.ldy < a.Cout || a.res || a.y32 || ((uintptr_t)a.y & 15))))
+        return hipErrorInvalidValue;
     const GemmDev d = make_dev(a, pl);
     if (n_launched) *n_launched += pl.splits > 1 ? 2 : 1;
     if (pl.kind == 1) return launch_conv_wsk(d, a.dtype, pl.variant, pl.nw, pl.tiles, s);
@@ -411,6 +415,9 @@ hipError_t launch_conv_gemm_pair(const ConvGemmArgs &a0, const GemmPlan &p0, con
                                  uint32_t *n_launched)
 {
     if (p0.kind != 1 || p1.kind != 1 || p0.variant != p1.variant || p0.nw != p1.nw || a0.dtype != a1.dtype) return hipErrorInvalidValue;
+    for (const ConvGemmArgs *a : {&a0, &a1})
+        if ((a->ldx && (a->ldx % 8 || a->ldx < a->Cin || a->nchw_c)) || (a->ldy && (a->ldy % 8 || a->ldy < a->Cout || a->res || a->y32 || ((uintptr_t)a->y & 15))))
+            return hipErrorInvalidValue;
     if (n_launched) *n_launched += 1;
     return launch_conv_wsk_pair(make_dev(a0, p0), p0.tiles, make_dev(a1, p1), p1.tiles, a0.dtype, p0.variant, p0.nw, s);
 }

@@ -378,6 +378,19 @@ __global__ __launch_bounds__(256) void concat_kernel(const T *a, const T *b, T *
     Pack<T, V>::store(y + m * (c0 + c1) + c, v);
 }
 
+// y[m][0 .. c) = x[m][:] where y's rows are ld channels apart: the first operand of a concatenation done in place
+// (c and ld multiples of 8, 16-bit types)
+template <typename T>
+__global__ __launch_bounds__(256) void chancopy_kernel(const T *x, T *y, int c, int ld, long total)
+{
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const unsigned cv = (unsigned)c / 8, ui = (unsigned)idx;
+    const unsigned j = (ui % cv) * 8;
+    const long m = ui / cv;
+    *reinterpret_cast<uint4 *>(y + m * ld + j) = *reinterpret_cast<const uint4 *>(x + m * c + j);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void shuffle_kernel(const T *x, T *y, int c, int groups, long total)
 {
@@ -839,6 +852,14 @@ hipError_t launch_concat(const void *a, const void *b, void *y, long rows, int c
     else if (dtype == DT_BF16) { if (vec) CC(bf16_t, 8) else CC(bf16_t, 1) }
     else { if (vec) CC(f16_t, 8) else CC(f16_t, 1) }
 #undef CC
+    return hipGetLastError();
+}
+
+hipError_t launch_chancopy(const void *x, void *y, long rows, int c, int ld, int dtype, hipStream_t s)
+{
+    if (dtype == DT_F32 || c % 8 || ld % 8 || ld < c || rows * (long)ld >= (1L << 31)) return hipErrorInvalidValue;
+    const long total = rows * (c / 8);
+    hipLaunchKernelGGL((chancopy_kernel<uint16_t>), dim3(blocks_for(total, 256)), dim3(256), 0, s, (const uint16_t *)x, (uint16_t *)y, c, ld, total);
     return hipGetLastError();
 }
 

@@ -43,7 +43,7 @@ __device__ __forceinline__ void wsk_finish(const GemmDev &p, const float4 *red4,
             const int m = m_base + r, n = n_base + c8 * 8;
             if (m < p.M && n < p.N) {
                 float o[8] = {s0[0], s0[1], s0[2], s0[3], s1[0], s1[1], s1[2], s1[3]};
-                epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, m, n, o);
+                epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.ldy, m, n, o);
             }
         }
         return;
@@ -58,7 +58,7 @@ __device__ __forceinline__ void wsk_finish(const GemmDev &p, const float4 *red4,
         const int blk = slot >> 6, l = slot & 63;
         const int i = blk / TN, j = blk - i * TN;
         // lane l of block (i, j) holds output pixel 16*i + (l & 15), channels 16*j + 4*(l >> 4) .. +3
-        epilogue_store<T, ACT>(p.bias, p.res, p.y, p.y32, p.M, p.N, m_base + i * 16 + (l & 15), n_base + j * 16 + (l >> 4) * 4, s);
+        epilogue_store<T, ACT>(p.bias, p.res, p.y, p.y32, p.M, p.N, m_base + i * 16 + (l & 15), n_base + j * 16 + (l >> 4) * 4, s, 4, p.ldy);
     }
 }
 
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p
         a_ih0[i] = oh * p.stride - p.pad;
         a_iw0[i] = ow * p.stride - p.pad;
         if constexpr (NCHW) a_off0[i] = ((unsigned)(b * p.nchw_c) * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * 2u;
-        else a_off0[i] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * (unsigned)p.Cin * 2u;
+        else a_off0[i] = ((unsigned)b * (unsigned)(p.H * p.W) + (unsigned)(a_ih0[i] * p.W + a_iw0[i])) * (unsigned)p.ldx * 2u;
     }
     const unsigned plane = (unsigned)(p.H * p.W) * 2u;            // NCHW: bytes between the planes of two channels
     // weights: 1 KB blocks of 16 rows x 32 k in lane order, so a fragment is one contiguous load
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(NW * 64) void conv_wsk_kernel(GemmDev p0, GemmDev p
     // branch-free: a lane whose chunk is padding, beyond M / N or beyond the wavefront's K slice loads zeros
     auto load = [&](Frag &f) {
         const int k_ok = k < k_lim, kb_ok = kb < ks1;
-        const unsigned tap_off = NCHW ? (unsigned)(kh * p.W + kw) * 2u : (unsigned)((kh * p.W + kw) * p.Cin + ci) * 2u;
+        const unsigned tap_off = NCHW ? (unsigned)(kh * p.W + kw) * 2u : (unsigned)((kh * p.W + kw) * p.ldx + ci) * 2u;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int ok = a_ok[i] & k_ok & (int)((unsigned)(a_ih0[i] + kh) < (unsigned)p.H) & (int)((unsigned)(a_iw0[i] + kw) < (unsigned)p.W);

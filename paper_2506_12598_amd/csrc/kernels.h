@@ -25,6 +25,9 @@ struct ConvGemmArgs {
     float *ws;           // split-K partial sums, >= splits*M*Cout floats when splits > 1
     int B, H, W, Cin, Ho, Wo, Cout, KH, KW, stride, pad, act, dtype;
     int nchw_c = 0;      // > 0: x is [B][nchw_c][H][W] with nchw_c <= 4 real channels, Cin == 8 (wave-split-K plans of conv_gemm_plan_stem only)
+    int ldx = 0;         // > 0: elements between consecutive pixels of x (x is the first Cin channels of a wider tensor); a multiple of 8
+    int ldy = 0;         // > 0: elements between consecutive rows of y (y points at a channel range of a wider tensor); a multiple of 8,
+                         // y 16-byte aligned, res and y32 null
 };
 struct GemmPlan {
     int kind;      // 0 = LDS-tiled kernel (large problems), 1 = wave-split-K kernel (few tiles, long K)
@@ -94,6 +97,8 @@ hipError_t launch_gconv_mfma(const GConvArgs &a, int S, int n_cu, hipStream_t s)
 long gconv_mfma_workgroups(long M, int groups, int cog, int S, int n_cu);   // the grid launch_gconv_mfma uses (M = B*Ho*Wo)
 // y[m][0 .. c0) = a[m][:], y[m][c0 .. c0 + c1) = b[m][:]
 hipError_t launch_concat(const void *a, const void *b, void *y, long rows, int c0, int c1, int dtype, hipStream_t s);
+// y[m][0 .. c) = x[m][:], rows of y ld channels apart (16-bit types, c and ld multiples of 8)
+hipError_t launch_chancopy(const void *x, void *y, long rows, int c, int ld, int dtype, hipStream_t s);
 // y[m][j] = x[m][(j % groups) * (c / groups) + j / groups]
 hipError_t launch_shuffle(const void *x, void *y, long rows, int c, int groups, int dtype, hipStream_t s);
 

@@ -447,6 +447,56 @@ def test_densenet_style_small():
     check(wl.densenet(blocks=(2, 4, 2), growth=16, hw=64, n_classes=100), batch=2)
 
 
+def _kernels_of(m):
+    h = ec.Model(shared_pool(), m, wl.to_storage(m.weights, m.dtype), max_batch=1)
+    try:
+        return [h.kernel_info(i, 0, 1) for i in range(len(m.layers))]
+    finally:
+        h.free()
+
+
+def test_densenet_blocks_concatenate_in_place_and_match_the_copying_path():
+    """A chain of concatenations shares one buffer: the head copies its first operand in, the others launch nothing, the
+    convolutions in between read and write channel ranges of that buffer.  Same result as with ECLIP_CONCAT_COPY=1 (every
+    CONCAT a copy kernel), bit for bit, and both within tolerance of the oracle."""
+    m = wl.densenet(blocks=(3, 4), growth=16, hw=48, n_classes=50)
+    info = _kernels_of(m)
+    names = [k["kernel"] for k, L in zip(info, m.layers) if L.op == wl.OP_CONCAT]
+    assert names == ["chancopy_kernel", "(in place)", "(in place)", "chancopy_kernel", "(in place)", "(in place)", "(in place)"]
+    assert all(k["launches"] == 0 for k in info if k["kernel"] == "(in place)")
+    x = wl.make_input(m, 3)
+    got = run_gpu(m, x)
+    os.environ["ECLIP_CONCAT_COPY"] = "1"
+    try:
+        assert all(k["kernel"] == "concat_kernel" for k, L in zip(_kernels_of(m), m.layers) if L.op == wl.OP_CONCAT)
+        ref = run_gpu(m, x)
+    finally:
+        os.environ.pop("ECLIP_CONCAT_COPY", None)
+    assert np.array_equal(got, ref)
+    assert rel_to_range(got, orc.run_model(m, x)) <= TOL_16
+
+
+def test_concatenation_chain_breaks_at_a_reader_that_needs_a_contiguous_tensor():
+    """c1 = concat(x0, y1) is also read by a max-pool, which knows nothing of channel pitches: c2 = concat(c1, y2) must
+    start a buffer of its own (copying c1), while c3 = concat(c2, q) extends it in place."""
+    import workloads.graphs as G
+    b = G._Builder("chain", wl.DT_BF16, 3, G.IN_IMAGE, 16, 12, 12)
+    x0 = b.conv(-1, 32, 3, 1, 1, wl.ACT_RELU)
+    y1 = b.conv(x0, 16, 3, 1, 1, wl.ACT_RELU)
+    c1 = b.concat(x0, y1)
+    y2 = b.conv(c1, 16, 1, 1, 0, wl.ACT_RELU)
+    c2 = b.concat(c1, y2)
+    p = b.maxpool(c1, 3, 1, 1)
+    q = b.conv(p, 24, 3, 1, 1, wl.ACT_NONE, bias_std=0.3)
+    c3 = b.concat(c2, q)
+    b.conv(c3, 40, 1, 1, 0, wl.ACT_NONE)
+    m = b.finish()
+    names = [k["kernel"] for k, L in zip(_kernels_of(m), m.layers) if L.op == wl.OP_CONCAT]
+    assert names == ["chancopy_kernel", "chancopy_kernel", "(in place)"]
+    for batch in (1, 3):
+        check(m, batch=batch, tol=8e-3)
+
+
 def test_shufflenet_style_small():
     check(wl.shufflenet(groups=4, reps=(2, 2), base=128, hw=64, n_classes=100), batch=2)
 
