@@ -35,6 +35,7 @@
  *                         convolution reading the caller's tensor)
  *   ECLIP_GCONV_DIRECT=1  read at eclip_model_load: grouped convolutions take the direct kernel, not the matrix cores
  *   ECLIP_CONCAT_COPY=1   read at eclip_model_load: every CONCAT layer copies its operands (no concatenation in place)
+ *   ECLIP_SHUFFLE_KERNEL=1  read at eclip_model_load: every SHUFFLE layer runs its kernel (no folding into weights)
  *   ECLIP_TRACE=1         the set-up steps of the library (pool, model load) on stderr
  */
 #ifndef ECLIP_H

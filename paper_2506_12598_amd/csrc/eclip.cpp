@@ -368,6 +368,9 @@ struct LayerPlan {
     int c_off = 0;             // first channel of this layer's output in it
     bool concat_copy = false;  // CONCAT in place, head of a chain: the first operand is copied into the buffer, the second is there
     bool concat_noop = false;  // CONCAT in place whose operands are both already in the buffer: nothing to launch
+    // Channel shuffle folded into weights: the SHUFFLE layer launches nothing and its readers' weights are permuted at load.
+    bool shuffle_noop = false;
+    int perm_groups = 0;       // > 0: this layer's input arrives NOT shuffled; its weights are laid out for that order
     bool pair_next = false;    // this layer and the next are independent GEMM layers of one group: one launch may carry both
     bool gapfc_next = false;   // global average pool whose only reader is the linear layer that follows: one launch may do both
 };
@@ -728,6 +731,45 @@ static eclip_status plan_model(const eclip_model_desc *d, size_t weight_elems, e
             B.c_off = C.in.c;
         }
     }
+    // Channel shuffle folded into weights (ShuffleNet-style units: grouped 1x1 -> shuffle -> depthwise -> grouped 1x1).
+    // A shuffle is a fixed permutation of channels, y[j] = x[s(j)].  A depthwise convolution treats channels one by one,
+    // so dw(shuffle(x)) = shuffle(dw'(x)) with dw' = dw with its per-channel filters permuted; and a convolution that sums
+    // over ALL of its input channels (dense, or grouped with every group inside one super-group of the matrix-core
+    // kernel, whose weight block is stored dense anyway) absorbs a permutation of its input into the order of its weight
+    // columns.  So when a SHUFFLE is read only by a depthwise CONV (no residual) that is read only by such a convolution,
+    // the two filters are permuted once at load and the SHUFFLE layer is its input, untouched: no launch, no traffic.
+    if (m->dtype != ECLIP_F32 && !getenv("ECLIP_SHUFFLE_KERNEL")) {
+        const int n = (int)d->n_layers;
+        auto readers_of = [&](int idx, int *only) {
+            int cnt = 0;
+            for (int j = 0; j < n; ++j)
+                if (m->layers[j].L.in0 == idx || m->layers[j].L.in1 == idx) { ++cnt; *only = j; }
+            return cnt;
+        };
+        for (int i = 0; i + 2 < n; ++i) {
+            LayerPlan &S = m->layers[i];
+            if (S.L.op != ECLIP_OP_SHUFFLE || S.L.in0 < 0 || S.L.groups < 2) continue;
+            const LayerPlan &A = m->layers[S.L.in0];
+            if (A.buf != S.L.in0 || A.ld) continue;                        // the input is a plain tensor of its own
+            int dwi = -1, g2 = -1;
+            if (readers_of(i, &dwi) != 1) continue;
+            LayerPlan &D = m->layers[dwi];
+            const bool is_dw = D.L.op == ECLIP_OP_CONV && D.L.groups > 1 && D.L.groups == D.in.c && D.L.c == D.L.groups;
+            if (!is_dw || D.L.in0 != i || D.L.in1 != -2 || dwi == n - 1) continue;
+            if (readers_of(dwi, &g2) != 1) continue;
+            LayerPlan &Gc = m->layers[g2];
+            if (Gc.L.op != ECLIP_OP_CONV || Gc.L.in0 != dwi || Gc.L.in1 == dwi) continue;
+            const bool dense = Gc.gemm && Gc.L.groups == 1;
+            const bool grouped = Gc.L.groups > 1 && !(Gc.L.groups == Gc.in.c && Gc.L.c == Gc.L.groups);
+            const bool one_super_group = grouped && Gc.L.groups <= 16 && Gc.in.c % 32 == 0 && Gc.L.c % 16 == 0 && !getenv("ECLIP_GCONV_DIRECT");
+            if (!dense && !one_super_group) continue;
+            if (one_super_group) Gc.gc_super = Gc.L.groups;
+            S.shuffle_noop = true;
+            S.buf = S.L.in0;
+            D.perm_groups = S.L.groups;
+            Gc.perm_groups = S.L.groups;
+        }
+    }
     return ECLIP_OK;
 }
 
@@ -756,6 +798,10 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
             const bool dw = L.op == ECLIP_OP_CONV && L.groups > 1 && L.groups == cin_l && L.c == L.groups;
             const bool grouped = L.op == ECLIP_OP_CONV && L.groups > 1 && !dw;
             const E *src = w + L.w_off;
+            // input channel i of this layer, as it arrives, is channel unshuf(i) of the tensor the weights were made for
+            // (identity unless a channel shuffle in front of the layer was folded away: shuffled[j] = x[(j % G)(c/G) + j/G])
+            const int pg = P.perm_groups, pcg = pg ? cin_l / pg : 1;
+            auto unshuf = [&](int i) { return pg ? (i % pcg) * pg + i / pcg : i; };
             if (grouped && P.gc_super) {
                 // Block-diagonal dense weights of every super-group (gc_super neighbouring groups), in the 1 KB blocks of
                 // 16 output channels x 32 k that the matrix instruction consumes: block (sg, nb, t) at
@@ -778,8 +824,9 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
                                 E *d8 = dst + (((sg * NB + nb) * KT + t) * 64 + (size_t)l) * 8;
                                 for (int e = 0; e < 8; ++e) {
                                     const size_t k = k0 + e;
-                                    if (n / cog != k / cig) continue;                  // off the diagonal
-                                    const size_t co = sg * SO + n, ci = k % cig;
+                                    const size_t kk = pg ? (size_t)unshuf((int)k) : k;          // pg: one super-group, k is the layer's channel
+                                    if (n / cog != kk / cig) continue;                 // off the diagonal
+                                    const size_t co = sg * SO + n, ci = kk % cig;
                                     d8[e] = src[(co * cig + ci) * kh * kw + tap];
                                 }
                             }
@@ -797,7 +844,7 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
             if (dw) {                                   // -> [kh][kw][c]
                 std::vector<E> t((size_t)kh * kw * L.c);
                 for (int c = 0; c < L.c; ++c)
-                    for (int i = 0; i < kh * kw; ++i) t[(size_t)i * L.c + c] = src[(size_t)c * kh * kw + i];
+                    for (int i = 0; i < kh * kw; ++i) t[(size_t)i * L.c + c] = src[(size_t)unshuf(c) * kh * kw + i];
                 put(arena, cursor, t.data(), t.size() * es, &P.w_dev);
             } else if (f32) {                           // -> [kh][kw][cin][cout]
                 std::vector<E> t((size_t)kh * kw * cin_s * L.c);
@@ -815,13 +862,13 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
                 const size_t K = (size_t)kh * kw * cin_s;
                 const size_t KB = (K + 31) / 32, NB = ((size_t)L.c + 15) / 16;
                 std::vector<E> plain((size_t)L.c * K, 0);
-                if (kh * kw == 1 && cin_l == cin_s) {
+                if (kh * kw == 1 && cin_l == cin_s && !pg) {
                     memcpy(plain.data(), src, plain.size() * es);
                 } else {
                     for (int co = 0; co < L.c; ++co)
                         for (int ci = 0; ci < cin_l; ++ci)
                             for (int i = 0; i < kh * kw; ++i)
-                                plain[(size_t)co * K + (size_t)i * cin_s + ci] = src[((size_t)co * cin_l + ci) * kh * kw + i];
+                                plain[(size_t)co * K + (size_t)i * cin_s + ci] = src[((size_t)co * cin_l + unshuf(ci)) * kh * kw + i];
                 }
                 size_t off;
                 put(arena, cursor, nullptr, NB * KB * 512 * es, &off);
@@ -838,7 +885,11 @@ static void relayout_weights(eclip_model *m, const E *w, std::vector<char> &aren
                         }
                 P.w_dev = off;
             }
-            if (L.b_off >= 0) put(arena, cursor, w + L.b_off, (size_t)L.c * es, &P.b_dev);
+            if (L.b_off >= 0 && dw && pg) {             // a depthwise layer's channels moved with its input's: so does its bias
+                std::vector<E> t((size_t)L.c);
+                for (int c = 0; c < L.c; ++c) t[c] = w[L.b_off + unshuf(c)];
+                put(arena, cursor, t.data(), t.size() * es, &P.b_dev);
+            } else if (L.b_off >= 0) put(arena, cursor, w + L.b_off, (size_t)L.c * es, &P.b_dev);
         } else if (L.op == ECLIP_OP_LAYERNORM) {
             if (L.g_off >= 0) put(arena, cursor, w + L.g_off, (size_t)L.c * es, &P.g_dev);
             if (L.be_off >= 0) put(arena, cursor, w + L.be_off, (size_t)L.c * es, &P.be_dev);
@@ -1108,7 +1159,10 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
         name = P.concat_noop ? "(in place)" : P.concat_copy ? "chancopy_kernel" : "concat_kernel";
         if (P.concat_noop) out->launches = 0;
         break;
-    case ECLIP_OP_SHUFFLE: name = "shuffle_kernel"; break;
+    case ECLIP_OP_SHUFFLE:
+        name = P.shuffle_noop ? "(folded into weights)" : "shuffle_kernel";
+        if (P.shuffle_noop) out->launches = 0;
+        break;
     default: break;
     }
     snprintf(out->kernel, sizeof out->kernel, "%s", name);
@@ -1216,7 +1270,8 @@ static hipError_t launch_layer(eclip_model *m, uint32_t i, int batch, hipStream_
         else e = launch_concat(src(L.in0), src(L.in1), y, rows, P.in.c, L.c - P.in.c, dt, s);
         break;
     case ECLIP_OP_SHUFFLE:
-        e = launch_shuffle(src(L.in0), y, rows, L.c, L.groups, dt, s);
+        if (P.shuffle_noop) *n_launched -= 1;                // folded into the weights of the layers that read it
+        else e = launch_shuffle(src(L.in0), y, rows, L.c, L.groups, dt, s);
         break;
     default:
         e = hipErrorInvalidValue;

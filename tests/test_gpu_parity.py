@@ -501,5 +501,33 @@ def test_shufflenet_style_small():
     check(wl.shufflenet(groups=4, reps=(2, 2), base=128, hw=64, n_classes=100), batch=2)
 
 
+def test_channel_shuffle_folds_into_the_weights_of_its_readers():
+    """shuffle -> depthwise -> grouped 1x1 (all groups in one super-group): the shuffle launches nothing, the two
+    filters are permuted at load.  Same network output as with the shuffle kernel (ECLIP_SHUFFLE_KERNEL=1) up to the
+    order of the float32 sums, and within tolerance of the oracle; also with a dense 1x1 as the last reader."""
+    import workloads.graphs as G
+    m = wl.shufflenet(groups=4, reps=(2, 2), base=128, hw=64, n_classes=100)
+    names = [k["kernel"] for k, L in zip(_kernels_of(m), m.layers) if L.op == wl.OP_SHUFFLE]
+    assert names == ["(folded into weights)"] * 4
+    b = G._Builder("shuf_dense", wl.DT_F16, 5, G.IN_IMAGE, 32, 9, 11)
+    y = b.conv(-1, 48, 1, 1, 0, wl.ACT_RELU, groups=4, bias_std=0.2)
+    y = b.shuffle(y, 4)
+    y = b.conv(y, 48, 3, 2, 1, wl.ACT_NONE, groups=48, bias_std=0.5)
+    b.conv(y, 40, 1, 1, 0, wl.ACT_RELU, bias_std=0.2)
+    m2 = b.finish()
+    assert [k["kernel"] for k in _kernels_of(m2)][1] == "(folded into weights)"
+    for model in (m, m2):
+        x = wl.make_input(model, 2)
+        got = run_gpu(model, x)
+        os.environ["ECLIP_SHUFFLE_KERNEL"] = "1"
+        try:
+            assert all(k["kernel"] == "shuffle_kernel" for k, L in zip(_kernels_of(model), model.layers) if L.op == wl.OP_SHUFFLE)
+            ref = run_gpu(model, x)
+        finally:
+            os.environ.pop("ECLIP_SHUFFLE_KERNEL", None)
+        assert rel_to_range(got, ref) <= 2e-3
+        assert rel_to_range(got, orc.run_model(model, x)) <= TOL_16
+
+
 def test_albert_style_small():
     check(wl.albert(n_layers=4, hidden=256, heads=4, ffn=512, seq=64, vocab=1000, embed=64), batch=2)
