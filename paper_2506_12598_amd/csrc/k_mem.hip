@@ -220,16 +220,43 @@ __global__ __launch_bounds__(256) void dwconv3_row_kernel(DwConvArgs a, unsigned
     }
 }
 
-// The same for stride-1 layers tall enough to give every compute unit several strips: a thread owns PW output
+// The same for stride-1 layers tall enough to give every compute unit several strips: a thread owns 2 output
 // columns x `ph` output rows of 8 channels and walks down its strip.  An input row is then loaded once per strip
-// instead of once per output row it touches, the 9 weight vectors, the bias and the index arithmetic are paid once
-// per strip, and the input row of the next output row is in flight while the current one is multiplied.  The input
-// rows live in a ring of R register rows (R - 3 rows ahead of the arithmetic); the walk is unrolled by R so that ring
-// positions are constants.
-template <typename T, int PW, int R>
+// instead of once per output row it touches, the weights, the bias and the index arithmetic are paid once per strip,
+// and the input row of the next output row is in flight while the current one is multiplied.
+// Arithmetic: the kernel was bound by its vector instructions, not by memory (two per multiply-add: unpack a 16-bit
+// value, fused multiply-add; 19 instructions per output element with the weights unpacked again for every row).  Now
+// two horizontally adjacent taps of one channel go through one v_dot2 (float accumulate of two 16-bit products): when
+// an input row arrives, the columns (0,1) and (1,2) of every channel are packed into pairs with v_perm_b32 -- once per
+// input row, used by the three output rows that read it -- and the weights are packed the same way, (kw 0, kw 1), once
+// per strip; the third tap of a row stays a fused multiply-add.  10 instructions per output element.  That alone
+// changed nothing (237 -> 234 us at 192 x 1120 x 1120): with one row of loads in flight per thread the kernel waits for
+// memory, and the registers the packed weights freed now hold three input rows in flight instead of one (-> 217 us).
+// Three paired rows are live (ring) and three raw rows are on their way (raw); the walk is unrolled by 3 so that
+// ring positions are constants.
+template <typename T> struct Dot2;
+template <> struct Dot2<bf16_t> {
+    __device__ static __forceinline__ float run(uint32_t a, uint32_t b, float c)
+    {
+        typedef __bf16 v2 __attribute__((ext_vector_type(2)));
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(v2, a), __builtin_bit_cast(v2, b), c, false);
+    }
+};
+template <> struct Dot2<f16_t> {
+    __device__ static __forceinline__ float run(uint32_t a, uint32_t b, float c)
+    {
+        typedef _Float16 v2 __attribute__((ext_vector_type(2)));
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(v2, a), __builtin_bit_cast(v2, b), c, false);
+    }
+};
+// (low half of a, low half of b) and (high half of a, high half of b) as 2 x 16 bits, a in the low half of the result
+__device__ __forceinline__ uint32_t pair_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t pair_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+template <typename T, int R>
 __global__ __launch_bounds__(256, 2) void dwconv3_strip_kernel(DwConvArgs a, unsigned total, unsigned wq, unsigned hq, int ph)
 {
-    constexpr int COLS = PW + 2;
+    constexpr int PW = 2, COLS = PW + 2;
     const unsigned ui = banded_block() * blockDim.x + threadIdx.x;
     if (ui >= total) return;
     const unsigned cv = (unsigned)a.C >> 3;
@@ -242,10 +269,22 @@ __global__ __launch_bounds__(256, 2) void dwconv3_strip_kernel(DwConvArgs a, uns
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, (int)((unsigned)a.B * a.H * a.W * a.C * 2u), 0x00020000);
     const T *w = (const T *)a.w;
-    uint4 wp[9];                             // the 9 taps x 8 channels, kept packed: 36 registers instead of 72
-    float bv[8];
+    uint32_t wpair[3][8];                    // (kw 0, kw 1) of every row of the window, per channel
+    float wlast[3][8], bv[8];                // kw 2
 #pragma unroll
-    for (int t = 0; t < 9; ++t) wp[t] = *reinterpret_cast<const uint4 *>(w + (long)t * a.C + c);
+    for (int kh = 0; kh < 3; ++kh) {
+        const uint4 q0 = *reinterpret_cast<const uint4 *>(w + (long)(kh * 3 + 0) * a.C + c);
+        const uint4 q1 = *reinterpret_cast<const uint4 *>(w + (long)(kh * 3 + 1) * a.C + c);
+        const uint4 q2 = *reinterpret_cast<const uint4 *>(w + (long)(kh * 3 + 2) * a.C + c);
+        const uint32_t w0[4] = {q0.x, q0.y, q0.z, q0.w}, w1[4] = {q1.x, q1.y, q1.z, q1.w}, w2[4] = {q2.x, q2.y, q2.z, q2.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            wpair[kh][2 * e] = pair_lo(w0[e], w1[e]);
+            wpair[kh][2 * e + 1] = pair_hi(w0[e], w1[e]);
+            wlast[kh][2 * e] = Cvt<T>::from_bits(w2[e] & 0xffffu);
+            wlast[kh][2 * e + 1] = Cvt<T>::from_bits(w2[e] >> 16);
+        }
+    }
     if (a.bias) Pack<T, 8>::load((const T *)a.bias + c, bv);
     else
 #pragma unroll
@@ -255,7 +294,11 @@ __global__ __launch_bounds__(256, 2) void dwconv3_strip_kernel(DwConvArgs a, uns
 #pragma unroll
     for (int j = 0; j < COLS; ++j) col_off[j] = (unsigned)(iw0 + j) < (unsigned)a.W ? (unsigned)((iw0 + j) * a.C + c) * 2u : 0xffffffffu;
     const unsigned row_bytes = (unsigned)(a.W * a.C) * 2u;
-    u32x4 ring[R][COLS];
+    // a ring row: columns (0,1) and (1,2) paired per channel, and columns 2 and 3 as loaded (8 channels in 4 registers)
+    struct Row { uint32_t p01[8], p12[8]; u32x4 c2, c3; };
+    static_assert(R == 3, "three paired rows are live, three more are on their way");
+    u32x4 raw[R][COLS];                      // rows on their way from memory, three rows ahead of the arithmetic
+    Row ring[R];                             // the three rows the current output row reads, paired
     auto load_row = [&](int r, u32x4 (&q)[COLS]) {           // input row ih0 + r of the strip
         const int ih = ih0 + r;
         const bool row_ok = (unsigned)ih < (unsigned)a.H;
@@ -264,13 +307,29 @@ __global__ __launch_bounds__(256, 2) void dwconv3_strip_kernel(DwConvArgs a, uns
         for (int j = 0; j < COLS; ++j)
             q[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, (row_ok && col_off[j] != 0xffffffffu) ? base + col_off[j] : 0xffffffffu, 0, 0);
     };
+    auto take = [&](const u32x4 (&q)[COLS], Row &d) {        // pairs the columns of a row that has arrived
+        const uint32_t x0[4] = {q[0].x, q[0].y, q[0].z, q[0].w}, x1[4] = {q[1].x, q[1].y, q[1].z, q[1].w}, x2[4] = {q[2].x, q[2].y, q[2].z, q[2].w};
 #pragma unroll
-    for (int r = 0; r < R - 1; ++r) load_row(r, ring[r]);
+        for (int e = 0; e < 4; ++e) {
+            d.p01[2 * e] = pair_lo(x0[e], x1[e]);
+            d.p01[2 * e + 1] = pair_hi(x0[e], x1[e]);
+            d.p12[2 * e] = pair_lo(x1[e], x2[e]);
+            d.p12[2 * e + 1] = pair_hi(x1[e], x2[e]);
+        }
+        d.c2 = q[2];
+        d.c3 = q[3];
+    };
+    // raw[k] and ring[k] hold rows k (mod 3).  Rows 0..4 are requested up front and rows 0, 1 paired; output row i then
+    // pairs row i + 2 and requests row i + 5 into the slot that frees.
+    load_row(0, raw[0]); load_row(1, raw[1]); load_row(2, raw[2]);
+    take(raw[0], ring[0]); load_row(3, raw[0]);
+    take(raw[1], ring[1]); load_row(4, raw[1]);
     for (int i0 = 0; i0 < ph; i0 += R) {
 #pragma unroll
         for (int u = 0; u < R; ++u) {
             const int i = i0 + u;                            // output row oh0 + i reads input rows i .. i + 2
-            load_row(i + R - 1, ring[(u + R - 1) % R]);      // R - 3 output rows ahead (beyond the image: zeros)
+            take(raw[(u + 2) % R], ring[(u + 2) % R]);
+            load_row(i + 5, raw[(u + 2) % R]);               // beyond the image: zeros
             float acc[PW][8];
 #pragma unroll
             for (int p = 0; p < PW; ++p)
@@ -278,28 +337,15 @@ __global__ __launch_bounds__(256, 2) void dwconv3_strip_kernel(DwConvArgs a, uns
                 for (int e = 0; e < 8; ++e) acc[p][e] = bv[e];
 #pragma unroll
             for (int kh = 0; kh < 3; ++kh) {
-                float wv[3][8];
+                const Row &r = ring[(u + kh) % R];
+                const uint32_t s2[4] = {r.c2.x, r.c2.y, r.c2.z, r.c2.w}, s3[4] = {r.c3.x, r.c3.y, r.c3.z, r.c3.w};
 #pragma unroll
-                for (int kw = 0; kw < 3; ++kw) {
-                    const uint32_t ws[4] = {wp[kh * 3 + kw].x, wp[kh * 3 + kw].y, wp[kh * 3 + kw].z, wp[kh * 3 + kw].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { wv[kw][2 * e] = Cvt<T>::from_bits(ws[e] & 0xffffu); wv[kw][2 * e + 1] = Cvt<T>::from_bits(ws[e] >> 16); }
-                }
-#pragma unroll
-                for (int j = 0; j < COLS; ++j) {
-                    const u32x4 q = ring[(u + kh) % R][j];
-                    const uint32_t xs[4] = {q.x, q.y, q.z, q.w};
-                    float xv[8];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) { xv[2 * e] = Cvt<T>::from_bits(xs[e] & 0xffffu); xv[2 * e + 1] = Cvt<T>::from_bits(xs[e] >> 16); }
-#pragma unroll
-                    for (int p = 0; p < PW; ++p) {
-                        const int kw = j - p;                // a constant once the loops are unrolled
-                        if (kw >= 0 && kw < 3) {
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) acc[p][e] = fmaf(xv[e], wv[kw][e], acc[p][e]);
-                        }
-                    }
+                for (int e = 0; e < 8; ++e) {
+                    acc[0][e] = Dot2<T>::run(r.p01[e], wpair[kh][e], acc[0][e]);
+                    acc[1][e] = Dot2<T>::run(r.p12[e], wpair[kh][e], acc[1][e]);
+                    const uint32_t h2 = s2[e >> 1], h3 = s3[e >> 1];
+                    acc[0][e] = fmaf(Cvt<T>::from_bits((e & 1) ? h2 >> 16 : h2 & 0xffffu), wlast[kh][e], acc[0][e]);
+                    acc[1][e] = fmaf(Cvt<T>::from_bits((e & 1) ? h3 >> 16 : h3 & 0xffffu), wlast[kh][e], acc[1][e]);
                 }
             }
             const int oh = oh0 + i;
@@ -760,12 +806,12 @@ int dwconv_pixels_per_thread(const DwConvArgs &a, int n_cu)
     return (total >= 4L * n_cu * 256 && total < (1L << 31)) ? 4 : 1;
 }
 
-// Output rows per thread of the strip kernel (a multiple of its ring size, 4), or 0 when the layer is not a stride-1
-// 3x3 one with at least 4 workgroups of strips per compute unit: the tallest of 24, 16, 12, 8 that leaves that many.
+// Output rows per thread of the strip kernel (a multiple of its ring size, 3), or 0 when the layer is not a stride-1
+// 3x3 one with at least 4 workgroups of strips per compute unit: the tallest of 24, 18, 12, 9 that leaves that many.
 int dwconv_strip_rows(const DwConvArgs &a, int n_cu)
 {
     if (dwconv_pixels_per_thread(a, n_cu) != 4 || a.stride != 1) return 0;
-    for (int ph : {24, 16, 12, 8}) {
+    for (int ph : {24, 18, 12, 9}) {
         const long strips = (long)a.B * ((a.Ho + ph - 1) / ph) * ((a.Wo + 1) / 2) * (a.C / 8);
         if (strips >= 4L * n_cu * 256) return ph;
     }
@@ -781,8 +827,8 @@ hipError_t launch_dwconv(const DwConvArgs &a, int n_cu, hipStream_t s)
             const unsigned hq = (unsigned)(a.Ho + ph - 1) / ph, wq2 = (unsigned)(a.Wo + 1) / 2;
             const long strips = (long)a.B * hq * wq2 * (a.C / 8);
             const dim3 grid(banded_blocks_for(strips, 256));
-            if (a.dtype == DT_BF16) hipLaunchKernelGGL((dwconv3_strip_kernel<bf16_t, 2, 4>), grid, dim3(256), 0, s, a, (unsigned)strips, wq2, hq, ph);
-            else hipLaunchKernelGGL((dwconv3_strip_kernel<f16_t, 2, 4>), grid, dim3(256), 0, s, a, (unsigned)strips, wq2, hq, ph);
+            if (a.dtype == DT_BF16) hipLaunchKernelGGL((dwconv3_strip_kernel<bf16_t, 3>), grid, dim3(256), 0, s, a, (unsigned)strips, wq2, hq, ph);
+            else hipLaunchKernelGGL((dwconv3_strip_kernel<f16_t, 3>), grid, dim3(256), 0, s, a, (unsigned)strips, wq2, hq, ph);
             return hipGetLastError();
         }
         const long total = (long)a.B * a.Ho * wq * (a.C / 8);
