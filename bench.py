@@ -896,15 +896,6 @@ def main():
     # ... and the corner of the configuration space where nothing is partitioned: every worker on a mask of all CUs.  The
     # (1 + alpha) law misjudges that corner by 10-15 % on this GPU in either direction (workgroups of different kernels
     # interleave on a compute unit more gracefully than "twice as long"), so it is always part of the trial.
-    # ... and two points between the model's partition and no partition at all: the measured-slope allocation with every
-    # CU count scaled by 4/3 and by 5/3 (nearest configuration).  More overlap than the model asks
-    # for, less than everything everywhere: on this GPU the best trade of throughput against energy often lies there.
-    base = next((c for c in cand if c[0] == "measured slope"), None) or next((c for c in cand if c[0] == "paper slope"), None)
-    if base is not None and n_w > 1:
-        for num, den in ((4, 3), (5, 3)):
-            a = [[min(range(len(configs)), key=lambda k: abs(configs[k] - configs[ci] * num / den)) for ci in w] for w in base[1]]
-            if not any(a == c[1] for c in cand):
-                cand.append((f"{base[0]}, CUs x {num}/{den}", a, [sum(1 for k in range(1, len(w)) if w[k] != w[k - 1]) for w in a]))
     a_full = [[full] * m.n_groups for m in models]
     if not any(a_full == c[1] for c in cand):
         cand.append(("every worker on all CUs (masked streams, full overlap)", a_full, [0] * n_w))
