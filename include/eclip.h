@@ -36,6 +36,8 @@
  *   ECLIP_GCONV_DIRECT=1  read at eclip_model_load: grouped convolutions take the direct kernel, not the matrix cores
  *   ECLIP_CONCAT_COPY=1   read at eclip_model_load: every CONCAT layer copies its operands (no concatenation in place)
  *   ECLIP_SHUFFLE_KERNEL=1  read at eclip_model_load: every SHUFFLE layer runs its kernel (no folding into weights)
+ *   ECLIP_SWITCH_EVENTS=1   read at eclip_model_load / eclip_bench_switch: stream switches are ordered by an event pair
+ *                         instead of stream memory operations (write / wait on a word of signal memory)
  *   ECLIP_TRACE=1         the set-up steps of the library (pool, model load) on stderr
  */
 #ifndef ECLIP_H
@@ -406,8 +408,8 @@ eclip_status eclip_alloc_kernel_wise(const eclip_alloc_problem *problem, uint32_
 /* Measures, with a trivially short kernel, the wall-clock cost per kernel of three ways of running
  * a chain of `iters` dependent kernels:
  *   same_stream_ns  all on pool entry mask_a (no repartitioning);
- *   pooled_ns       alternating between pool entries mask_a and mask_b, ordered by events
- *                   (switching through the pre-allocated pool);
+ *   pooled_ns       alternating between pool entries mask_a and mask_b, ordered the way eclip_submit orders a
+ *                   stream switch (switching through the pre-allocated pool);
  *   create_ns       every kernel on a stream created with mask_b's CU mask for that kernel (applying the mask
  *                   at run time): host time to create the stream and queue the dependent kernel on it; draining
  *                   and destroying the previous stream is not counted.
