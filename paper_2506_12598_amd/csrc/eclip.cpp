@@ -220,6 +220,50 @@ extern "C" eclip_status eclip_pool_pipe(const eclip_pool *pool, uint32_t mask_id
     return ECLIP_OK;
 }
 
+// A dependency between two streams ("the next kernel group waits for everything queued so far on the stream it leaves").
+// With stream memory operations (hipStreamWriteValue64 on the stream that is left, hipStreamWaitValue64 on the one that
+// is entered, on a word of signal memory) a hop costs about 6 us on top of the kernel, with an event pair about 13 us
+// (dependent chain of trivial kernels alternating between two masked streams: 9.0 against 16.3 us per kernel).  Values
+// grow by one per hop, and a hop's write is always queued before its wait, on a stream that has itself passed every
+// earlier wait of the chain, so the word only ever grows and no wait can be left behind unanswered.  Falls back to
+// events where the device lacks the operations or ECLIP_SWITCH_EVENTS is set.
+struct HopSignal {
+    uint64_t *word = nullptr;                // device, signal memory
+    uint64_t seq = 0;
+    hipError_t init(int device)
+    {
+        int can = 0;
+        if (getenv("ECLIP_SWITCH_EVENTS") || hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, device) != hipSuccess || !can) {
+            (void)hipGetLastError();
+            return hipSuccess;
+        }
+        hipError_t e = hipExtMallocWithFlags((void **)&word, 8, hipMallocSignalMemory);
+        if (e != hipSuccess) { word = nullptr; (void)hipGetLastError(); return hipSuccess; }
+        const uint64_t zero = 0;
+        e = hipMemcpy(word, &zero, 8, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { (void)hipFree(word); word = nullptr; }
+        return e;
+    }
+    void release()
+    {
+        if (word) (void)hipFree(word);
+        word = nullptr;
+    }
+    // `ev` is the event used when stream memory operations are not available
+    hipError_t hop(hipStream_t from, hipStream_t to, hipEvent_t ev)
+    {
+        if (word) {
+            const uint64_t v = ++seq;
+            hipError_t e = hipStreamWriteValue64(from, word, v, 0);
+            if (e != hipSuccess) return e;
+            return hipStreamWaitValue64(to, word, v, hipStreamWaitValueGte, ~(uint64_t)0);
+        }
+        hipError_t e = hipEventRecord(ev, from);
+        if (e != hipSuccess) return e;
+        return hipStreamWaitEvent(to, ev, 0);
+    }
+};
+
 extern "C" eclip_status eclip_bench_streams(eclip_pool *pool, const uint32_t *mask_ids, uint32_t n, uint32_t iters,
                                             double *ns_per_kernel)
 {
@@ -234,6 +278,8 @@ extern "C" eclip_status eclip_bench_streams(eclip_pool *pool, const uint32_t *ma
     hipError_t e = hipMemset(d, 0, 256);
     std::vector<hipEvent_t> ev(n, nullptr);
     for (uint32_t i = 0; i < n && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&ev[i], hipEventDisableTiming);
+    HopSignal hops;                                  // the same dependency mechanism eclip_submit uses
+    if (e == hipSuccess) e = hops.init(pool->device);
     double result = 0.0;
     for (int pass = 0; pass < 2 && e == hipSuccess; ++pass) {          // pass 0 warms every queue up
         const uint32_t count = pass == 0 ? std::min<uint32_t>(iters, 4 * n) : iters;
@@ -242,8 +288,7 @@ extern "C" eclip_status eclip_bench_streams(eclip_pool *pool, const uint32_t *ma
             const hipStream_t cur = pool->streams[mask_ids[i % n]].stream;
             if (i && n > 1) {
                 const hipStream_t prev = pool->streams[mask_ids[(i - 1) % n]].stream;
-                e = hipEventRecord(ev[i % n], prev);
-                if (e == hipSuccess) e = hipStreamWaitEvent(cur, ev[i % n], 0);
+                e = hops.hop(prev, cur, ev[i % n]);
             }
             if (e == hipSuccess) e = launch_tick(d, cur);
         }
@@ -252,6 +297,8 @@ extern "C" eclip_status eclip_bench_streams(eclip_pool *pool, const uint32_t *ma
     }
     for (hipEvent_t x : ev)
         if (x) (void)hipEventDestroy(x);
+    (void)hipDeviceSynchronize();
+    hops.release();
     (void)hipFree(d);
     if (e != hipSuccess) return fail(ECLIP_EHIP, "stream bench failed: %s", hipGetErrorString(e));
     *ns_per_kernel = result;
@@ -353,50 +400,6 @@ extern "C" eclip_status eclip_pool_probe_graph(eclip_pool *pool, uint32_t mask_i
 static const size_t NONE = (size_t)-1;
 
 struct Dims { int kind, c, h, w; };   // c as stored (the network input's channels may be padded)
-
-// A dependency between two streams ("the next kernel group waits for everything queued so far on the stream it leaves").
-// With stream memory operations (hipStreamWriteValue64 on the stream that is left, hipStreamWaitValue64 on the one that
-// is entered, on a word of signal memory) a hop costs about 6 us on top of the kernel, with an event pair about 13 us
-// (dependent chain of trivial kernels alternating between two masked streams: 9.0 against 16.3 us per kernel).  Values
-// grow by one per hop, and a hop's write is always queued before its wait, on a stream that has itself passed every
-// earlier wait of the chain, so the word only ever grows and no wait can be left behind unanswered.  Falls back to
-// events where the device lacks the operations or ECLIP_SWITCH_EVENTS is set.
-struct HopSignal {
-    uint64_t *word = nullptr;                // device, signal memory
-    uint64_t seq = 0;
-    hipError_t init(int device)
-    {
-        int can = 0;
-        if (getenv("ECLIP_SWITCH_EVENTS") || hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, device) != hipSuccess || !can) {
-            (void)hipGetLastError();
-            return hipSuccess;
-        }
-        hipError_t e = hipExtMallocWithFlags((void **)&word, 8, hipMallocSignalMemory);
-        if (e != hipSuccess) { word = nullptr; (void)hipGetLastError(); return hipSuccess; }
-        const uint64_t zero = 0;
-        e = hipMemcpy(word, &zero, 8, hipMemcpyHostToDevice);
-        if (e != hipSuccess) { (void)hipFree(word); word = nullptr; }
-        return e;
-    }
-    void release()
-    {
-        if (word) (void)hipFree(word);
-        word = nullptr;
-    }
-    // `ev` is the event used when stream memory operations are not available
-    hipError_t hop(hipStream_t from, hipStream_t to, hipEvent_t ev)
-    {
-        if (word) {
-            const uint64_t v = ++seq;
-            hipError_t e = hipStreamWriteValue64(from, word, v, 0);
-            if (e != hipSuccess) return e;
-            return hipStreamWaitValue64(to, word, v, hipStreamWaitValueGte, ~(uint64_t)0);
-        }
-        hipError_t e = hipEventRecord(ev, from);
-        if (e != hipSuccess) return e;
-        return hipStreamWaitEvent(to, ev, 0);
-    }
-};
 
 struct LayerPlan {
     eclip_layer L;
