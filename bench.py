@@ -570,15 +570,23 @@ def policies_mode(args):
     a_g, _, _ = ec.eclip_alloc_solve(256, configs, g_nk, g_beta, args.switch_max, max_configs=mc, switch_cost_ns=switch_cost_ns)
     policies.append((f"ECLIP, stage groups, switchMax {args.switch_max}, <= {mc} configs/worker, switch cost",
                      [[a_g[w][m.group_of_layer[k]] for k in range(len(m.layers))] for w, m in enumerate(stage_models)]))
-    # ECLIP on single kernels: the optimizer derives the groups; sweep of the switch budget
-    a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, args.switch_max, max_configs=mc, switch_cost_ns=switch_cost_ns)
-    policies.append((f"ECLIP, per kernel, switchMax {args.switch_max}, <= {mc} configs/worker, switch cost", a))
+    # ECLIP on single kernels: the optimizer derives the groups; sweep of the switch budget.  (The exact solver's state
+    # space grows with units x switch budget x CU sums; workers of 150+ kernels exceed its budget, and the sweep is
+    # then limited to what it accepts.)
+    def per_kernel(label, sm, **kw):
+        try:
+            a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, sm, **kw)
+            policies.append((label, a))
+        except ec.EclipError as err:
+            if err.status != ec.ELIMIT:
+                raise
+            log(f"{label}: not solved ({err})")
+    per_kernel(f"ECLIP, per kernel, switchMax {args.switch_max}, <= {mc} configs/worker, switch cost", args.switch_max,
+               max_configs=mc, switch_cost_ns=switch_cost_ns)
     # the budget alone (no price on a switch), as in the paper: how much do the switches it allows cost here?
     for sm in (0, 2, 4, 8, 14, 28):
-        a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, sm, max_configs=mc)
-        policies.append((f"ECLIP, per kernel, switchMax {sm}, <= {mc} configs/worker, no switch cost", a))
-    a, _, _ = ec.eclip_alloc_solve(256, configs, ones, beta, args.switch_max)
-    policies.append((f"ECLIP, per kernel, switchMax {args.switch_max}, model as printed (no stream limit, no switch cost)", a))
+        per_kernel(f"ECLIP, per kernel, switchMax {sm}, <= {mc} configs/worker, no switch cost", sm, max_configs=mc)
+    per_kernel(f"ECLIP, per kernel, switchMax {args.switch_max}, model as printed (no stream limit, no switch cost)", args.switch_max)
 
     rows = []
     pool = prof_pool
