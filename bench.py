@@ -904,6 +904,11 @@ def main():
     # ... and the corner of the configuration space where nothing is partitioned: every worker on a mask of all CUs.  The
     # (1 + alpha) law misjudges that corner by 10-15 % on this GPU in either direction (workgroups of different kernels
     # interleave on a compute unit more gracefully than "twice as long"), so it is always part of the trial.
+    # ... the plain static partition: equal disjoint shares, 256 / workers CUs each (what Model-Wise gives identical workers)
+    if 256 // n_w in configs and n_w > 1:
+        a_eq = [[configs.index(256 // n_w)] * m.n_groups for m in models]
+        if not any(a_eq == c[1] for c in cand):
+            cand.append(("equal disjoint shares", a_eq, [0] * n_w))
     a_full = [[full] * m.n_groups for m in models]
     if not any(a_full == c[1] for c in cand):
         cand.append(("every worker on all CUs (masked streams, full overlap)", a_full, [0] * n_w))
