@@ -371,21 +371,25 @@ def stats_from(trace_csv):
 # ---------------------------------------------------------------------------------------------------
 # single kernels at roofline shapes
 # ---------------------------------------------------------------------------------------------------
-def kernels_mode(only=None, extra_gemms=None, tune=True):
+def kernels_mode(only=None, extra_gemms=None, tune=True, cus=256):
     import workloads as wl
     import workloads.graphs as G
     import paper_2506_12598_amd as ec
-    pool = ec.Pool([(None, -1)])
+    # --cus N: the kernels run on a stream masked to N CUs (N / 8 in every XCD) and matrix-core rows are held against the
+    # matrix peak scaled by N / 256
+    sid = 0 if cus >= 256 else 1
+    pool = ec.Pool([(None, -1)] + ([] if cus >= 256 else [(ec.eclip_mask_layout(256, 16, 1, 0, cus // 16), 0)]))
+    mfma_peak = MFMA_PEAK_TFLOPS * min(cus, 256) / 256.0
     B = wl.DT_BF16
     rows = []
 
     def time_first(model, batch=1):
         h = ec.Model(pool, model, wl.to_storage(model.weights, model.dtype), max_batch=batch)
-        h.alloc_set([0] * model.n_groups)
+        h.alloc_set([sid] * model.n_groups)
         if tune:
-            h.tune(0, batch, 2)
-        ns = h.profile_group(0, 0, batch, 5)[0]
-        info = h.kernel_info(0, 0, batch)
+            h.tune(sid, batch, 2)
+        ns = h.profile_group(0, sid, batch, 5)[0]
+        info = h.kernel_info(0, sid, batch)
         h.free()
         return ns, info
 
@@ -400,7 +404,7 @@ def kernels_mode(only=None, extra_gemms=None, tune=True):
         ns, info = time_first(bb.finish())
         tf = 2.0 * m_ * k_ * n_ / ns / 1e3
         rows.append((f"{name} M{m_} N{n_} K{k_} tile {info['tile'][0]}x{info['tile'][1]}", info["kernel"], "mfma", tf,
-                     MFMA_PEAK_TFLOPS, "TFLOP/s", ns / 1e3))
+                     mfma_peak, "TFLOP/s", ns / 1e3))
 
     # every case is a two-layer model whose first layer is the kernel under test (so that it writes the 16-bit type)
     def c_ln():
@@ -452,6 +456,8 @@ def kernels_mode(only=None, extra_gemms=None, tune=True):
             m_, n_, k_ = (int(v) for v in shape.split(","))
             gemm("linear", m_, k_, n_)
     pool.destroy()
+    if cus < 256:
+        print(f"# on a stream masked to {cus} CUs; matrix-core rows against {mfma_peak:.1f} TFLOP/s = 2500 x {cus} / 256")
     print(f"{'case':66s} {'kernel':18s} {'bound':5s} {'achieved':>10s} {'peak':>8s} {'unit':8s} {'frac':>6s} {'us/launch':>10s}")
     for name, kern, bound, ach, peak, unit, us in rows:
         print(f"{name:66s} {kern:18s} {bound:5s} {ach:10.1f} {peak:8.0f} {unit:8s} {ach / peak:6.3f} {us:10.1f}")
@@ -671,6 +677,7 @@ def main():
     ap.add_argument("--no-tune", action="store_true", help="keep the planner's cost-model choices (skip eclip_model_tune)")
     ap.add_argument("--policy", default="eclip", choices=["eclip", "unpart_a", "unpart_b"], help="policy of the timed region")
     ap.add_argument("--kernels", action="store_true", help="time single kernels at roofline shapes and print a table")
+    ap.add_argument("--cus", type=int, default=256, help="with --kernels: run on a stream masked to this many CUs (a multiple of 16)")
     ap.add_argument("--gemm", default=None, help="with --kernels: time linear layers of these shapes, 'M,N,K;M,N,K;...'")
     ap.add_argument("--only", default=None, help="with --kernels: comma-separated case keys (layernorm, softmax, maxpool, dwconv, "
                     "gap, gelu, copy, fc, gemm8192, gemm4096, ffn1, ffn2, qkv, proj, base_ffn1)")
@@ -707,7 +714,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.init()
     if args.kernels:
-        kernels_mode(args.only, args.gemm, tune=not args.no_tune)
+        kernels_mode(args.only, args.gemm, tune=not args.no_tune, cus=args.cus)
         return
     if args.characterize:
         characterize_mode()
