@@ -36,7 +36,7 @@ special case:
                pair in use is one pooled stream, and the GPU runs only a few streams without
                oversubscribing its hardware queues (7 on the paper's MI50; 4 on MI355X, one per pipe).
   switch_cost  nanoseconds added to a worker's solo time per configuration switch: factor (iii) of
-               Sec. III-B ("the overhead of CU configuration switches"), which the paper bounds with the
+               Sec. III-B (what a change of CU configuration costs), which the paper bounds with the
                budget only; with a cost the optimizer stops switching for gains smaller than a switch.
 
 All arithmetic is exact (Python integers).  With D = lcm_w(N_w), S_D = D * sum_w

@@ -44,7 +44,7 @@ def test_hand_worked_example_optimum_and_tie_break():
 
 
 def test_calibration_two_identical_kernels_take_twice_as_long():
-    # Sec. III-B: two identical kernels sharing the same CUs both took twice as long -> alpha = 1.
+    # Sec. III-B calibrates alpha on one observation: a kernel co-run with a copy of itself on the same CUs needs 2x its solo time -> alpha = 1.
     beta = 1000
     p = wl.AllocProblem(60, [60], [wl.Worker([1], [[beta]]), wl.Worker([1], [[beta]])], 0, oa.OVERLAP_EXCESS)
     _, num, _ = oa.solve_exhaustive(p)
