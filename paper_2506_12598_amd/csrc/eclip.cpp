@@ -1190,7 +1190,10 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
         }
         break;
     }
-    case ECLIP_OP_MAXPOOL: name = "maxpool_kernel"; break;
+    case ECLIP_OP_MAXPOOL:
+        // 3x3 windows at stride 2 on vector-width channels: two outputs per thread (see launch_maxpool)
+        name = (P.L.kh == 3 && P.L.kw == 3 && P.L.stride == 2 && P.L.c % (model->dtype == ECLIP_F32 ? 4 : 8) == 0) ? "maxpool3s2_block_kernel" : "maxpool_kernel";
+        break;
     case ECLIP_OP_GAP: name = "gap_kernel"; break;
     case ECLIP_OP_LAYERNORM:
     case ECLIP_OP_SOFTMAX: {

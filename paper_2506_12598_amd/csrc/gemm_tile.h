@@ -25,6 +25,64 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
         // are all inside the row and aligned; otherwise the (rare) ragged form stores them one by one from a loop
         // that is not unrolled, to keep it out of the way.
         // 32 rows (two 16-row blocks) per round; an odd TM ends with a round of 16
+        if constexpr (N8 && TN % 2 == 0) {
+            // Even TN: no LDS at all.  The four lanes that hold a pixel's channels of two neighbouring blocks (quads
+            // q = lane >> 4 of blocks j and j + 1) trade registers so that each ends up with 8 consecutive channels:
+            // v_permlane16_swap exchanges the odd 16-lane rows of one register with the even rows of another, which
+            // leaves lane row q with channels 16 (q & 1) + 8 (q >> 1) .. +7 of the 32-channel pair.  A store
+            // instruction then writes 16 bytes per lane, 64 contiguous bytes per pixel.  Bias and residual are fetched
+            // before the first store, as below.
+            const int q = lane >> 4;
+            const int m0 = m_base + wm * (BM / WM) + (lane & 15);
+            const int n0 = n_base + wn * (BN / WN) + 16 * (q & 1) + 8 * (q >> 1);
+            float bv[TN / 2][8];
+            uint4 rq[TM][TN / 2];
+            static_for<TN / 2>([&](auto jc) {
+                constexpr int jp = decltype(jc)::value;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bv[jp][e] = 0.f;
+                if (p.bias && n0 + 32 * jp < p.N) Pack<T, 8>::load(reinterpret_cast<const T *>(p.bias) + n0 + 32 * jp, bv[jp]);
+            });
+            if (p.res) {
+                static_for<TM>([&](auto ic) {
+                    constexpr int i = decltype(ic)::value;
+                    static_for<TN / 2>([&](auto jc) {
+                        constexpr int jp = decltype(jc)::value;
+                        const int m = m0 + 16 * i, n = n0 + 32 * jp;
+                        rq[i][jp] = (m < p.M && n < p.N) ? *reinterpret_cast<const uint4 *>(p.res + (long)m * p.ldy + n) : make_uint4(0u, 0u, 0u, 0u);
+                    });
+                });
+            }
+            static_for<TM>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                static_for<TN / 2>([&](auto jc) {
+                    constexpr int jp = decltype(jc)::value;
+                    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                    float o[8];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const u32x2 sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[i][2 * jp][c]), __float_as_uint(acc[i][2 * jp + 1][c]), false, false);
+                        o[c] = __uint_as_float(sw[0]);
+                        o[4 + c] = __uint_as_float(sw[1]);
+                    }
+                    const int m = m0 + 16 * i, n = n0 + 32 * jp;
+                    if (m < p.M && n < p.N) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[e] += bv[jp][e];
+                        if (p.res) {
+                            const uint32_t w[4] = {rq[i][jp].x, rq[i][jp].y, rq[i][jp].z, rq[i][jp].w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                o[2 * e] += Cvt<T>::from_bits(w[e] & 0xffffu);
+                                o[2 * e + 1] += Cvt<T>::from_bits(w[e] >> 16);
+                            }
+                        }
+                        epilogue_store8<T, ACT>(nullptr, nullptr, p.y, p.y32, p.ldy, m, n, o);
+                    }
+                });
+            });
+            return;
+        }
         constexpr int COLS = TN * 16, SP = COLS + 4;          // row pitch in floats: the 4-float pad spreads the banks
         constexpr int LPR = COLS / 8, RPP = 64 / LPR;          // lanes per row, rows per pass (lanes beyond RPP * LPR idle)
         constexpr int PASSES = (32 + RPP - 1) / RPP;
@@ -32,7 +90,31 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
         float *stage = reinterpret_cast<float *>(smem) + wave * (32 * SP);
         const int rr0 = lane / LPR, col8 = (lane % LPR) * 8;
         const int n = n_base + wn * (BN / WN) + col8;
-        static_for<(TM + 1) / 2>([&](auto hc) {
+        constexpr int ROUNDS = (TM + 1) / 2;
+        const int m0 = m_base + wm * (BM / WM) + rr0;
+        // Everything the rounds read from global memory is fetched here, before their first store: a lane's 8 channels
+        // are the same in every pass, so the bias is read once, and the residual chunks of all passes are in flight
+        // together.  Loaded inside the passes, each read would queue behind the previous pass's store (loads and stores
+        // retire in issue order, and the compiler cannot move a load across a store that may alias it): sixteen
+        // dependent round trips on a 256 x 256 tile, about 10 us against 2 for the stores themselves.
+        float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        uint4 rq[ROUNDS][PASSES];
+        if constexpr (N8) {
+            if (p.bias && n < p.N) Pack<T, 8>::load(reinterpret_cast<const T *>(p.bias) + n, bv);
+            if (p.res) {
+                static_for<ROUNDS>([&](auto hc) {
+                    constexpr int h = decltype(hc)::value;
+                    constexpr int NBLK = (2 * h + 1 < TM) ? 2 : 1;
+                    static_for<PASSES>([&](auto pc) {
+                        constexpr int ps = decltype(pc)::value;
+                        const int rr = ps * RPP + rr0, m = m0 + h * 32 + ps * RPP;
+                        const bool ok = lane < RPP * LPR && rr < NBLK * 16 && m < p.M && n < p.N;
+                        rq[h][ps] = ok ? *reinterpret_cast<const uint4 *>(p.res + (long)m * p.ldy + n) : make_uint4(0u, 0u, 0u, 0u);
+                    });
+                });
+            }
+        }
+        static_for<ROUNDS>([&](auto hc) {
             constexpr int h = decltype(hc)::value;
             constexpr int NBLK = (2 * h + 1 < TM) ? 2 : 1;       // 16-row blocks in this round
             static_for<NBLK>([&](auto ic) {
@@ -45,23 +127,38 @@ __device__ __forceinline__ void tile_epilogue_impl(const GemmDev &p, f32x4 (&acc
             });
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_s_waitcnt(0xc07f);              // lgkmcnt(0): this wavefront's LDS writes have landed
-            auto pass = [&](int ps) {
-                const int rr = ps * RPP + rr0;
-                const int m = m_base + wm * (BM / WM) + h * 32 + rr;
-                if (lane < RPP * LPR && rr < NBLK * 16 && m < p.M && n < p.N) {
-                    const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
-                    const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
-                    float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-                    if constexpr (N8) epilogue_store8<T, ACT>(p.bias, p.res, p.y, p.y32, p.ldy, m, n, o);
-                    else epilogue_store8_ragged<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, p.ldy, m, n, o);
-                }
-            };
             if constexpr (N8) {
+                static_for<PASSES>([&](auto pc) {
+                    constexpr int ps = decltype(pc)::value;
+                    const int rr = ps * RPP + rr0, m = m0 + h * 32 + ps * RPP;
+                    if (lane < RPP * LPR && rr < NBLK * 16 && m < p.M && n < p.N) {
+                        const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
+                        const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
+                        float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
 #pragma unroll
-                for (int ps = 0; ps < PASSES; ++ps) pass(ps);
+                        for (int e = 0; e < 8; ++e) o[e] += bv[e];
+                        if (p.res) {
+                            const uint32_t w[4] = {rq[h][ps].x, rq[h][ps].y, rq[h][ps].z, rq[h][ps].w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                o[2 * e] += Cvt<T>::from_bits(w[e] & 0xffffu);
+                                o[2 * e + 1] += Cvt<T>::from_bits(w[e] >> 16);
+                            }
+                        }
+                        epilogue_store8<T, ACT>(nullptr, nullptr, p.y, p.y32, p.ldy, m, n, o);
+                    }
+                });
             } else {
 #pragma unroll 1
-                for (int ps = 0; ps < PASSES; ++ps) pass(ps);
+                for (int ps = 0; ps < PASSES; ++ps) {
+                    const int rr = ps * RPP + rr0, m = m0 + h * 32 + ps * RPP;
+                    if (lane < RPP * LPR && rr < NBLK * 16 && m < p.M && n < p.N) {
+                        const float4 q0 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8]);
+                        const float4 q1 = *reinterpret_cast<const float4 *>(&stage[rr * SP + col8 + 4]);
+                        const float o[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+                        epilogue_store8_ragged<T, ACT>(p.bias, p.res, p.y, p.y32, p.N, p.ldy, m, n, o);
+                    }
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_s_waitcnt(0xc07f);              // reads done before the next 32 rows overwrite the buffer

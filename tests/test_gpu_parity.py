@@ -187,7 +187,10 @@ def test_gap_and_classifier_share_a_launch(c, h, w, n, batch, act, then, dt):
 # ---------------- pooling, row kernels, element-wise, embedding ------------------------------------------------
 @pytest.mark.parametrize("dt", [wl.DT_F32] + DTS)
 def test_maxpool_and_gap(dt):
-    for k, s, p, c, h in [(3, 2, 1, 64, 29), (2, 2, 0, 24, 16), (3, 2, 1, 12, 9)]:
+    # 3x3 / 2 with vector-width channels takes the kernel with two outputs per thread: odd and even output heights,
+    # no padding with a clamped fifth row, a single output row
+    for k, s, p, c, h in [(3, 2, 1, 64, 29), (2, 2, 0, 24, 16), (3, 2, 1, 12, 9), (3, 2, 0, 16, 8), (3, 2, 1, 8, 8), (3, 2, 0, 8, 3),
+                          (3, 1, 1, 16, 7)]:
         m = wl.single_layer("maxpool", dt, c=c, h=h, w=h + 1, k=k, stride=s, pad=p)
         x = wl.make_input(m, 2)
         assert np.array_equal(run_gpu(m, x), orc.run_model(m, x))      # selection only: exact
