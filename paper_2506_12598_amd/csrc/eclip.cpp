@@ -1205,7 +1205,7 @@ extern "C" eclip_status eclip_model_kernel_info(const eclip_model *model, uint32
         out->workgroups = (uint32_t)((rows + per_wg - 1) / per_wg);
         break;
     }
-    case ECLIP_OP_ATTENTION: name = "attention_kernel"; break;
+    case ECLIP_OP_ATTENTION: name = (P.in.w + 31) / 32 * 32 > 256 ? "attention_chunk_kernel" : "attention_kernel"; break;   // see launch_attention
     case ECLIP_OP_EMBED: name = "embed_kernel"; break;
     case ECLIP_OP_ELTWISE: name = "eltwise_kernel"; break;
     case ECLIP_OP_CONCAT:

@@ -242,7 +242,11 @@ def test_eltwise_and_embed(dt):
                                                     (512, 64, 1, 1),
                                                     # beyond 256 keys the keys are staged in LDS: 128 queries per workgroup when
                                                     # there are enough (batch, head) pairs, head size 32, a ragged length
-                                                    (384, 1024, 16, 3), (300, 128, 4, 2)])
+                                                    (384, 1024, 16, 3), (300, 128, 4, 2),
+                                                    # two chunks of keys with a running maximum: the second chunk almost
+                                                    # all padding, 512 keys (16 blocks per chunk) on 128-query workgroups,
+                                                    # head size 32 on 128-query workgroups
+                                                    (257, 128, 2, 1), (512, 1024, 16, 2), (384, 512, 16, 2)])
 def test_attention(seq, hidden, heads, batch, dt):
     m = wl.single_layer("attention", dt, seed=seq, seq=seq, hidden=hidden, heads=heads)
     check(m, batch=batch, tol=6e-3)
