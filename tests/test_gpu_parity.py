@@ -194,6 +194,8 @@ def test_maxpool_and_gap(dt):
         m = wl.single_layer("maxpool", dt, c=c, h=h, w=h + 1, k=k, stride=s, pad=p)
         x = wl.make_input(m, 2)
         assert np.array_equal(run_gpu(m, x), orc.run_model(m, x))      # selection only: exact
+        paired = k == 3 and s == 2 and c % (4 if dt == wl.DT_F32 else 8) == 0
+        assert _kernel_of_single_layer(m) == ("maxpool3s2_block_kernel" if paired else "maxpool_kernel")
     for c, h in [(512, 7), (40, 5), (1280, 3)]:
         m = wl.single_layer("gap", dt, c=c, h=h, w=h)
         check(m, batch=3, tol=1e-5)
@@ -250,6 +252,7 @@ def test_eltwise_and_embed(dt):
 def test_attention(seq, hidden, heads, batch, dt):
     m = wl.single_layer("attention", dt, seed=seq, seq=seq, hidden=hidden, heads=heads)
     check(m, batch=batch, tol=6e-3)
+    assert _kernel_of_single_layer(m) == ("attention_chunk_kernel" if seq > 256 else "attention_kernel")
 
 
 def test_attention_equal_keys_gives_mean_of_values():
