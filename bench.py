@@ -373,7 +373,9 @@ def stats_from(trace_csv):
         for fn, a in sorted(acc.items(), key=lambda kv: -kv[1][2]):
             print(f"{fn:28s} {a[0]:9d} {a[0] - a[1]:9d} {a[2] / a[1]:9.2f} {a[3] / a[0]:10.2f} {100.0 * a[2] / tot:8.2f}")
 
-    table(range(len(rows)), "all dispatches of the process (outliers: beyond 8x the median of their tile shape and grid, left out of the mean)")
+    # the marker kernel itself is left out: its dispatches follow idle queues, so their start stamps are the artefact above
+    table([i for i in range(len(rows)) if rows[i][2] != "probe_kernel"],
+          "all dispatches of the process (outliers: beyond 8x the median of their tile shape and grid, left out of the mean)")
     if len(marks) >= 2:
         table(range(marks[-2] + 1, marks[-1]), "per-layer timing pass (each layer 8 times back to back, alone on the GPU)")
 
