@@ -255,6 +255,29 @@ def test_attention(seq, hidden, heads, batch, dt):
     assert _kernel_of_single_layer(m) == ("attention_chunk_kernel" if seq > 256 else "attention_kernel")
 
 
+@pytest.mark.parametrize("dt", DTS)
+@pytest.mark.parametrize("seq", [384, 300])
+def test_attention_peaked_scores_across_key_chunks(seq, dt):
+    """Beyond 256 keys the keys are taken in two chunks with a running maximum.  Inputs four times the usual size make
+    the scores 16 times larger, so that most of a row's weight sits on a few keys; queries and keys of the second
+    half are given a common offset in the first half, and of the first half in the second, so that for half of the
+    rows the maximum lies in the first chunk and for the other half in the second (the rescaling between chunks then
+    runs in both directions)."""
+    hidden, heads = 128, 2
+    m = wl.single_layer("attention", dt, seed=seq + 1, seq=seq, hidden=hidden, heads=heads)
+    x = wl.make_input(m, 2) * 4.0
+    half = seq // 2
+    x[:, :half, :hidden] += 1.5
+    x[:, half:, hidden:2 * hidden] += 1.5
+    x[:, half:, :hidden] -= 1.5
+    x[:, :half, hidden:2 * hidden] -= 1.5
+    x = wl.round_to_dtype(x.astype(np.float32), dt)
+    exp = orc.run_model(m, x)
+    got = run_gpu(m, x)
+    assert np.isfinite(got).all()
+    assert rel_to_range(got, exp) <= 6e-3
+
+
 def test_attention_equal_keys_gives_mean_of_values():
     m = wl.single_layer("attention", wl.DT_F16, seq=40, hidden=64, heads=2)
     x = wl.make_input(m, 1)
