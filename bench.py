@@ -64,6 +64,9 @@ class PowerSampler:
     def __init__(self, hz: float = 20.0):
         self.paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average")) or \
             sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        # the shader clock the GPU is running at: the level marked "*" in the amdgpu DPM table
+        self.clk_paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+        self.clocks = []
         self.dt = 1.0 / hz
         self.samples = []
         self.source = "hwmon" if self.paths else "amd-smi"
@@ -86,15 +89,30 @@ class PowerSampler:
         except Exception:   # noqa: BLE001
             return None
 
+    def read_clock_mhz(self):
+        try:
+            cur = [l for l in open(self.clk_paths[0]).read().splitlines() if "*" in l][0]
+            return float(cur.split(":")[1].lower().split("mhz")[0])
+        except (OSError, ValueError, IndexError):
+            return None
+
     def _run(self):
         while not self._stop.is_set():
             v = self.read()
             if v is not None:
                 self.samples.append((time.perf_counter(), v))
+            c = self.read_clock_mhz()
+            if c is not None:
+                self.clocks.append((time.perf_counter(), c))
             self._stop.wait(self.dt)
+
+    def mean_clock_mhz(self, t0, t1):
+        c = [v for t, v in self.clocks if t0 <= t <= t1]
+        return float(np.mean(c)) if c else None
 
     def start(self):
         self.samples = []
+        self.clocks = []
         self._stop.clear()
         self._th = threading.Thread(target=self._run, daemon=True)
         self._th.start()
@@ -1037,7 +1055,7 @@ def main():
         for pol in ("unpart_a", "unpart_b", "eclip"):
             set_policy(pol)
             n_pol = max(1, int(n_e * ms_per_step / closed[pol]["ms_per_step"]))
-            vals, watts = [], []
+            vals, watts, mhz = [], [], []
             for _ in range(args.energy_repeats):
                 sampler.start()
                 time.sleep(0.1)
@@ -1050,11 +1068,16 @@ def main():
                 if e:
                     vals.append(served / e)
                     watts.append(e / (t_b - t_a))
+                    c = sampler.mean_clock_mhz(t_a, t_b)
+                    if c:
+                        mhz.append(c)
             if vals:
                 closed[pol].update({"inferences_per_joule": float(np.mean(vals)), "inferences_per_joule_min": float(min(vals)),
                                     "inferences_per_joule_max": float(max(vals)), "avg_power_w": float(np.mean(watts)),
-                                    "energy_windows": len(vals), "energy_window_s": float(n_pol * closed[pol]["ms_per_step"] / 1e3)})
-                log(f"closed loop {pol}: {np.mean(vals):.4f} inf/J (min {min(vals):.4f}, max {max(vals):.4f}) at {np.mean(watts):.0f} W")
+                                    "energy_windows": len(vals), "energy_window_s": float(n_pol * closed[pol]["ms_per_step"] / 1e3),
+                                    "avg_sclk_mhz": float(np.mean(mhz)) if mhz else None})
+                log(f"closed loop {pol}: {np.mean(vals):.4f} inf/J (min {min(vals):.4f}, max {max(vals):.4f}) at {np.mean(watts):.0f} W"
+                    + (f", shader clock {np.mean(mhz):.0f} MHz" if mhz else ""))
 
     # ---- open loop: Poisson arrivals, p99 latency, energy
     open_res = {}
