@@ -1115,6 +1115,19 @@ def main():
     for wk in workers:
         wk.h.graphs(False)
     roofline = measure_roofline(pool)
+    # ... and every worker on the CU share it is served on: its request's solo latency there (sum over its kernel groups
+    # of the profiled latency table, Sec. III-B factor (i)) against the matrix peak scaled by that share.  Whole requests,
+    # every kernel and launch gap included -- context for `frac`, which is one kernel on all CUs.
+    served_share = []
+    for w, wk in enumerate(workers):
+        t_ns = sum(beta[w][g][assign[w][g]] for g in range(wk.model.n_groups))
+        cu_ns = sum(beta[w][g][assign[w][g]] * configs[assign[w][g]] for g in range(wk.model.n_groups))
+        fl = sum(x[1] for x in gemm_work(wk.model, prof_batch[w]) if x is not None)
+        fl += sum(4.0 * prof_batch[w] * L.w * L.w * L.c for L in wk.model.layers if L.op == wl.OP_ATTENTION)     # 4 B h S^2 d, h d = c
+        cus_w = cu_ns / max(t_ns, 1)
+        served_share.append({"worker": w, "model": wk.model.name, "batch": prof_batch[w], "cus": round(cus_w, 1), "solo_request_us": t_ns / 1e3,
+                             "tflops": fl / max(t_ns, 1) / 1e3, "frac_of_scaled_peak": fl / max(t_ns, 1) / 1e3 / (MFMA_PEAK_TFLOPS * cus_w / 256.0)})
+    roofline["served_share"] = served_share
 
     # ---- CPU oracle on the host cores, same models and inputs: one full forward pass per worker on the batch of its
     # last timed request.  The passes are the parity check of every worker's output (in the launch configuration that
