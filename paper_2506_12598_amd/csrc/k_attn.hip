@@ -149,26 +149,23 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float c2 = p.scale * 1.4426950408889634f, off2 = -mx * c2;
     float sum = 0.0f;
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-        if (kb < nkb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float e = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], c2, off2));      // exp2(-inf) = 0 for padded keys
-                sc[kb][r] = e;
-                sum += e;
-            }
-    sum += __shfl_xor(sum, 16, 64);
-    sum += __shfl_xor(sum, 32, 64);
-    const float inv = 1.0f / sum;
 
-    // ---- out^T[j][query] = sum_key V^T[j][key] * P[query][key]
+    // ---- out^T[j][query] = sum_key V^T[j][key] * P[query][key], the exponentials taken pair of key blocks by pair of key
+    // blocks so that vector-ALU work and the LDS reads and matrix instructions of the product alternate
     f32x4 o[D / 16];
 #pragma unroll
     for (int jb = 0; jb < D / 16; ++jb) o[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kp2 = 0; kp2 < KB / 2; ++kp2) {
         if (2 * kp2 < nkb) {
+#pragma unroll
+            for (int kb = 2 * kp2; kb < 2 * kp2 + 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float e = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], c2, off2));      // exp2(-inf) = 0 for padded keys
+                    sc[kb][r] = e;
+                    sum += e;
+                }
             // contraction slot e of lane group g  <->  key (2*kp2 + e/4)*16 + 4*g + e%4
             uint4 pf;
             pf.x = Cvt<T>::pack2(sc[2 * kp2][0], sc[2 * kp2][1]);
@@ -185,6 +182,9 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnDev p)
         }
     }
 
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.0f / sum;
     // lane holds head dims jb*16 + 4*g .. +3 of its query
 #pragma unroll
     for (int jb = 0; jb < D / 16; ++jb)
@@ -332,25 +332,26 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 && KBC <= 12) ? 4 : 2) void atten
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
         m_run = m_new;
         const float off2 = -m_new * c2;
-        float part = 0.0f;
-#pragma unroll
-        for (int kb = 0; kb < KBC; ++kb)
-            if (kb < nkb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float e = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], c2, off2));
-                    sc[kb][r] = e;
-                    part += e;
-                }
-        sum = fmaf(sum, alpha, part);
 #pragma unroll
         for (int jb = 0; jb < D / 16; ++jb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) o[jb][r] *= alpha;
 
+        // exponentials and P.V pair of key blocks by pair of key blocks, so that the vector ALU (8 exp2 per pair) and the
+        // LDS reads and matrix instructions of the product alternate in every wavefront's instruction stream instead of
+        // forming two long phases that all wavefronts of the workgroup enter together
+        float part = 0.0f;
 #pragma unroll
         for (int kp2 = 0; kp2 < KBC / 2; ++kp2) {
             if (2 * kp2 < nkb) {
+#pragma unroll
+                for (int kb = 2 * kp2; kb < 2 * kp2 + 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float e = __builtin_amdgcn_exp2f(fmaf(sc[kb][r], c2, off2));
+                        sc[kb][r] = e;
+                        part += e;
+                    }
                 uint4 pf;
                 pf.x = Cvt<T>::pack2(sc[2 * kp2][0], sc[2 * kp2][1]);
                 pf.y = Cvt<T>::pack2(sc[2 * kp2][2], sc[2 * kp2][3]);
@@ -365,6 +366,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 && KBC <= 12) ? 4 : 2) void atten
                 }
             }
         }
+        sum = fmaf(sum, alpha, part);
     }
     sum += __shfl_xor(sum, 16, 64);
     sum += __shfl_xor(sum, 32, 64);
