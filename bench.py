@@ -471,7 +471,16 @@ def kernels_mode(only=None, extra_gemms=None, tune=True, cus=256):
         nbytes = 2 * (8 * 25088 + 4096 * 25088 + 8 * 4096)
         rows.append(("VGG FC1 b8: linear M8 N4096 K25088 (weight streaming)", info["kernel"], "hbm", nbytes / ns, HBM_PEAK_GBS, "GB/s", ns / 1e3))
 
-    cases = [("layernorm", c_ln), ("softmax", c_sm), ("maxpool", c_mp), ("dwconv", c_dw), ("gap", c_gap), ("gelu", c_gelu),
+    def c_attn(batch):
+        # fused attention of BERT-large (16 heads of 64, 384 keys): 4 B S Hd elements move, 4 B S^2 Hd flops -- S / 2 = 192
+        # flop per byte, below the ridge, so the row is held against the memory roofline
+        bb = G._Builder("attn", B, 0, G.IN_SEQ, 3 * 1024, 1, 384); x = bb.attention(-1, 16); bb.eltwise(x)
+        ns, info = time_first(bb.finish(), batch)
+        nbytes = 2.0 * 4 * batch * 384 * 1024
+        rows.append((f"attention 16 x 64, 384 keys, batch {batch} ({4.0 * batch * 384 * 384 * 1024 / ns / 1e3:.0f} TFLOP/s)", info["kernel"], "hbm",
+                     nbytes / ns, HBM_PEAK_GBS, "GB/s", ns / 1e3))
+
+    cases = [("attention", lambda: c_attn(256)), ("attention_b4", lambda: c_attn(4)), ("layernorm", c_ln), ("softmax", c_sm), ("maxpool", c_mp), ("dwconv", c_dw), ("gap", c_gap), ("gelu", c_gelu),
              ("copy", c_copy), ("fc", c_fc),
              ("gemm8192", lambda: gemm("linear", 8192, 8192, 8192)), ("gemm4096", lambda: gemm("linear", 4096, 4096, 4096)),
              ("ffn1", lambda: gemm("BERT-large FFN1 b4", 1536, 1024, 4096)), ("ffn2", lambda: gemm("BERT-large FFN2 b4", 1536, 4096, 1024)),
